@@ -1,0 +1,80 @@
+"""Model segmentation: cut the unit list into N contiguous components of near-equal compute.
+
+Section 3.2 asks for components of comparable computational load so that the slowest one,
+which sets the cost of a parallel step (Eq. 7), is as small as possible; Appendix A
+("Model Segmentation") says the split is sequential.  Reading used here: cost = exact
+integer FLOPs (2 per multiply-accumulate) of the convolutions, linear layers and attention
+matmuls of a unit; minimise the maximum component cost over all contiguous cuts; among
+optimal cuts take the lexicographically smallest vector of cut positions.
+"""
+from typing import List
+
+from .unet import UNetConfig, Unit, build_units
+
+
+def unit_flops(cfg: UNetConfig, u: Unit) -> int:
+    b = cfg.batch
+    conv = lambda ci, co, k, ho, wo: 2 * b * ho * wo * co * ci * k * k
+    if u.kind in ("conv_in", "down", "up", "out"):
+        return conv(u.c_in, u.c_out, 3, u.h_out, u.w_out)
+    if u.kind == "res":
+        ci = u.c_in + u.c_skip
+        f = conv(ci, u.c_out, 3, u.h_out, u.w_out) + conv(u.c_out, u.c_out, 3, u.h_out, u.w_out)
+        f += 2 * b * cfg.temb_dim * u.c_out
+        if ci != u.c_out:
+            f += conv(ci, u.c_out, 1, u.h_out, u.w_out)
+        return f
+    if u.kind == "tfm":
+        c, l, lk = u.c_in, u.h_in * u.w_in, cfg.ctx_len
+        lin = 2 * b * l * c * c
+        f = 2 * lin                                   # proj_in, proj_out
+        per = 4 * lin + 4 * b * l * l * c             # self: q,k,v,o + QK^T and PV over all heads
+        per += 2 * lin + 2 * (2 * b * lk * c * cfg.ctx_dim) + 4 * b * l * lk * c   # cross
+        per += 24 * b * l * c * c                     # GEGLU: C->8C and 4C->C
+        return f + u.depth * per
+    raise ValueError(u.kind)
+
+
+def unit_score_flops(cfg: UNetConfig, u: Unit) -> int:
+    """The part of unit_flops spent in QK^T and PV (module-level MAC counters leave it out)."""
+    if u.kind != "tfm":
+        return 0
+    c, l = u.c_in, u.h_in * u.w_in
+    return u.depth * (4 * cfg.batch * l * l * c + 4 * cfg.batch * l * cfg.ctx_len * c)
+
+
+def partition(costs: List[int], n: int) -> List[int]:
+    """Return the N-1 cut positions (component k ends before cuts[k]); minimax, then lexicographic."""
+    m = len(costs)
+    assert 1 <= n <= m
+    pre = [0]
+    for c in costs:
+        pre.append(pre[-1] + c)
+    seg = lambda a, b: pre[b] - pre[a]               # units a..b-1
+    inf = float("inf")
+    # best[k][i] = minimal max-load splitting units i..m-1 into k parts
+    best = [[inf] * (m + 1) for _ in range(n + 1)]
+    best[0][m] = 0
+    for k in range(1, n + 1):
+        for i in range(m - k, -1, -1):
+            v = inf
+            for e in range(i + 1, m - (k - 1) + 1):
+                v = min(v, max(seg(i, e), best[k - 1][e]))
+            best[k][i] = v
+    opt = best[n][0]
+    cuts, i = [], 0
+    for k in range(n, 1, -1):
+        for e in range(i + 1, m - (k - 1) + 1):
+            if seg(i, e) <= opt and best[k - 1][e] <= opt:
+                cuts.append(e)
+                i = e
+                break
+    return cuts
+
+
+def component_ranges(cfg: UNetConfig, n: int):
+    """[(first_unit, last_unit)] for the N components."""
+    units = build_units(cfg)
+    cuts = partition([unit_flops(cfg, u) for u in units], n)
+    edges = [0] + cuts + [len(units)]
+    return [(edges[k], edges[k + 1] - 1) for k in range(n)]

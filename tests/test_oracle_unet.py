@@ -1,0 +1,206 @@
+"""Pins for oracle/unet.py and oracle/partition.py.
+
+What fixes the UNet here is public knowledge about the SD-shaped networks the paper runs
+(Section 4.1) and the MAC totals it prints in Table 1.
+"""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+
+import synthetic_inputs as SI
+from configs import CONFIGS
+from oracle import primitives as P
+from oracle.partition import component_ranges, partition, unit_flops, unit_score_flops
+from oracle.unet import UNetConfig, build_units, component_io, run_units, unet_forward, weight_manifest, run_unit
+
+GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.json")))
+
+
+def n_params(cfg):
+    return sum(int(np.prod(s)) for _, s in weight_manifest(cfg))
+
+
+def test_topology_counts():
+    cfg = UNetConfig(**CONFIGS["sd21_768"])
+    units = build_units(cfg)
+    assert len(units) == 46
+    assert sum(u.skip_from >= 0 for u in units) == 12
+    assert sorted(u.skip_from for u in units if u.skip_from >= 0) == sorted(set(u.skip_from for u in units if u.skip_from >= 0))
+    # skips are consumed last-in first-out with matching resolution
+    for u in units:
+        if u.skip_from >= 0:
+            s = units[u.skip_from]
+            assert (s.h_out, s.w_out) == (u.h_in, u.w_in) and s.c_out == u.c_skip
+    assert [u.kind for u in units[:6]] == ["conv_in", "res", "tfm", "res", "tfm", "down"]
+    assert units[-1].kind == "out" and units[-1].c_out == 4
+    tiny = build_units(UNetConfig(**CONFIGS["tiny"]))
+    assert [u.name for u in tiny] == ["conv_in", "d0.0.res", "d0.ds", "d1.0.res", "mid.res0", "mid.tfm", "mid.res1",
+                                      "u1.0.res", "u1.1.res", "u1.us", "u0.0.res", "u0.1.res", "out"]
+
+
+def test_parameter_counts_match_public_sd_unets():
+    # Stable Diffusion 2.1 UNet: 865,910,724 parameters; SD 1.5 (text width 768): 859,520,964.
+    assert n_params(UNetConfig(**CONFIGS["sd21_768"])) == 865_910_724
+    c15 = dict(CONFIGS["sd_512"], ctx_dim=768)
+    assert n_params(UNetConfig(**c15)) == 859_520_964
+
+
+def macs_T(cfg, steps=50):
+    units = build_units(cfg)
+    return steps * sum(unit_flops(cfg, u) - unit_score_flops(cfg, u) for u in units) / 2 / 1e12
+
+
+def test_mac_totals_match_table_1():
+    g = GOLD["macs_totals"]
+    assert round(macs_T(UNetConfig(**CONFIGS["sd21_768"]))) == g["sd21_768"]
+    assert round(macs_T(UNetConfig(**dict(CONFIGS["sd_512"], ctx_dim=768)))) == g["sd15_512"]
+    assert round(macs_T(UNetConfig(**CONFIGS["sdxl_1024"]))) == g["sdxl_1024"]
+
+
+def test_macs_per_device_match_table_1():
+    # each of the N*S device-slots does total/(N*S) (Table 1, SD 2.1, MACs column, to the printed precision)
+    g = GOLD["macs_per_device_sd21"]
+    total = macs_T(UNetConfig(**CONFIGS["sd21_768"]))
+    for key in ("N2_S1", "N3_S1", "N4_S1", "N2_S2", "N3_S2"):
+        n, s = int(key[1]), int(key[4])
+        assert abs(total / (n * s) - g[key]) <= 0.51
+
+
+def test_partition_matches_brute_force():
+    rng = np.random.default_rng(3)
+    for trial in range(40):
+        m = int(rng.integers(3, 11))
+        n = int(rng.integers(1, min(m, 5) + 1))
+        costs = [int(c) for c in rng.integers(1, 30, m)]
+        if trial % 5 == 0:
+            costs = [5] * m                       # many ties
+        best = None
+        for cuts in itertools.combinations(range(1, m), n - 1):
+            e = [0] + list(cuts) + [m]
+            load = max(sum(costs[e[k]:e[k + 1]]) for k in range(n))
+            key = (load, list(cuts))
+            if best is None or key < best:
+                best = key
+        assert partition(costs, n) == best[1]
+
+
+def test_partition_of_real_configs_brute_force():
+    for name, n in (("tiny", 2), ("tiny", 3), ("sd21_768", 2), ("sd21_768", 3)):
+        cfg = UNetConfig(**CONFIGS[name])
+        units = build_units(cfg)
+        costs = [unit_flops(cfg, u) for u in units]
+        best = min((max(sum(costs[a:b]) for a, b in zip([0] + list(c), list(c) + [len(costs)])), list(c))
+                   for c in itertools.combinations(range(1, len(costs)), n - 1))
+        assert partition(costs, n) == best[1]
+    cfg = UNetConfig(**CONFIGS["sd21_768"])
+    loads = [sum(unit_flops(cfg, u) for u in build_units(cfg)[a:b + 1]) for a, b in component_ranges(cfg, 4)]
+    assert max(loads) / sum(loads) < 0.26        # "comparable computational load" (Section 3.2)
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    cfg = UNetConfig(**CONFIGS["tiny"])
+    wts = {k: v.astype(np.float64) for k, v in SI.make_weights(weight_manifest(cfg), std=0.2).items()}
+    x = SI.make_latent(4, 16, 16).astype(np.float64)[None]
+    ctx = SI.make_text(1, 8, 32).astype(np.float64)
+    return cfg, wts, x, ctx
+
+
+def test_components_compose_to_the_whole_model(tiny):
+    cfg, wts, x, ctx = tiny
+    units = build_units(cfg)
+    whole = unet_forward(cfg, wts, x, 500, ctx)
+    for n in (2, 3, 4):
+        avail = {-1: x}
+        for a, b in component_ranges(cfg, n):
+            ins, outs = component_io(units, a, b)
+            out = run_units(cfg, units, a, b, wts, {i: avail[i] for i in ins}, 500, ctx)
+            assert sorted(out) == outs
+            avail.update(out)
+        np.testing.assert_array_equal(avail[len(units) - 1], whole)     # Eq. 4: cascade == model
+
+
+def test_component_io_brute_force(tiny):
+    cfg = tiny[0]
+    units = build_units(UNetConfig(**CONFIGS["sd21_768"]))
+    for a, b in [(0, 9), (10, 24), (25, 36), (37, 45), (5, 5), (0, 45)]:
+        ins, outs = component_io(units, a, b)
+        reads = {a - 1} | {u.skip_from for u in units[a:b + 1] if 0 <= u.skip_from < a}
+        later = {b} | {u.skip_from for u in units[b + 1:] if a <= u.skip_from <= b}
+        assert ins == sorted(reads) and outs == sorted(later)
+
+
+def test_zero_weight_special_cases(tiny):
+    cfg, wts, x, ctx = tiny
+    units = build_units(cfg)
+    z = {k: (np.zeros_like(v) if not k.endswith(".g") else v) for k, v in wts.items()}
+    temb = np.zeros((1, cfg.temb_dim))
+    h = np.random.default_rng(0).standard_normal((1, 64, 8, 8))
+    # residual structure: blocks with zeroed weights are the identity
+    np.testing.assert_array_equal(run_unit(cfg, units, 4, z, h, None, temb, ctx), h)      # mid.res0
+    np.testing.assert_array_equal(run_unit(cfg, units, 5, z, h, None, temb, ctx), h)      # mid.tfm
+    # only the last conv bias set: res(x) = x + bias
+    z2 = dict(z); z2["mid.res0.conv2.b"] = wts["mid.res0.conv2.b"]
+    np.testing.assert_allclose(run_unit(cfg, units, 4, z2, h, None, temb, ctx),
+                               h + wts["mid.res0.conv2.b"][None, :, None, None], atol=1e-15)
+    # time-embedding path: conv2 = delta kernel, gn2 turned into identity is not available, so check
+    # linearity instead: doubling (temb weight, bias) doubles the pre-norm offset -> output unchanged
+    # when the offset is constant per channel and the group is one channel wide.
+    # transformer with zero attention/ff output weights but proj_in/out set: x + proj_out(proj_in(GN(x)))
+    z3 = dict(z)
+    for k in ("mid.tfm.proj_in.w", "mid.tfm.proj_in.b", "mid.tfm.proj_out.w", "mid.tfm.proj_out.b"):
+        z3[k] = wts[k]
+    g = P.group_norm(h, cfg.gn_groups, wts["mid.tfm.gn.g"], wts["mid.tfm.gn.b"], cfg.gn_eps)
+    t = g.reshape(1, 64, 64).transpose(0, 2, 1)
+    t = P.linear(P.linear(t, wts["mid.tfm.proj_in.w"], wts["mid.tfm.proj_in.b"]), wts["mid.tfm.proj_out.w"], wts["mid.tfm.proj_out.b"])
+    np.testing.assert_allclose(run_unit(cfg, units, 5, z3, h, None, temb, ctx),
+                               h + t.transpose(0, 2, 1).reshape(1, 64, 8, 8), atol=1e-13)
+
+
+def test_blocks_against_torch_modules(tiny):
+    """Independent restatement with torch.nn.functional in NCHW, fp64 (consistency check, not the only pin)."""
+    import torch
+    import torch.nn.functional as TF
+    cfg, wts, x, ctx = tiny
+    units = build_units(cfg)
+    T = lambda k: torch.from_numpy(np.ascontiguousarray(wts[k]))
+    temb_np = np.random.default_rng(1).standard_normal((1, cfg.temb_dim))
+    # up-path ResBlock with concat and 1x1 shortcut: u1.0.res (unit 7): 64 + 64 -> 64
+    u = units[7]
+    h = np.random.default_rng(2).standard_normal((1, 64, 8, 8)); s = np.random.default_rng(3).standard_normal((1, 64, 8, 8))
+    n = u.name
+    xin = torch.cat([torch.from_numpy(h), torch.from_numpy(s)], 1)
+    a = TF.conv2d(TF.silu(TF.group_norm(xin, 8, T(f"{n}.gn1.g"), T(f"{n}.gn1.b"), 1e-5)), T(f"{n}.conv1.w"), T(f"{n}.conv1.b"), padding=1)
+    a = a + TF.linear(TF.silu(torch.from_numpy(temb_np)), T(f"{n}.temb.w"), T(f"{n}.temb.b"))[:, :, None, None]
+    a = TF.conv2d(TF.silu(TF.group_norm(a, 8, T(f"{n}.gn2.g"), T(f"{n}.gn2.b"), 1e-5)), T(f"{n}.conv2.w"), T(f"{n}.conv2.b"), padding=1)
+    ref = TF.conv2d(xin, T(f"{n}.short.w"), T(f"{n}.short.b")) + a
+    np.testing.assert_allclose(run_unit(cfg, units, 7, wts, h, s, temb_np, ctx), ref.numpy(), rtol=1e-10, atol=1e-11)
+    # transformer
+    n = "mid.tfm"
+    xt = torch.from_numpy(h)
+    t = TF.group_norm(xt, 8, T(f"{n}.gn.g"), T(f"{n}.gn.b"), 1e-5).flatten(2).transpose(1, 2)
+    t = TF.linear(t, T(f"{n}.proj_in.w"), T(f"{n}.proj_in.b"))
+    heads = 4
+    def mha(q, k, v):
+        sp = lambda z: z.reshape(1, -1, heads, 16).transpose(1, 2)
+        return TF.scaled_dot_product_attention(sp(q), sp(k), sp(v)).transpose(1, 2).reshape(1, -1, 64)
+    p = f"{n}.0"
+    c = torch.from_numpy(ctx)
+    y = TF.layer_norm(t, (64,), T(f"{p}.ln1.g"), T(f"{p}.ln1.b"), 1e-5)
+    t = t + TF.linear(mha(TF.linear(y, T(f"{p}.attn1.q.w")), TF.linear(y, T(f"{p}.attn1.k.w")), TF.linear(y, T(f"{p}.attn1.v.w"))), T(f"{p}.attn1.o.w"), T(f"{p}.attn1.o.b"))
+    y = TF.layer_norm(t, (64,), T(f"{p}.ln2.g"), T(f"{p}.ln2.b"), 1e-5)
+    t = t + TF.linear(mha(TF.linear(y, T(f"{p}.attn2.q.w")), TF.linear(c, T(f"{p}.attn2.k.w")), TF.linear(c, T(f"{p}.attn2.v.w"))), T(f"{p}.attn2.o.w"), T(f"{p}.attn2.o.b"))
+    y = TF.layer_norm(t, (64,), T(f"{p}.ln3.g"), T(f"{p}.ln3.b"), 1e-5)
+    f = TF.linear(y, T(f"{p}.ff1.w"), T(f"{p}.ff1.b"))
+    t = t + TF.linear(f[..., :256] * TF.gelu(f[..., 256:]), T(f"{p}.ff2.w"), T(f"{p}.ff2.b"))
+    t = TF.linear(t, T(f"{n}.proj_out.w"), T(f"{n}.proj_out.b"))
+    ref = xt + t.transpose(1, 2).reshape(1, 64, 8, 8)
+    np.testing.assert_allclose(run_unit(cfg, units, 5, wts, h, None, temb_np, ctx), ref.numpy(), rtol=1e-10, atol=1e-11)
+    # down / up
+    np.testing.assert_allclose(run_unit(cfg, units, 2, wts, np.asarray(TF.pad(torch.from_numpy(h[:, :32]), (0, 0, 0, 0))), None, temb_np, ctx),
+                               TF.conv2d(torch.from_numpy(h[:, :32]), T("d0.ds.conv.w"), T("d0.ds.conv.b"), stride=2, padding=1).numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(run_unit(cfg, units, 9, wts, h, None, temb_np, ctx),
+                               TF.conv2d(TF.interpolate(xt, scale_factor=2, mode="nearest"), T("u1.us.conv.w"), T("u1.us.conv.b"), padding=1).numpy(), rtol=1e-10, atol=1e-12)
