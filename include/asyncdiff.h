@@ -1,0 +1,233 @@
+/*
+ * asyncdiff.h - C ABI of the MI355X (gfx950) asynchronous-denoising library.
+ *
+ * The library runs the noise-prediction UNet of a latent diffusion model cut into N
+ * sequential components (AsyncDiff, arXiv 2406.06911, Section 3.2, Eq. 4), under the paper's
+ * asynchronous schedule: w sequential warm-up steps, then component n of a step consumes what
+ * component n-1 (and every other producer of its skip features) stored in the previous
+ * parallel round (Section 3.2 "Asynchronous Denoising", Eq. 5, "Multi-Device Communication"),
+ * optionally with stride denoising (Section 3.2 "Stride Denoising", Appendix A) and time
+ * shifting (Appendix A), followed by the sampler update S(x_t, eps_t, t) (Section 3.1, Eq. 3).
+ * The paper spreads the components over GPUs; here one GPU runs them concurrently on the
+ * HIP streams the caller passes.
+ *
+ * Conventions
+ *   - Every pointer argument says whether it is HOST or DEVICE memory.  The library never
+ *     allocates device memory: the caller allocates the two arenas whose sizes
+ *     ad_device_bytes() reports and hands them over with ad_bind_device_memory().
+ *   - Hidden states are DEVICE tensors in NHWC order [batch][H][W][C], element type = cfg.dtype.
+ *     The latent is DEVICE fp32 [latent_channels][H][W] (one image; the batch rows of
+ *     classifier-free guidance share it).  The noise prediction is DEVICE fp32
+ *     [batch][latent_channels][H][W].  The text embedding is DEVICE, element type = cfg.dtype,
+ *     [batch][ctx_len][ctx_dim]; the pooled embedding DEVICE fp32 [batch][pooled_dim].
+ *   - Steps are numbered i = 0..T-1 in execution order; tau_i is the training timestep of step i.
+ *   - Calls that take a stream only enqueue work; they never synchronise.
+ *   - Every call returns an ad_status; no exception crosses the boundary.  ad_last_error()
+ *     returns a HOST string describing the last failure on the calling thread.
+ *   - A context is not thread-safe; use one per host thread or serialise calls.
+ */
+#ifndef ASYNCDIFF_H
+#define ASYNCDIFF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ad_status {
+  AD_OK = 0,
+  AD_ERR_INVALID = 1, /* bad argument or configuration */
+  AD_ERR_NOMEM = 2,   /* bound arenas too small / host allocation failed */
+  AD_ERR_HIP = 3,     /* a HIP runtime call failed */
+  AD_ERR_DONE = 4,    /* ad_step called after the last step */
+  AD_ERR_STATE = 5    /* call order violated (e.g. forward before weights are loaded) */
+} ad_status;
+
+typedef enum ad_dtype { AD_F32 = 0, AD_BF16 = 1 } ad_dtype;
+typedef enum ad_sampler_kind { AD_DDIM = 0, AD_EULER = 1 } ad_sampler_kind;
+typedef enum ad_beta_kind { AD_BETA_LINEAR = 0, AD_BETA_SCALED_LINEAR = 1 } ad_beta_kind;
+typedef enum ad_unit_kind {
+  AD_UNIT_CONV_IN = 0, AD_UNIT_RES = 1, AD_UNIT_TFM = 2, AD_UNIT_DOWN = 3, AD_UNIT_UP = 4, AD_UNIT_OUT = 5
+} ad_unit_kind;
+
+#define AD_MAX_LEVELS 4
+#define AD_NAME_LEN 64
+
+/* Shape of the UNet.  The paper uses the denoiser as a black box (Section 4.1); this struct
+ * describes the Stable-Diffusion-shaped family it is evaluated on. */
+typedef struct ad_unet_cfg {
+  int latent_channels;                  /* 4 */
+  int height, width;                    /* latent size */
+  int batch;                            /* 2 with classifier-free guidance, else 1 */
+  int n_levels;                         /* <= AD_MAX_LEVELS */
+  int channels[AD_MAX_LEVELS];          /* per level; multiples of 32 (fp32) / 64 (bf16) */
+  int layers_per_block;                 /* ResBlocks per down level (up levels have one more) */
+  int transformer_depth[AD_MAX_LEVELS]; /* transformer layers after each ResBlock of the level; 0 = none */
+  int mid_depth;                        /* transformer layers in the middle block; 0 = none */
+  int head_dim;                         /* attention head width; channels[l] % head_dim == 0 */
+  int gn_groups;
+  int ctx_len, ctx_dim;                 /* text embedding */
+  int pooled_dim;                       /* 0 = no pooled-embedding branch */
+  float gn_eps, ln_eps;
+  int dtype;                            /* ad_dtype: storage type of weights and hidden states */
+} ad_unet_cfg;
+
+typedef struct ad_unit_info {
+  char name[AD_NAME_LEN];
+  int kind;        /* ad_unit_kind */
+  int c_in, c_skip, c_out;
+  int h_in, w_in, h_out, w_out;
+  int depth;       /* transformer layers */
+  int skip_from;   /* unit whose output is concatenated to the main input, or -1 */
+  int64_t flops;   /* 2 per multiply-accumulate: convolutions, linear layers, attention matmuls */
+} ad_unit_info;
+
+typedef struct ad_weight_info {
+  char name[AD_NAME_LEN];
+  int ndim;
+  int shape[4];    /* conv: [out][in][k][k]; linear: [out][in]; vectors: [n] */
+} ad_weight_info;
+
+/* One component evaluation of the schedule table (Section 3.2; Appendix A). */
+typedef struct ad_sched_row {
+  int round;       /* parallel round; warm-up steps are rounds 0..w-1 */
+  int comp;        /* 1..N */
+  int tau_step;    /* step whose timestep feeds the time embedding */
+  int read_slot;   /* 0/1: which stored-state slot the inputs come from */
+  int write_slot;  /* 0/1, or -1 when only the noise prediction of this evaluation is kept */
+  int latent_step; /* step index of the latent read by component 1, else -1 */
+  int eps_step;    /* step whose noise prediction this evaluation yields (component N), else -1 */
+} ad_sched_row;
+
+typedef struct ad_ctx ad_ctx;
+typedef void* ad_stream; /* a hipStream_t */
+
+/* ---- life cycle (host only, no GPU needed) -------------------------------------------------- */
+
+/* Builds the unit list, the FLOP-balanced contiguous partition into n_components (Section 3.2:
+ * components of comparable load; Appendix A "Model Segmentation") and the memory plan.
+ * warmup >= 1 is required when n_components > 1 (the stored states must exist before the first
+ * asynchronous round); stride >= 1.  cfg: HOST.  *out receives a context owned by the library. */
+ad_status ad_create(const ad_unet_cfg* cfg, int n_components, int warmup, int stride, ad_ctx** out);
+void ad_destroy(ad_ctx* ctx); /* NULL is allowed */
+const char* ad_last_error(void);
+
+/* ---- introspection (host only; integer results are bit-exact by contract) ------------------- */
+int ad_num_units(const ad_ctx* ctx);
+ad_status ad_get_unit(const ad_ctx* ctx, int unit, ad_unit_info* out);
+/* first[k], last[k]: unit range of component k+1; arrays of n_components ints (HOST). */
+ad_status ad_get_partition(const ad_ctx* ctx, int* first, int* last);
+/* Tensors a component reads from earlier components / offers to later ones, named by producing
+ * unit (-1 = the latent).  Arrays HOST, capacity cap each; n_in and n_out receive the counts.
+ * The main hidden state (previous unit / last unit) is always listed.  Order: ascending. */
+ad_status ad_component_io(const ad_ctx* ctx, int comp, int cap, int* in_units, int* n_in, int* out_units, int* n_out);
+/* Shape and byte size of the tensor unit `unit` produces (unit -1: the latent, fp32). */
+ad_status ad_tensor_shape(const ad_ctx* ctx, int unit, int* b, int* h, int* w, int* c, size_t* bytes);
+int ad_num_weights(const ad_ctx* ctx);
+ad_status ad_get_weight(const ad_ctx* ctx, int index, ad_weight_info* out);
+
+/* ---- device memory and weights --------------------------------------------------------------- */
+ad_status ad_device_bytes(const ad_ctx* ctx, size_t* weight_bytes, size_t* work_bytes);
+/* weights_dev, work_dev: DEVICE, 256-byte aligned, at least the sizes above; owned by the caller and
+ * must outlive the context's use.  The work arena holds the stored-state slots, the per-component
+ * activations and the noise predictions. */
+ad_status ad_bind_device_memory(ad_ctx* ctx, void* weights_dev, size_t weight_bytes, void* work_dev, size_t work_bytes);
+/* host_ptrs[i]: HOST fp32 array of weight i in manifest order and manifest shape.  The library
+ * converts to cfg.dtype, re-lays-out for its kernels and copies to the weight arena (synchronous). */
+ad_status ad_load_weights(ad_ctx* ctx, const float* const* host_ptrs, int n);
+
+/* ---- run set-up -------------------------------------------------------------------------------- */
+/* Fixes the number of steps T, the sampler and the noise schedule, builds the schedule table and
+ * rewinds the step counter.  Timesteps: tau_i = (T-1-i) * (1000 / T); betas over 1000 training steps
+ * from 0.00085 to 0.012 (linear, or linear in sqrt(beta)).  time_shift: Appendix A "Time Shifting". */
+ad_status ad_reset(ad_ctx* ctx, int T, int sampler_kind, int beta_kind, float cfg_scale, int time_shift);
+ad_status ad_get_timesteps(const ad_ctx* ctx, int* tau, int cap);           /* HOST out, T entries */
+int ad_num_sched_rows(const ad_ctx* ctx);
+ad_status ad_get_schedule(const ad_ctx* ctx, ad_sched_row* rows, int cap);  /* HOST out */
+/* Sampler coefficients of step i: x' = c_x * x + c_eps * eps; in_scale multiplies the latent before it
+ * enters the model (1 for DDIM); init_scale multiplies the initial noise (1 for DDIM).  HOST out. */
+ad_status ad_get_sampler_coeffs(const ad_ctx* ctx, int step, double* c_x, double* c_eps, double* in_scale, double* init_scale);
+
+/* ---- the hot path ------------------------------------------------------------------------------ */
+
+/* One evaluation of component `comp` (1..N) = eps_theta^comp(., t) of Eq. 4.
+ *   lane        which private activation workspace to use: 0, or 0..stride-1 for the last component
+ *               (two evaluations that run concurrently must use different lanes);
+ *   hidden_in   HOST array of DEVICE pointers, one per input of ad_component_io() in its order
+ *               (for component 1 the single entry is the fp32 latent);
+ *   t_index     step index i whose timestep tau_i feeds the time embedding (0..T-1);
+ *   latent_scale  factor applied to the latent on entry (component 1 only; ad_get_sampler_coeffs);
+ *   text_emb, pooled_emb  DEVICE (pooled_emb may be NULL when cfg.pooled_dim == 0);
+ *   hidden_out  HOST array of DEVICE pointers, one per output of ad_component_io() in its order
+ *               (the last component's single output is the fp32 noise prediction);
+ *   stream      all work is enqueued here.
+ * Inputs are only read, outputs only written; nothing else outside the lane's workspace changes. */
+ad_status ad_component_forward(ad_ctx* ctx, int comp, int lane, const void* const* hidden_in, int t_index,
+                               float latent_scale, const void* text_emb, const void* pooled_emb,
+                               void* const* hidden_out, ad_stream stream);
+
+/* One parallel round of the schedule (one step during warm-up, `stride` steps afterwards, fewer in a
+ * trailing partial round): evaluates the round's components concurrently on the given streams
+ * (evaluation e runs on streams[e % n_streams]; n_streams = 1 gives the serial order), stores their
+ * outputs in the slot the table names, then applies the sampler once per completed step.
+ *   latent      DEVICE fp32, updated in place;
+ *   streams     HOST array of hipStream_t;
+ *   steps_done  HOST out: total steps completed after this call.
+ * On return all work is enqueued; the last used event is waited on by streams[0], so synchronising
+ * streams[0] is enough to observe the round.  Returns AD_ERR_DONE once T steps are complete. */
+ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* pooled_emb,
+                  const ad_stream* streams, int n_streams, int* steps_done);
+
+/* Sampler update of step `step_index` (Section 3.1, Eq. 3, read as deterministic DDIM; or Euler),
+ * fused with the guidance combination eps = eps_u + g (eps_c - eps_u) (batch row 0 = conditional):
+ *   x  DEVICE fp32 [C][H][W] in place;  eps  DEVICE fp32 [batch][C][H][W]. */
+ad_status ad_ddim_update(ad_ctx* ctx, void* x, const void* eps, int step_index, float cfg_scale, ad_stream stream);
+/* The same kernel on an arbitrary element count (used to measure it at a bandwidth-bound size):
+ *   x DEVICE fp32 [n] in place; eps DEVICE fp32 [batch][n]; x' = c_x * x + c_eps * guided eps. */
+ad_status ad_sampler_update_raw(void* x, const void* eps, size_t n, int batch, float c_x, float c_eps,
+                                float cfg_scale, ad_stream stream);
+
+/* After ad_step: DEVICE pointer of the stored output of `unit` in slot 0/1 (valid for units listed as a
+ * component output), and of noise-prediction buffer j (0..stride-1). */
+ad_status ad_get_slot_tensor(const ad_ctx* ctx, int slot, int unit, void** ptr, size_t* bytes);
+ad_status ad_get_eps_buffer(const ad_ctx* ctx, int j, void** ptr, size_t* bytes);
+
+/* ---- single kernels (entry points for kernel-level parity tests and measurements) -------------- *
+ * All pointers DEVICE; element type `dtype` (ad_dtype) unless stated.  Tensors NHWC. */
+
+/* Implicit-GEMM convolution / linear layer:  out[m][n] = sum_k A[m][k] W[n][k] (+bias +rowvec +residual).
+ *   src0/src1  inputs concatenated on channels (src1 may be NULL, c1 = 0); stored spatial size hs x ws;
+ *   up         1: the logical input is the nearest-2x upsampling of the stored one;
+ *   ksize 1|3, stride 1|2, padding ksize/2;  w_packed: weights as produced by ad_pack_conv_weight;
+ *   bias fp32 [n] or NULL; rowvec fp32 [batch][n] or NULL; residual [m][n] or NULL;
+ *   out_mode 0: [m][n] dtype; 1: GEGLU (weights packed with geglu=1) -> [m][n/2]; 2: transposed
+ *   [batch][n][ld_t] in dtype; 3: transposed fp32 [batch][n][ld_t]. */
+ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hs, int ws,
+                          int up, int ksize, int stride, const void* w_packed, int n_out, const float* bias,
+                          const float* rowvec, const void* residual, void* out, int out_mode, int ld_t,
+                          ad_stream stream);
+/* Packs HOST fp32 weights [n_out][c_in][k][k] into the kernel layout (HOST out, dtype elements).
+ * Returns the packed size in bytes through *bytes when out == NULL. */
+ad_status ad_pack_conv_weight(int dtype, const float* w, int n_out, int c_in, int ksize, int geglu, void* out, size_t* bytes);
+/* GroupNorm (+SiLU when silu != 0) over the channel concatenation of src0/src1; gamma/beta fp32;
+ * scratch: fp32, at least ad_groupnorm_scratch_bytes(); out [batch][hw][c0+c1]. */
+size_t ad_groupnorm_scratch_bytes(int batch, int hw, int c);
+ad_status ad_groupnorm_forward(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw,
+                               int groups, const float* gamma, const float* beta, float eps, int silu,
+                               void* out, void* scratch, ad_stream stream);
+ad_status ad_layernorm_forward(int dtype, const void* src, int rows, int c, const float* gamma, const float* beta,
+                               float eps, void* out, ad_stream stream);
+/* Multi-head attention out[b][l][h*d+j] = softmax(q k^T / sqrt(d)) v, heads = c / head_dim.
+ *   q [batch][l][ldq], k [batch][lk][ldk], out [batch][l][ldo] (leading dimensions in elements);
+ *   v_is_transposed 0: v [batch][lk][ldv]; 1: v [batch][c][ldv] (keys contiguous, ldv >= lk rounded up to 64).
+ *   The MFMA kernel is used for bf16, head_dim 64, transposed v; the generic kernel otherwise. */
+ad_status ad_attention_forward(int dtype, const void* q, const void* k, const void* v, int v_is_transposed,
+                               int batch, int l, int lk, int c, int head_dim, int ldq, int ldk, int ldv, int ldo,
+                               void* out, ad_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASYNCDIFF_H */

@@ -1,0 +1,43 @@
+// Launchers of the HIP kernels (device pointers, explicit stream).  Shapes are validated here,
+// on the host, before any launch.
+#pragma once
+
+#include "ad_internal.h"
+
+namespace ad {
+
+struct ConvArgs {
+  int dtype;
+  const void* src0; const void* src1;   // NHWC sources, concatenated on channels
+  int c0, c1;
+  int batch, hs, ws;                    // stored spatial size of the sources
+  int up;                               // 1: logical input = nearest-2x of the stored one
+  int ksize, stride;
+  const void* w;                        // packed [n_pad][k_pad]
+  int n_out;                            // GEMM N (for GEGLU: the 2x-wide packed projection)
+  const float* bias; const float* rowvec; int rowvec_ld;   // rowvec [batch][rowvec_ld]
+  const void* residual;
+  void* out; int out_mode; int ld_t;
+};
+enum { OUT_ROWMAJOR = 0, OUT_GEGLU = 1, OUT_TRANSPOSED = 2, OUT_TRANSPOSED_F32 = 3 };
+
+ad_status launch_conv(const ConvArgs& a, hipStream_t s);
+
+ad_status launch_groupnorm(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw, int groups,
+                           const float* gamma, const float* beta, float eps, int silu, void* out, void* scratch,
+                           size_t scratch_bytes, hipStream_t s);
+ad_status launch_layernorm(int dtype, const void* src, int rows, int c, const float* gamma, const float* beta, float eps,
+                           void* out, hipStream_t s);
+ad_status launch_attention(int dtype, const void* q, const void* k, const void* v, int v_t, int batch, int l, int lk, int c,
+                           int head_dim, int ldq, int ldk, int ldv, int ldo, void* out, hipStream_t s);
+// out[r][n] = act_out(bias[n] + sum_k act_in(in[r*in_ld + k]) w[n][k]); in/out fp32, w in dtype; rows <= 16;
+// in_ld = 0 feeds every row the same input
+ad_status launch_linear_rows(int dtype, const float* in, int in_ld, int rows, int k, const void* w, const float* bias, int n,
+                             int silu_in, int silu_out, int accumulate, float* out, hipStream_t s);
+ad_status launch_sinusoid(float tau, int dim, float* out, hipStream_t s);
+// im2col of the fp32 latent [cl][h][w] (times scale) for the first 3x3 convolution: out [batch*h*w][kConvInK]
+ad_status launch_pack_latent(int dtype, const float* latent, float scale, int cl, int h, int w, int batch, void* out,
+                             hipStream_t s);
+ad_status launch_sampler(float* x, const float* eps, size_t n, int batch, float cx, float ce, float g, hipStream_t s);
+
+}  // namespace ad

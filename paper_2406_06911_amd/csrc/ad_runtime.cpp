@@ -1,0 +1,444 @@
+// Component runtime: weight upload, evaluation of one component (a contiguous unit range) on a
+// stream, and the round driver that runs the schedule table over the caller's streams with the
+// double-buffered stored states.
+#include <cstring>
+
+#include "ad_internal.h"
+#include "ad_kernels.h"
+
+namespace ad {
+
+static inline Ctx* C(ad_ctx* p) { return reinterpret_cast<Ctx*>(p); }
+static inline const Ctx* C(const ad_ctx* p) { return reinterpret_cast<const Ctx*>(p); }
+
+#define AD_TRY(expr)                  \
+  do {                                \
+    ad_status st_ = (expr);           \
+    if (st_ != AD_OK) return st_;     \
+  } while (0)
+
+// Device-side view of the weights of one evaluation.
+struct WView {
+  const Ctx& c;
+  const void* at(int idx) const { return c.weights_dev + c.weights[idx].dev_off; }
+  const float* f32(int idx) const { return (const float*)at(idx); }
+};
+
+struct Eval {
+  Ctx& c;
+  const Component& cp;
+  const Workspace& ws;
+  const void* const* in;
+  void* const* out;
+  const void* text;
+  hipStream_t s;
+  int dt;
+  const float* proj = nullptr;   // fused time projection of the component's ResBlocks [batch][proj_ld]
+  int proj_ld = 0;
+
+  char* work(size_t off) const { return c.work_dev + off; }
+  void* temp(int t) const { return work(ws.temp_off[t]); }
+  float* f32area() const { return (float*)work(ws.f32_off); }
+
+  // tensor produced by `unit` (may live outside this component)
+  const void* tensor_in(int unit) const {
+    if (unit >= cp.first && unit <= cp.last) return tensor_out(unit);
+    for (size_t i = 0; i < cp.in_units.size(); ++i)
+      if (cp.in_units[i] == unit) return in[i];
+    return nullptr;
+  }
+  void* tensor_out(int unit) const {
+    const size_t off = ws.unit_off[unit - cp.first];
+    if (off != SIZE_MAX) return work(off);
+    for (size_t i = 0; i < cp.out_units.size(); ++i)
+      if (cp.out_units[i] == unit) return out[i];
+    return nullptr;
+  }
+
+  ad_status conv(const void* src0, const void* src1, int c0, int c1, int hs, int wsz, int up, int ksize, int stride,
+                 int w_idx, int b_idx, const float* rowvec, const void* residual, void* dst, int mode = OUT_ROWMAJOR,
+                 int ld_t = 0) const {
+    WView wv{c};
+    ConvArgs a{dt, src0, src1, c0, c1, c.cfg.batch, hs, wsz, up, ksize, stride, wv.at(w_idx), c.weights[w_idx].info.shape[0],
+               b_idx >= 0 ? wv.f32(b_idx) : nullptr, rowvec, proj_ld, residual, dst, mode, ld_t};
+    return launch_conv(a, s);
+  }
+  // linear layer on a [rows][cin] matrix
+  ad_status linear(const void* src, int rows, int cin, int w_idx, int b_idx, const void* residual, void* dst,
+                   int mode = OUT_ROWMAJOR, int batch = 1, int ld_t = 0) const {
+    WView wv{c};
+    ConvArgs a{dt, src, nullptr, cin, 0, batch, rows / batch, 1, 0, 1, 1, wv.at(w_idx), c.weights[w_idx].info.shape[0],
+               b_idx >= 0 ? wv.f32(b_idx) : nullptr, nullptr, 0, residual, dst, mode, ld_t};
+    return launch_conv(a, s);
+  }
+  ad_status gn(const void* src0, const void* src1, int c0, int c1, int hw, int g_idx, int silu, void* dst) const {
+    WView wv{c};
+    return launch_groupnorm(dt, src0, src1, c0, c1, c.cfg.batch, hw, c.cfg.gn_groups, wv.f32(g_idx), wv.f32(g_idx + 1),
+                            c.cfg.gn_eps, silu, dst, work(ws.gn_off), c.gn_bytes, s);
+  }
+  ad_status ln(const void* src, int rows, int ch, int g_idx, void* dst) const {
+    WView wv{c};
+    return launch_layernorm(dt, src, rows, ch, wv.f32(g_idx), wv.f32(g_idx + 1), c.cfg.ln_eps, dst, s);
+  }
+
+  ad_status res(const Unit& u, int ui) const {
+    const ad_unit_info& f = u.info;
+    const int hw = f.h_in * f.w_in, ci = f.c_in + f.c_skip, w0 = u.w_first;
+    const void* x0 = tensor_in(ui - 1);
+    const void* x1 = f.skip_from >= 0 ? tensor_in(f.skip_from) : nullptr;
+    if (!x0 || (f.skip_from >= 0 && !x1)) AD_FAIL(AD_ERR_STATE, "unit %s: missing input", f.name);
+    // manifest order: gn1.g gn1.b conv1.w conv1.b temb.w temb.b gn2.g gn2.b conv2.w conv2.b [short.w short.b]
+    AD_TRY(gn(x0, x1, f.c_in, f.c_skip, hw, w0 + 0, 1, temp(0)));
+    // conv1 adds this block's slice of the fused time projection per (sample, channel)
+    const float* rowvec = proj + (u.temb_row - cp.temb_row0);
+    AD_TRY(conv(temp(0), nullptr, ci, 0, f.h_in, f.w_in, 0, 3, 1, w0 + 2, w0 + 3, rowvec, nullptr, temp(1)));
+    AD_TRY(gn(temp(1), nullptr, f.c_out, 0, hw, w0 + 6, 1, temp(0)));
+    const void* shortcut = x0;
+    if (ci != f.c_out) {
+      AD_TRY(conv(x0, x1, f.c_in, f.c_skip, f.h_in, f.w_in, 0, 1, 1, w0 + 10, w0 + 11, nullptr, nullptr, temp(2)));
+      shortcut = temp(2);
+    }
+    return conv(temp(0), nullptr, f.c_out, 0, f.h_in, f.w_in, 0, 3, 1, w0 + 8, w0 + 9, nullptr, shortcut, tensor_out(ui));
+  }
+  ad_status tfm(const Unit& u, int ui) const {
+    const ad_unit_info& f = u.info;
+    const int B = c.cfg.batch, L = f.h_in * f.w_in, Cc = f.c_in, M = B * L, d = c.cfg.head_dim;
+    const int Lk = c.cfg.ctx_len, lp = round_up(L, 64), lkp = round_up(Lk, 64);
+    const bool vt = dt == AD_BF16 && d == 64;          // transposed V feeds the MFMA attention kernel
+    const void* x = tensor_in(ui - 1);
+    if (!x) AD_FAIL(AD_ERR_STATE, "unit %s: missing input", f.name);
+    int w = u.w_first;
+    // gn.g gn.b proj_in.w proj_in.b | per layer 20 entries | proj_out.w proj_out.b
+    AD_TRY(gn(x, nullptr, Cc, 0, L, w + 0, 0, temp(0)));
+    AD_TRY(linear(temp(0), M, Cc, w + 2, w + 3, nullptr, temp(1)));
+    w += 4;
+    void* h = temp(1);
+    for (int k = 0; k < f.depth; ++k, w += 20) {
+      // ln1.g ln1.b a1.q a1.k a1.v a1.o.w a1.o.b ln2.g ln2.b a2.q a2.k a2.v a2.o.w a2.o.b ln3.g ln3.b ff1.w ff1.b ff2.w ff2.b
+      AD_TRY(ln(h, M, Cc, w + 0, temp(0)));
+      AD_TRY(linear(temp(0), M, Cc, w + 2, -1, nullptr, temp(2)));
+      AD_TRY(linear(temp(0), M, Cc, w + 3, -1, nullptr, temp(3)));
+      if (vt) AD_TRY(linear(temp(0), M, Cc, w + 4, -1, nullptr, temp(4), OUT_TRANSPOSED, B, lp));
+      else AD_TRY(linear(temp(0), M, Cc, w + 4, -1, nullptr, temp(4)));
+      AD_TRY(launch_attention(dt, temp(2), temp(3), temp(4), vt, B, L, L, Cc, d, Cc, Cc, vt ? lp : Cc, Cc, temp(5), s));
+      AD_TRY(linear(temp(5), M, Cc, w + 5, w + 6, h, h));
+      AD_TRY(ln(h, M, Cc, w + 7, temp(0)));
+      AD_TRY(linear(temp(0), M, Cc, w + 9, -1, nullptr, temp(2)));
+      AD_TRY(linear(text, B * Lk, c.cfg.ctx_dim, w + 10, -1, nullptr, temp(7)));
+      if (vt) AD_TRY(linear(text, B * Lk, c.cfg.ctx_dim, w + 11, -1, nullptr, temp(8), OUT_TRANSPOSED, B, lkp));
+      else AD_TRY(linear(text, B * Lk, c.cfg.ctx_dim, w + 11, -1, nullptr, temp(8)));
+      AD_TRY(launch_attention(dt, temp(2), temp(7), temp(8), vt, B, L, Lk, Cc, d, Cc, Cc, vt ? lkp : Cc, Cc, temp(5), s));
+      AD_TRY(linear(temp(5), M, Cc, w + 12, w + 13, h, h));
+      AD_TRY(ln(h, M, Cc, w + 14, temp(0)));
+      AD_TRY(linear(temp(0), M, Cc, w + 16, w + 17, nullptr, temp(6), OUT_GEGLU));
+      AD_TRY(linear(temp(6), M, 4 * Cc, w + 18, w + 19, h, h));
+    }
+    return linear(h, M, Cc, w + 0, w + 1, x, tensor_out(ui));
+  }
+};
+
+// temb = Lin2(SiLU(Lin1(sinusoid(tau)))) (+ pooled branch), then every ResBlock projection of the
+// component in one launch: proj[b][row] = temb_b[row] + sum_k SiLU(temb[b][k]) W[row][k].
+static ad_status time_projection(Eval& e, int tau, const void* pooled) {
+  Ctx& c = e.c;
+  const int B = c.cfg.batch, td = c.temb_dim, c0 = c.cfg.channels[0], dt = e.dt;
+  float* sinus = e.f32area();
+  float* t1 = sinus + c0;
+  float* temb = t1 + (size_t)B * td;
+  float* pool1 = temb + (size_t)B * td;
+  float* proj = pool1 + 2 * (size_t)B * td;
+  WView wv{c};
+  AD_TRY(launch_sinusoid((float)tau, c0, sinus, e.s));
+  // the sinusoid is the same for every batch row: evaluate the MLP on one row, broadcast below
+  AD_TRY(launch_linear_rows(dt, sinus, 0, 1, c0, wv.at(0), wv.f32(1), td, 0, 1, 0, t1, e.s));
+  AD_TRY(launch_linear_rows(dt, t1, 0, B, td, wv.at(2), wv.f32(3), td, 0, 0, 0, temb, e.s));
+  if (c.cfg.pooled_dim > 0) {
+    if (!pooled) AD_FAIL(AD_ERR_INVALID, "pooled embedding required by this configuration");
+    AD_TRY(launch_linear_rows(dt, (const float*)pooled, c.cfg.pooled_dim, B, c.cfg.pooled_dim, wv.at(4), wv.f32(5), td, 0, 1, 0, pool1, e.s));
+    AD_TRY(launch_linear_rows(dt, pool1, td, B, td, wv.at(6), wv.f32(7), td, 0, 0, 1, temb, e.s));
+  }
+  e.proj = proj;
+  e.proj_ld = e.cp.temb_rows;
+  if (e.cp.temb_rows > 0) {
+    const char* wmat = c.weights_dev + c.temb_w_off + (size_t)e.cp.temb_row0 * td * esize(dt);
+    const float* bvec = (const float*)(c.weights_dev + c.temb_b_off) + e.cp.temb_row0;
+    AD_TRY(launch_linear_rows(dt, temb, td, B, td, wmat, bvec, e.cp.temb_rows, 1, 0, 0, proj, e.s));
+  }
+  return AD_OK;
+}
+
+static ad_status run_component(Ctx& c, int comp, int lane, const void* const* in, int tau, float latent_scale,
+                               const void* text, const void* pooled, void* const* out, hipStream_t s,
+                               hipEvent_t latent_consumed = nullptr) {
+  const Component& cp = c.comps[comp - 1];
+  Eval e{c, cp, c.ws[comp - 1][lane], in, out, text, s, c.cfg.dtype};
+  const ad_unet_cfg& g = c.cfg;
+  AD_TRY(time_projection(e, tau, pooled));
+  for (int ui = cp.first; ui <= cp.last; ++ui) {
+    const Unit& u = c.units[ui];
+    const ad_unit_info& f = u.info;
+    switch (f.kind) {
+      case AD_UNIT_CONV_IN: {
+        const void* latent = e.tensor_in(-1);
+        if (!latent) AD_FAIL(AD_ERR_STATE, "conv_in: missing latent");
+        AD_TRY(launch_pack_latent(e.dt, (const float*)latent, latent_scale, g.latent_channels, g.height, g.width, g.batch, e.temp(0), s));
+        if (latent_consumed) AD_HIP(hipEventRecord(latent_consumed, s));
+        AD_TRY(e.conv(e.temp(0), nullptr, kConvInK, 0, g.height, g.width, 0, 1, 1, u.w_first, u.w_first + 1, nullptr, nullptr, e.tensor_out(ui)));
+        break;
+      }
+      case AD_UNIT_RES: {
+        AD_TRY(e.res(u, ui));
+        break;
+      }
+      case AD_UNIT_TFM: AD_TRY(e.tfm(u, ui)); break;
+      case AD_UNIT_DOWN:
+        AD_TRY(e.conv(e.tensor_in(ui - 1), nullptr, f.c_in, 0, f.h_in, f.w_in, 0, 3, 2, u.w_first, u.w_first + 1, nullptr, nullptr, e.tensor_out(ui)));
+        break;
+      case AD_UNIT_UP:
+        AD_TRY(e.conv(e.tensor_in(ui - 1), nullptr, f.c_in, 0, f.h_in, f.w_in, 1, 3, 1, u.w_first, u.w_first + 1, nullptr, nullptr, e.tensor_out(ui)));
+        break;
+      case AD_UNIT_OUT:
+        AD_TRY(e.gn(e.tensor_in(ui - 1), nullptr, f.c_in, 0, f.h_in * f.w_in, u.w_first, 1, e.temp(0)));
+        AD_TRY(e.conv(e.temp(0), nullptr, f.c_in, 0, f.h_in, f.w_in, 0, 3, 1, u.w_first + 2, u.w_first + 3, nullptr, nullptr,
+                      e.tensor_out(ui), OUT_TRANSPOSED_F32, f.h_out * f.w_out));
+        break;
+    }
+  }
+  return AD_OK;
+}
+
+}  // namespace ad
+
+using namespace ad;
+
+extern "C" {
+
+void ad_destroy(ad_ctx* ctx) {
+  if (!ctx) return;
+  Ctx* c = C(ctx);
+  for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+  if (c->ev_pack) (void)hipEventDestroy(c->ev_pack);
+  delete c;
+}
+
+ad_status ad_bind_device_memory(ad_ctx* ctx, void* weights_dev, size_t weight_bytes, void* work_dev, size_t work_bytes) {
+  if (!ctx || !weights_dev || !work_dev) AD_FAIL(AD_ERR_INVALID, "null argument");
+  Ctx& c = *C(ctx);
+  if (weight_bytes < c.weight_bytes || work_bytes < c.work_bytes)
+    AD_FAIL(AD_ERR_NOMEM, "arenas too small: need %zu + %zu bytes", c.weight_bytes, c.work_bytes);
+  if (((uintptr_t)weights_dev | (uintptr_t)work_dev) % kAlign) AD_FAIL(AD_ERR_INVALID, "arenas must be %zu-byte aligned", kAlign);
+  c.weights_dev = (char*)weights_dev;
+  c.work_dev = (char*)work_dev;
+  c.weights_loaded = false;
+  return AD_OK;
+}
+
+ad_status ad_load_weights(ad_ctx* ctx, const float* const* host_ptrs, int n) {
+  if (!ctx || !host_ptrs) AD_FAIL(AD_ERR_INVALID, "null argument");
+  Ctx& c = *C(ctx);
+  if (!c.weights_dev) AD_FAIL(AD_ERR_STATE, "ad_bind_device_memory has not been called");
+  if (n != (int)c.weights.size()) AD_FAIL(AD_ERR_INVALID, "expected %zu weight tensors, got %d", c.weights.size(), n);
+  const int dt = c.cfg.dtype;
+  std::vector<char> stage;
+  for (int i = 0; i < n; ++i)
+    if (!host_ptrs[i]) AD_FAIL(AD_ERR_INVALID, "weight %d (%s) is null", i, c.weights[i].info.name);
+  // the fused time-projection matrix is assembled from the ResBlocks' rows
+  std::vector<char> temb_w((size_t)c.temb_rows_total * c.temb_dim * esize(dt));
+  std::vector<float> temb_b((size_t)c.temb_rows_total);
+  size_t temb_row = 0;
+  for (int i = 0; i < n; ++i) {
+    const Weight& w = c.weights[i];
+    const int* sh = w.info.shape;
+    const float* src = host_ptrs[i];
+    if (w.role == W_TEMB) {
+      pack_rows(dt, src, (size_t)sh[0] * sh[1], temb_w.data() + temb_row * c.temb_dim * esize(dt));
+      continue;
+    }
+    if (w.role == W_TEMB_BIAS) {
+      std::memcpy(temb_b.data() + temb_row, src, (size_t)sh[0] * 4);
+      temb_row += sh[0];
+      continue;
+    }
+    stage.assign(w.dev_bytes, 0);
+    switch (w.role) {
+      case W_CONV3: pack_conv(dt, src, sh[0], sh[1], 3, false, stage.data()); break;
+      case W_CONV1: pack_conv(dt, src, sh[0], sh[1], 1, false, stage.data()); break;
+      case W_GEGLU: pack_conv(dt, src, sh[0], sh[1], 1, true, stage.data()); break;
+      case W_CONV_IN: {
+        // K index = tap * c_in + channel, padded to kConvInK
+        std::vector<float> tmp((size_t)sh[0] * kConvInK, 0.f);
+        for (int o = 0; o < sh[0]; ++o)
+          for (int ci = 0; ci < sh[1]; ++ci)
+            for (int t = 0; t < 9; ++t) tmp[(size_t)o * kConvInK + t * sh[1] + ci] = src[((size_t)o * sh[1] + ci) * 9 + t];
+        pack_rows(dt, tmp.data(), tmp.size(), stage.data());
+        break;
+      }
+      case W_SMALL: pack_rows(dt, src, (size_t)sh[0] * sh[1], stage.data()); break;
+      case W_VEC_F32: std::memcpy(stage.data(), src, (size_t)sh[0] * 4); break;
+      case W_GEGLU_BIAS: {
+        float* dst = (float*)stage.data();
+        const int half = sh[0] / 2;
+        for (int r = 0; r < sh[0]; ++r) {
+          const int blk = r / 64, in = r % 64;
+          dst[r] = src[in < 32 ? blk * 32 + in : half + blk * 32 + in - 32];
+        }
+        break;
+      }
+      default: break;
+    }
+    AD_HIP(hipMemcpy(c.weights_dev + w.dev_off, stage.data(), w.dev_bytes, hipMemcpyHostToDevice));
+  }
+  if (c.temb_rows_total > 0) {
+    AD_HIP(hipMemcpy(c.weights_dev + c.temb_w_off, temb_w.data(), temb_w.size(), hipMemcpyHostToDevice));
+    AD_HIP(hipMemcpy(c.weights_dev + c.temb_b_off, temb_b.data(), temb_b.size() * 4, hipMemcpyHostToDevice));
+  }
+  AD_HIP(hipDeviceSynchronize());
+  c.weights_loaded = true;
+  return AD_OK;
+}
+
+ad_status ad_component_forward(ad_ctx* ctx, int comp, int lane, const void* const* hidden_in, int t_index,
+                               float latent_scale, const void* text_emb, const void* pooled_emb,
+                               void* const* hidden_out, ad_stream stream) {
+  if (!ctx || !hidden_in || !hidden_out) AD_FAIL(AD_ERR_INVALID, "null argument");
+  Ctx& c = *C(ctx);
+  if (!c.weights_loaded) AD_FAIL(AD_ERR_STATE, "weights are not loaded");
+  if (c.T == 0) AD_FAIL(AD_ERR_STATE, "ad_reset has not been called");
+  if (comp < 1 || comp > c.N) AD_FAIL(AD_ERR_INVALID, "component %d out of range", comp);
+  if (lane < 0 || lane >= (int)c.ws[comp - 1].size()) AD_FAIL(AD_ERR_INVALID, "lane %d out of range for component %d", lane, comp);
+  if (t_index < 0 || t_index >= c.T) AD_FAIL(AD_ERR_INVALID, "t_index %d out of range", t_index);
+  const Component& cp = c.comps[comp - 1];
+  for (size_t i = 0; i < cp.in_units.size(); ++i) if (!hidden_in[i]) AD_FAIL(AD_ERR_INVALID, "hidden_in[%zu] is null", i);
+  for (size_t i = 0; i < cp.out_units.size(); ++i) if (!hidden_out[i]) AD_FAIL(AD_ERR_INVALID, "hidden_out[%zu] is null", i);
+  bool needs_text = false;
+  for (int i = cp.first; i <= cp.last; ++i) needs_text |= c.units[i].info.kind == AD_UNIT_TFM;
+  if (needs_text && !text_emb) AD_FAIL(AD_ERR_INVALID, "text_emb is null");
+  return run_component(c, comp, lane, hidden_in, c.taus[t_index], latent_scale, text_emb, pooled_emb, hidden_out, (hipStream_t)stream);
+}
+
+ad_status ad_ddim_update(ad_ctx* ctx, void* x, const void* eps, int step_index, float cfg_scale, ad_stream stream) {
+  if (!ctx || !x || !eps) AD_FAIL(AD_ERR_INVALID, "null argument");
+  const Ctx& c = *C(ctx);
+  if (c.T == 0) AD_FAIL(AD_ERR_STATE, "ad_reset has not been called");
+  if (step_index < 0 || step_index >= c.T) AD_FAIL(AD_ERR_INVALID, "step %d out of range", step_index);
+  double cx, ce, s0, s1;
+  sampler_coeffs(c, step_index, &cx, &ce, &s0, &s1);
+  const size_t n = (size_t)c.cfg.latent_channels * c.cfg.height * c.cfg.width;
+  return launch_sampler((float*)x, (const float*)eps, n, c.cfg.batch, (float)cx, (float)ce, cfg_scale, (hipStream_t)stream);
+}
+
+ad_status ad_get_slot_tensor(const ad_ctx* ctx, int slot, int unit, void** ptr, size_t* bytes) {
+  if (!ctx || !ptr) AD_FAIL(AD_ERR_INVALID, "null argument");
+  const Ctx& c = *C(ctx);
+  if (slot < 0 || slot > 1 || unit < 0 || unit >= (int)c.units.size()) AD_FAIL(AD_ERR_INVALID, "slot/unit out of range");
+  if (c.slot_off[slot][unit] == SIZE_MAX) AD_FAIL(AD_ERR_INVALID, "unit %d is not a stored component output", unit);
+  if (!c.work_dev) AD_FAIL(AD_ERR_STATE, "no device memory bound");
+  *ptr = c.work_dev + c.slot_off[slot][unit];
+  if (bytes) *bytes = tensor_bytes(c, unit);
+  return AD_OK;
+}
+
+ad_status ad_get_eps_buffer(const ad_ctx* ctx, int j, void** ptr, size_t* bytes) {
+  if (!ctx || !ptr) AD_FAIL(AD_ERR_INVALID, "null argument");
+  const Ctx& c = *C(ctx);
+  if (j < 0 || j >= c.stride) AD_FAIL(AD_ERR_INVALID, "buffer %d out of range", j);
+  if (!c.work_dev) AD_FAIL(AD_ERR_STATE, "no device memory bound");
+  *ptr = c.work_dev + c.eps_off[j];
+  if (bytes) *bytes = tensor_bytes(c, (int)c.units.size() - 1);
+  return AD_OK;
+}
+
+// One round of the table.  Streams: evaluation e of the round runs on streams[e % n]; every stream
+// first waits for the events that closed the previous round (the round reads the slot that round
+// wrote and overwrites the slot that round read), the sampler runs behind the last-component
+// evaluations and behind the latent read of component 1.
+ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* pooled_emb, const ad_stream* streams,
+                  int n_streams, int* steps_done) {
+  if (!ctx || !latent || !streams || n_streams < 1) AD_FAIL(AD_ERR_INVALID, "bad argument");
+  Ctx& c = *C(ctx);
+  if (!c.weights_loaded) AD_FAIL(AD_ERR_STATE, "weights are not loaded");
+  if (c.T == 0) AD_FAIL(AD_ERR_STATE, "ad_reset has not been called");
+  if (c.next_row >= c.rows.size()) {
+    if (steps_done) *steps_done = c.steps_done;
+    return AD_ERR_DONE;
+  }
+  const int max_par = c.N + c.stride - 1;
+  const int ns = n_streams < max_par ? n_streams : max_par;
+  // events: [0..ns) end-of-round per stream, [ns..2ns) scratch for this round
+  while ((int)c.events.size() < 2 * max_par + 2) {
+    hipEvent_t ev;
+    AD_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    c.events.push_back(ev);
+  }
+  if (!c.ev_pack) AD_HIP(hipEventCreateWithFlags(&c.ev_pack, hipEventDisableTiming));
+
+  const size_t r0 = c.next_row;
+  size_t r1 = r0;
+  while (r1 < c.rows.size() && c.rows[r1].round == c.rows[r0].round) ++r1;
+  const bool warm = c.rows[r0].read_slot == c.rows[r0].write_slot;
+  const int nu = (int)c.units.size();
+
+  // previous round closed with event 0 recorded on streams[0] (see the end of this function)
+  hipStream_t s0 = (hipStream_t)streams[0];
+  if (c.rows[r0].round > 0)
+    for (int k = 1; k < ns; ++k) AD_HIP(hipStreamWaitEvent((hipStream_t)streams[k], c.events[0], 0));
+
+  std::vector<int> eps_steps, eps_lane;
+  std::vector<hipStream_t> eps_stream;
+  int lane_next = 0;
+  bool pack_recorded = false;
+  hipStream_t pack_stream = nullptr;
+  for (size_t r = r0; r < r1; ++r) {
+    const ad_sched_row& row = c.rows[r];
+    const Component& cp = c.comps[row.comp - 1];
+    hipStream_t s = warm ? s0 : (hipStream_t)streams[(r - r0) % ns];
+    const void* in[64];
+    void* out[64];
+    if (cp.in_units.size() > 64 || cp.out_units.size() > 64) AD_FAIL(AD_ERR_INVALID, "too many component tensors");
+    for (size_t i = 0; i < cp.in_units.size(); ++i)
+      in[i] = cp.in_units[i] < 0 ? latent : (const void*)(c.work_dev + c.slot_off[row.read_slot][cp.in_units[i]]);
+    int lane = 0;
+    if (row.comp == c.N) lane = lane_next++;
+    for (size_t i = 0; i < cp.out_units.size(); ++i) {
+      const int u = cp.out_units[i];
+      if (u == nu - 1) out[i] = c.work_dev + c.eps_off[lane];
+      else if (row.write_slot >= 0) out[i] = c.work_dev + c.slot_off[row.write_slot][u];
+      else AD_FAIL(AD_ERR_STATE, "schedule row drops a stored tensor");
+    }
+    double cx, ce, in_scale = 1.0, init_scale;
+    if (row.latent_step >= 0) sampler_coeffs(c, row.latent_step, &cx, &ce, &in_scale, &init_scale);
+    // the sampler may overwrite the latent only after component 1 has consumed it
+    AD_TRY(run_component(c, row.comp, lane, in, c.taus[row.tau_step], (float)in_scale, text_emb, pooled_emb, out, s,
+                         row.latent_step >= 0 ? c.ev_pack : nullptr));
+    if (row.latent_step >= 0) { pack_recorded = true; pack_stream = s; }
+    if (row.eps_step >= 0) { eps_steps.push_back(row.eps_step); eps_lane.push_back(lane); eps_stream.push_back(s); }
+  }
+  // sampler updates, in step order, on the stream of the last head evaluation
+  hipStream_t ss = eps_stream.empty() ? s0 : eps_stream.back();
+  for (size_t j = 0; j + 1 < eps_stream.size(); ++j)
+    if (eps_stream[j] != ss) {
+      AD_HIP(hipEventRecord(c.events[1 + j], eps_stream[j]));
+      AD_HIP(hipStreamWaitEvent(ss, c.events[1 + j], 0));
+    }
+  if (pack_recorded && pack_stream != ss) AD_HIP(hipStreamWaitEvent(ss, c.ev_pack, 0));
+  for (size_t j = 0; j < eps_steps.size(); ++j) {
+    double cx, ce, a, b;
+    sampler_coeffs(c, eps_steps[j], &cx, &ce, &a, &b);
+    const size_t n = (size_t)c.cfg.latent_channels * c.cfg.height * c.cfg.width;
+    AD_TRY(launch_sampler((float*)latent, (const float*)(c.work_dev + c.eps_off[eps_lane[j]]), n, c.cfg.batch, (float)cx,
+                          (float)ce, c.cfg_scale, ss));
+    c.steps_done = eps_steps[j] + 1;
+  }
+  // close the round: streams[0] waits for every other stream, then records the round event
+  if (!warm)
+    for (int k = 1; k < ns; ++k) {
+      AD_HIP(hipEventRecord(c.events[max_par + k], (hipStream_t)streams[k]));
+      AD_HIP(hipStreamWaitEvent(s0, c.events[max_par + k], 0));
+    }
+  AD_HIP(hipEventRecord(c.events[0], s0));
+  c.next_row = r1;
+  if (steps_done) *steps_done = c.steps_done;
+  return AD_OK;
+}
+
+}  // extern "C"
