@@ -1,0 +1,211 @@
+"""Benchmark of the hot path on one MI355X: asynchronous denoising steps per second of the SD2.1-shaped
+UNet at 768px (latent 4x96x96, guidance batch 2, N=4 components on 4 HIP streams, bf16).
+
+A step = one parallel round of the schedule: the N component evaluations (each with the inputs stored
+by the previous round) plus the sampler update.  Inputs are synthetic and resident in HBM before the
+timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def run_rounds(m, latent, text, streams, n):
+    for _ in range(n):
+        if m.step(latent, text, streams) is None:
+            raise RuntimeError("schedule exhausted")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", default="sd21_768")
+    ap.add_argument("--streams", type=int, default=0, help="HIP streams for the timed region (0 = one per concurrent evaluation)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the N components on ONE GPU (separate HIP streams); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2406_06911_amd as ad
+    import synthetic_inputs as SI
+    from configs import CONFIGS, RUNS
+
+    d, r = CONFIGS[args.config], RUNS[args.config]
+    dtype = ad.AD_BF16 if r["dtype"] == "bf16" else ad.AD_F32
+    N, w, S = r["N"], r["w"], r["S"]
+    K, W = args.steps, args.warmup
+    dev = "cuda:0"
+    t0 = time.time()
+    m = ad.AsyncDiff(d, N, w, S, dtype)
+    m.allocate(dev)
+    wts = SI.make_weights(m.weight_manifest(), bf16_exact=(dtype == ad.AD_BF16))
+    m.load_weights(wts)
+    del wts
+    log(f"model ready in {time.time() - t0:.1f}s; arenas {[round(b / 2**20) for b in m.device_bytes()]} MiB")
+    tdt = torch.bfloat16 if dtype == ad.AD_BF16 else torch.float32
+    text = torch.from_numpy(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"])).to(dev).to(tdt)
+    noise = torch.from_numpy(SI.make_latent(d["latent_channels"], d["height"], d["width"])).to(dev)
+    units = m.units()
+    flops_step = float(sum(u.flops for u in units))
+    sampler = ad.AD_DDIM if r["sampler"] == "ddim" else ad.AD_EULER
+    # rounds: w sequential warm-up steps of the method, then W untimed and K timed asynchronous rounds
+    rounds_needed = w + (W + K)
+    T = w + max(W + K, min(K, 10) + 2) * S
+    if T > 1000:
+        raise SystemExit("steps too large for one schedule (T <= 1000)")
+
+    def fresh(n_streams):
+        m.reset(T, sampler=sampler, cfg_scale=r["cfg_scale"])
+        lat = noise.clone()
+        ss = [torch.cuda.Stream(device=dev) for _ in range(n_streams)]
+        torch.cuda.synchronize()
+        return lat, ss
+
+    n_par = N + S - 1
+    n_streams = args.streams if args.streams > 0 else n_par
+    # ---- timed region: concurrent components -----------------------------------------------------
+    lat, ss = fresh(n_streams)
+    run_rounds(m, lat, text, ss, w + W)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    run_rounds(m, lat, text, ss, K)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    sec = t2 - t1
+    steps_per_s = K * S / sec
+    ms_per_step = sec / (K * S) * 1e3
+    assert bool(torch.isfinite(lat).all()), "latent is not finite"
+    log(f"concurrent ({n_streams} streams): {steps_per_s:.2f} steps/s, {ms_per_step:.3f} ms/step")
+    # ---- the same rounds on one stream (sequential UNet with the same kernels) ---------------------
+    K2 = min(K, 10)
+    lat, ss = fresh(1)
+    run_rounds(m, lat, text, ss, w + 1)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    run_rounds(m, lat, text, ss, K2)
+    torch.cuda.synchronize()
+    seq_sec = time.perf_counter() - t1
+    seq_steps_per_s = K2 * S / seq_sec
+    log(f"one stream: {seq_steps_per_s:.2f} steps/s")
+    # ---- per-kernel durations: HIP events around every launch of one more round, one stream ----------
+    m.profile(True)
+    run_rounds(m, lat, text, ss, 1)
+    torch.cuda.synchronize()
+    recs = m.profile_records()
+    m.profile(False)
+    agg = {}
+    for name, fl, by, ms in recs:
+        a = agg.setdefault(name, dict(calls=0, ms=0.0, flops=0.0, bytes=0.0))
+        a["calls"] += 1; a["ms"] += ms; a["flops"] += fl; a["bytes"] += by
+    kernels = {}
+    for name, a in sorted(agg.items(), key=lambda kv: -kv[1]["ms"]):
+        e = dict(calls=a["calls"], total_ms=round(a["ms"], 4), avg_us=round(a["ms"] / a["calls"] * 1e3, 2))
+        if a["flops"] > 0 and name.startswith(("igemm", "attn")):
+            e["tflops"] = round(a["flops"] / (a["ms"] * 1e-3) / 1e12, 2)
+            e["frac_mfma_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+        elif a["bytes"] > 0:
+            e["gbs"] = round(a["bytes"] / (a["ms"] * 1e-3) / 1e9, 1)
+            e["frac_hbm_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+        kernels[name] = e
+    dom = max(agg.items(), key=lambda kv: kv[1]["ms"])
+    dname, da = dom
+    if da["flops"] > 0:
+        ach = da["flops"] / (da["ms"] * 1e-3) / 1e12
+        roofline = dict(kernel=dname, bound="mfma", achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, launches=da["calls"],
+                        avg_launch_us=round(da["ms"] / da["calls"] * 1e3, 2),
+                        flops_per_launch=round(da["flops"] / da["calls"]))
+    else:
+        ach = da["bytes"] / (da["ms"] * 1e-3) / 1e9
+        roofline = dict(kernel=dname, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, launches=da["calls"],
+                        avg_launch_us=round(da["ms"] / da["calls"] * 1e3, 2),
+                        bytes_per_launch=round(da["bytes"] / da["calls"]))
+    # ---- the sampler kernel at a bandwidth-bound size (same kernel, synthetic size) ---------------------
+    n_big = 1 << 26
+    xb = torch.randn(n_big, device=dev)
+    eb = torch.randn(2, n_big, device=dev)
+    import ctypes as C
+    s0 = torch.cuda.current_stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for it in range(3):
+        if it == 1:
+            ev[0].record(s0)
+        ad.binding.check(ad.lib.ad_sampler_update_raw(C.c_void_p(xb.data_ptr()), C.c_void_p(eb.data_ptr()), n_big, 2, 1.0, 0.0, 7.5,
+                                                      C.c_void_p(s0.cuda_stream)))
+    ev[1].record(s0)
+    torch.cuda.synchronize()
+    samp_ms = ev[0].elapsed_time(ev[1]) / 2
+    samp_gbs = n_big * 16 / (samp_ms * 1e-3) / 1e9
+    del xb, eb
+    # ---- CPU oracle on a bounded sample of the same workload ---------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.unet import UNetConfig, build_units, run_units, weight_manifest
+        from oracle.partition import unit_flops
+        ocfg = UNetConfig(**d)
+        ounits = build_units(ocfg)
+        last = 2 if len(ounits) > 3 else len(ounits) - 1           # conv_in + first ResBlock + first transformer
+        names = {nm for nm, _ in weight_manifest(ocfg) if nm.startswith(("time.", "pool.", "conv_in.", ounits[1].name, ounits[last].name))}
+        sub = [(nm, sh) for nm, sh in weight_manifest(ocfg) if nm in names]
+        ow = {k: v.astype(np.float64) for k, v in SI.make_weights(sub).items()}
+        x = SI.make_latent(d["latent_channels"], d["height"], d["width"]).astype(np.float64)
+        xin = np.broadcast_to(x, (d["batch"],) + x.shape).copy()
+        ctx = SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]).astype(np.float64)
+        pooled = SI.make_pooled(d["batch"], d["pooled_dim"]) if d["pooled_dim"] else None
+        tc = time.perf_counter()
+        run_units(ocfg, ounits, 0, last, ow, {-1: xin}, 500, ctx, pooled)
+        cpu_sec = time.perf_counter() - tc
+        sample_flops = sum(unit_flops(ocfg, u) for u in ounits[:last + 1])
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        cpu = dict(value=round(1.0 / (cpu_sec * flops_step / sample_flops), 6), unit="steps/s", cores=int(cores), kind="oracle",
+                   sample=f"units {ounits[0].name}..{ounits[last].name} of one UNet forward ({sample_flops / 1e9:.0f} of "
+                          f"{flops_step / 1e9:.0f} GFLOP) in {cpu_sec:.1f}s, scaled by FLOPs to a full step",
+                   sample_seconds=round(cpu_sec, 2))
+    out = {
+        "metric": "UNet denoising steps/sec, 768px SD2.1-shape N=4, 1 GPU; % bf16 MFMA peak",
+        "value": round(steps_per_s, 3), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dtype == ad.AD_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config}: latent {d['latent_channels']}x{d['height']}x{d['width']}, batch {d['batch']} (guidance), "
+                               f"N={N} components on {n_streams} HIP streams, warm-up {w}, stride {S}, {r['sampler']}",
+                   "n_components": N, "stride": S, "streams": n_streams, "flops_per_step": flops_step},
+        "component_evals_per_s": round(steps_per_s / S * n_par, 2),
+        "sequential_steps_per_s": round(seq_steps_per_s, 3),
+        "concurrent_over_sequential": round(steps_per_s / seq_steps_per_s, 4),
+        "mfma_frac_whole_step": round(flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "roofline": roofline,
+        "kernels": kernels,
+        "sampler_large": {"n": n_big, "gbs": round(samp_gbs, 1), "frac_hbm_peak": round(samp_gbs / PEAK_HBM_GBS, 4),
+                          "note": "same kernel on 2^26 latent elements (synthetic size); 16 bytes per element"},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -194,6 +194,21 @@ ad_status ad_sampler_update_raw(void* x, const void* eps, size_t n, int batch, f
 ad_status ad_get_slot_tensor(const ad_ctx* ctx, int slot, int unit, void** ptr, size_t* bytes);
 ad_status ad_get_eps_buffer(const ad_ctx* ctx, int j, void** ptr, size_t* bytes);
 
+/* ---- per-launch timing --------------------------------------------------------------------------- *
+ * While enabled, every kernel the context launches (ad_component_forward, ad_step, ad_ddim_update) is
+ * bracketed by HIP events recorded on the kernel's own stream and tagged with its algorithmic work.
+ * ad_profile_get waits for record `index` to finish.  Off by default; costs two event records per launch. */
+typedef struct ad_profile_rec {
+  char kernel[32];  /* kernel class, e.g. "igemm_bf16_128x128" */
+  double flops;     /* algorithmic floating-point operations of the launch (2 per multiply-accumulate) */
+  double bytes;     /* algorithmic HBM bytes of the launch (operands read once, results written once) */
+  float ms;         /* duration between the two events */
+} ad_profile_rec;
+ad_status ad_profile_enable(ad_ctx* ctx, int on);
+ad_status ad_profile_clear(ad_ctx* ctx);
+int ad_profile_count(const ad_ctx* ctx);
+ad_status ad_profile_get(const ad_ctx* ctx, int index, ad_profile_rec* out); /* HOST out */
+
 /* ---- single kernels (entry points for kernel-level parity tests and measurements) -------------- *
  * All pointers DEVICE; element type `dtype` (ad_dtype) unless stated.  Tensors NHWC. */
 

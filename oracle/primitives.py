@@ -7,6 +7,7 @@ definitions of the layers a Stable-Diffusion-shaped UNet is made of.
 import math
 
 import numpy as np
+from scipy.special import erf
 
 F = np.float64
 
@@ -27,12 +28,13 @@ def conv2d(x, w, b=None, stride=1, pad=None):
     wo = (wd + 2 * p - k) // stride + 1
     xp = np.zeros((n, c, h + 2 * p, wd + 2 * p), F)
     xp[:, :, p:p + h, p:p + wd] = x
-    y = np.zeros((n, o, ho, wo), F)
+    y = np.zeros((o, n * ho * wo), F)
     for u in range(k):
         for v in range(k):
             xs = xp[:, :, u:u + (ho - 1) * stride + 1:stride, v:v + (wo - 1) * stride + 1:stride]
-            # sum over input channels for this tap: [O,C] @ [N,C,Ho*Wo]
-            y += np.matmul(w[:, :, u, v], xs.reshape(n, c, ho * wo)).reshape(n, o, ho, wo)
+            # sum over input channels for this tap: [O,C] @ [C, N*Ho*Wo]
+            y += np.matmul(np.ascontiguousarray(w[:, :, u, v]), xs.transpose(1, 0, 2, 3).reshape(c, n * ho * wo))
+    y = y.reshape(o, n, ho, wo).transpose(1, 0, 2, 3).copy()
     if b is not None:
         y += np.asarray(b, F)[None, :, None, None]
     return y
@@ -72,13 +74,10 @@ def silu(x):
     return x / (1.0 + np.exp(-x))
 
 
-_erf = np.vectorize(math.erf, otypes=[F])
-
-
 def gelu(x):
-    """Exact (erf) GELU: x * Phi(x)."""
+    """Exact (erf) GELU: x * Phi(x), Phi the standard normal CDF."""
     x = np.asarray(x, F)
-    return 0.5 * x * (1.0 + _erf(x / math.sqrt(2.0)))
+    return 0.5 * x * (1.0 + erf(x / math.sqrt(2.0)))
 
 
 def softmax_rows(s):

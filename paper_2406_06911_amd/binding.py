@@ -61,13 +61,17 @@ class SchedRow(C.Structure):
         return (self.round, self.comp, self.tau_step, self.read_slot, self.write_slot, self.latent_step, self.eps_step)
 
 
+class ProfileRec(C.Structure):
+    _fields_ = [("kernel", C.c_char * 32), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float)]
+
+
 EXPORTS = [
     "ad_create", "ad_destroy", "ad_last_error", "ad_num_units", "ad_get_unit", "ad_get_partition", "ad_component_io",
     "ad_tensor_shape", "ad_num_weights", "ad_get_weight", "ad_device_bytes", "ad_bind_device_memory", "ad_load_weights",
     "ad_reset", "ad_get_timesteps", "ad_num_sched_rows", "ad_get_schedule", "ad_get_sampler_coeffs",
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
     "ad_conv_forward", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
-    "ad_attention_forward",
+    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get",
 ]
 
 
@@ -108,6 +112,10 @@ def _load():
     L.ad_groupnorm_forward.argtypes = [ci, vp, vp, ci, ci, ci, ci, ci, vp, vp, cf, ci, vp, vp, vp]
     L.ad_layernorm_forward.argtypes = [ci, vp, ci, ci, vp, vp, cf, vp, vp]
     L.ad_attention_forward.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
+    L.ad_profile_enable.argtypes = [vp, ci]
+    L.ad_profile_clear.argtypes = [vp]
+    L.ad_profile_count.argtypes = [vp]
+    L.ad_profile_get.argtypes = [vp, ci, P(ProfileRec)]
     return L
 
 
@@ -242,6 +250,20 @@ class AsyncDiff:
 
     def ddim_update(self, x, eps, step_index, cfg_scale, stream):
         check(lib.ad_ddim_update(self._h, _ptr(x), _ptr(eps), step_index, float(cfg_scale), C.c_void_p(stream.cuda_stream)))
+
+    def profile(self, on):
+        check(lib.ad_profile_enable(self._h, int(on)))
+
+    def profile_records(self, clear=True):
+        """[(kernel, flops, bytes, ms)] of every launch recorded so far (waits for them to finish)."""
+        out = []
+        r = ProfileRec()
+        for i in range(lib.ad_profile_count(self._h)):
+            check(lib.ad_profile_get(self._h, i, C.byref(r)))
+            out.append((r.kernel.decode(), r.flops, r.bytes, r.ms))
+        if clear:
+            check(lib.ad_profile_clear(self._h))
+        return out
 
     def slot_tensor_ptr(self, slot, unit):
         p, n = C.c_void_p(), C.c_size_t()

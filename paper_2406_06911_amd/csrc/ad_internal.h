@@ -112,6 +112,7 @@ struct Ctx {
   int steps_done = 0;
   std::vector<hipEvent_t> events;      // one per stream used + helpers
   hipEvent_t ev_pack = nullptr;
+  void* profiler = nullptr;            // ad::Profiler*, owned
 };
 
 // host logic

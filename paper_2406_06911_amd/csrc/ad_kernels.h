@@ -6,6 +6,26 @@
 
 namespace ad {
 
+// Optional per-launch timing: when a profiler is installed and switched on, every kernel launch
+// is bracketed by HIP events on its own stream and tagged with its algorithmic work.
+struct ProfRec {
+  const char* name;
+  double flops;      // algorithmic floating-point operations of the launch
+  double bytes;      // algorithmic HBM bytes of the launch
+  hipEvent_t start, stop;
+};
+struct Profiler {
+  bool on = false;
+  std::vector<ProfRec> recs;
+};
+void set_profiler(Profiler* p);   // per host thread; nullptr removes it
+struct ProfLaunch {
+  ProfLaunch(const char* name, double flops, double bytes, hipStream_t s);
+  ~ProfLaunch();
+  hipEvent_t stop_ = nullptr;
+  hipStream_t s_ = nullptr;
+};
+
 struct ConvArgs {
   int dtype;
   const void* src0; const void* src1;   // NHWC sources, concatenated on channels

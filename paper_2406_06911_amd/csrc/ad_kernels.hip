@@ -12,6 +12,21 @@
 
 namespace ad {
 
+static thread_local Profiler* g_prof = nullptr;
+void set_profiler(Profiler* p) { g_prof = p; }
+ProfLaunch::ProfLaunch(const char* name, double flops, double bytes, hipStream_t s) {
+  if (!g_prof || !g_prof->on) return;
+  hipEvent_t a = nullptr, b = nullptr;
+  if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+  (void)hipEventRecord(a, s);
+  g_prof->recs.push_back(ProfRec{name, flops, bytes, a, b});
+  stop_ = b;
+  s_ = s;
+}
+ProfLaunch::~ProfLaunch() {
+  if (stop_) (void)hipEventRecord(stop_, s_);
+}
+
 typedef __bf16 bf16;
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -236,6 +251,11 @@ static ad_status run_igemm(const IgemmParams& p0, hipStream_t s) {
   IgemmParams p = p0;
   p.tiles_n = (p.N + BN - 1) / BN;
   const int tiles_m = (p.M + BM - 1) / BM;
+  const char* name = sizeof(T) == 2 ? (BM == 128 ? "igemm_bf16_128x128" : "igemm_bf16_64x64")
+                                    : (BM == 128 ? "igemm_f32_128x128" : "igemm_f32_64x64");
+  const double in_bytes = (double)p.M * p.ctot * sizeof(T) * (p.stride == 2 ? 4 : 1) / (p.up ? 4 : 1);
+  const double out_cols = p.out_mode == OUT_GEGLU ? p.N / 2 : p.N;
+  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s);
   hipLaunchKernelGGL((k_igemm<T, BM, BN>), dim3(p.tiles_n * tiles_m), dim3(256), 0, s, p);
   AD_HIP(hipGetLastError());
   return AD_OK;
@@ -462,12 +482,15 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
   const float scale = 1.f / sqrtf((float)head_dim);
   if (dtype == AD_BF16 && head_dim == 64 && v_t) {
     if (ldv < round_up(lk, 64) || (ldq | ldk | ldv | ldo) % 8) AD_FAIL(AD_ERR_INVALID, "attention: MFMA path needs padded, 8-aligned strides");
+    ProfLaunch pl("attn_mfma_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s);
     hipLaunchKernelGGL(k_attn_mfma, dim3((l + 127) / 128, heads, batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
                        (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, scale * 1.44269504088896341f);
   } else if (dtype == AD_BF16) {
+    ProfLaunch pl("attn_simple_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s);
     hipLaunchKernelGGL(k_attn_simple<bf16>, dim3((l + 3) / 4, heads, batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
                        (const bf16*)v, v_t, (bf16*)out, l, lk, c, head_dim, ldq, ldk, ldv, ldo, scale);
   } else if (dtype == AD_F32) {
+    ProfLaunch pl("attn_simple_f32", 4.0 * batch * l * lk * c, 4.0 * batch * c * (2.0 * l + 2.0 * lk), s);
     hipLaunchKernelGGL(k_attn_simple<float>, dim3((l + 3) / 4, heads, batch), dim3(256), 0, s, (const float*)q, (const float*)k,
                        (const float*)v, v_t, (float*)out, l, lk, c, head_dim, ldq, ldk, ldv, ldo, scale);
   } else {
@@ -596,13 +619,23 @@ static ad_status run_groupnorm(const void* src0, const void* src1, int c0, int c
   const int ctot = c0 + c1, nchunk = gn_chunks(hw);
   float* partial = (float*)scratch;
   float* ss = partial + (size_t)batch * kGnMaxChunks * ctot * 2;
-  hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src0, c0, hw, nchunk, ctot, 0, partial);
-  if (c1) hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src1, c1, hw, nchunk, ctot, c0, partial);
-  hipLaunchKernelGGL(k_gn_finalize, dim3(groups, batch), dim3(64), 0, s, partial, nchunk, ctot, groups, hw, gamma, beta, eps, ss);
   const long long rows = (long long)batch * hw;
+  {
+    ProfLaunch pl("gn_partial", 0, (double)rows * c0 * sizeof(T), s);
+    hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src0, c0, hw, nchunk, ctot, 0, partial);
+  }
+  if (c1) {
+    ProfLaunch pl("gn_partial", 0, (double)rows * c1 * sizeof(T), s);
+    hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src1, c1, hw, nchunk, ctot, c0, partial);
+  }
+  {
+    ProfLaunch pl("gn_finalize", 0, 0, s);
+    hipLaunchKernelGGL(k_gn_finalize, dim3(groups, batch), dim3(64), 0, s, partial, nchunk, ctot, groups, hw, gamma, beta, eps, ss);
+  }
   const long long vecs = rows * (ctot / Vec<T>::N);
   int blocks = (int)((vecs + 255) / 256 < 8192 ? (vecs + 255) / 256 : 8192);
   if (blocks < 1) blocks = 1;
+  ProfLaunch pl("gn_apply", 0, 2.0 * rows * ctot * sizeof(T), s);
   hipLaunchKernelGGL(k_gn_apply<T>, dim3(blocks), dim3(256), 0, s, (const T*)src0, (const T*)src1, c0, c1, rows, hw, ss, silu, (T*)out);
   AD_HIP(hipGetLastError());
   return AD_OK;
@@ -668,6 +701,7 @@ ad_status launch_layernorm(int dtype, const void* src, int rows, int c, const fl
   if (!src || !gamma || !beta || !out) AD_FAIL(AD_ERR_INVALID, "layernorm: null pointer");
   const int vn = dtype == AD_BF16 ? 8 : 4;
   if (rows < 1 || c < vn || c % vn || c > 64 * 8 * vn) AD_FAIL(AD_ERR_INVALID, "layernorm: unsupported width %d", c);
+  ProfLaunch pl("layernorm", 0, 2.0 * rows * c * (dtype == AD_BF16 ? 2 : 4), s);
   if (dtype == AD_BF16)
     hipLaunchKernelGGL(k_layernorm<bf16>, dim3((rows + 3) / 4), dim3(256), 0, s, (const bf16*)src, rows, c, gamma, beta, eps, (bf16*)out);
   else if (dtype == AD_F32)
@@ -717,6 +751,7 @@ ad_status launch_linear_rows(int dtype, const float* in, int in_ld, int rows, in
   if (!in || !w || !out) AD_FAIL(AD_ERR_INVALID, "linear_rows: null pointer");
   const int vn = dtype == AD_BF16 ? 8 : 4;
   if (rows < 1 || rows > 16 || k < vn || k % vn || n < 1) AD_FAIL(AD_ERR_INVALID, "linear_rows: bad shape");
+  ProfLaunch pl("linear_rows", 2.0 * rows * n * k, (double)n * k * (dtype == AD_BF16 ? 2 : 4), s);
   if (dtype == AD_BF16)
     hipLaunchKernelGGL(k_linear_rows<bf16>, dim3((n + 3) / 4), dim3(256), 0, s, in, in_ld, rows, k, (const bf16*)w, bias, n, silu_in, silu_out, accumulate, out);
   else if (dtype == AD_F32)
@@ -738,6 +773,7 @@ __global__ void k_sinusoid(float tau, int dim, float* __restrict__ out) {
 
 ad_status launch_sinusoid(float tau, int dim, float* out, hipStream_t s) {
   if (!out || dim < 2 || dim % 2) AD_FAIL(AD_ERR_INVALID, "sinusoid: bad argument");
+  ProfLaunch pl("sinusoid", 0, 0, s);
   hipLaunchKernelGGL(k_sinusoid, dim3((dim / 2 + 63) / 64), dim3(64), 0, s, tau, dim, out);
   AD_HIP(hipGetLastError());
   return AD_OK;
@@ -768,6 +804,7 @@ ad_status launch_pack_latent(int dtype, const float* latent, float scale, int cl
   if (!latent || !out || cl < 1 || 9 * cl > kConvInK || h < 1 || w < 1 || batch < 1) AD_FAIL(AD_ERR_INVALID, "pack_latent: bad argument");
   const long long total = (long long)batch * h * w * kConvInK;
   const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+  ProfLaunch pl("pack_latent", 0, (double)total * (dtype == AD_BF16 ? 2 : 4), s);
   if (dtype == AD_BF16) hipLaunchKernelGGL(k_pack_latent<bf16>, dim3(blocks), dim3(256), 0, s, latent, scale, cl, h, w, batch, (bf16*)out);
   else hipLaunchKernelGGL(k_pack_latent<float>, dim3(blocks), dim3(256), 0, s, latent, scale, cl, h, w, batch, (float*)out);
   AD_HIP(hipGetLastError());
@@ -805,6 +842,7 @@ ad_status launch_sampler(float* x, const float* eps, size_t n, int batch, float 
   size_t blocks = (n / 4 + 255) / 256;
   if (blocks < 1) blocks = 1;
   if (blocks > 2048) blocks = 2048;
+  ProfLaunch pl("sampler", 0, (double)n * 4 * (2 + batch), s);
   hipLaunchKernelGGL(k_sampler, dim3((unsigned)blocks), dim3(256), 0, s, x, eps, n, batch, cx, ce, g);
   AD_HIP(hipGetLastError());
   return AD_OK;

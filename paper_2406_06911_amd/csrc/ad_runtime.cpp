@@ -1,6 +1,7 @@
 // Component runtime: weight upload, evaluation of one component (a contiguous unit range) on a
 // stream, and the round driver that runs the schedule table over the caller's streams with the
 // double-buffered stored states.
+#include <cstdio>
 #include <cstring>
 
 #include "ad_internal.h"
@@ -213,9 +214,46 @@ using namespace ad;
 
 extern "C" {
 
+static Profiler* prof_of(const Ctx& c) { return (Profiler*)c.profiler; }
+
+static void prof_clear(Profiler* p) {
+  for (ProfRec& r : p->recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  p->recs.clear();
+}
+
+ad_status ad_profile_enable(ad_ctx* ctx, int on) {
+  if (!ctx) AD_FAIL(AD_ERR_INVALID, "null argument");
+  Ctx& c = *C(ctx);
+  if (!c.profiler) c.profiler = new Profiler();
+  prof_of(c)->on = on != 0;
+  return AD_OK;
+}
+
+ad_status ad_profile_clear(ad_ctx* ctx) {
+  if (!ctx) AD_FAIL(AD_ERR_INVALID, "null argument");
+  if (C(ctx)->profiler) prof_clear(prof_of(*C(ctx)));
+  return AD_OK;
+}
+
+int ad_profile_count(const ad_ctx* ctx) { return (ctx && C(ctx)->profiler) ? (int)prof_of(*C(ctx))->recs.size() : 0; }
+
+ad_status ad_profile_get(const ad_ctx* ctx, int index, ad_profile_rec* out) {
+  if (!ctx || !out) AD_FAIL(AD_ERR_INVALID, "null argument");
+  const Ctx& c = *C(ctx);
+  if (!c.profiler || index < 0 || index >= (int)prof_of(c)->recs.size()) AD_FAIL(AD_ERR_INVALID, "record %d out of range", index);
+  const ProfRec& r = prof_of(c)->recs[index];
+  AD_HIP(hipEventSynchronize(r.stop));
+  float ms = 0.f;
+  AD_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
+  std::snprintf(out->kernel, sizeof(out->kernel), "%s", r.name);
+  out->flops = r.flops; out->bytes = r.bytes; out->ms = ms;
+  return AD_OK;
+}
+
 void ad_destroy(ad_ctx* ctx) {
   if (!ctx) return;
   Ctx* c = C(ctx);
+  if (c->profiler) { prof_clear(prof_of(*c)); delete prof_of(*c); }
   for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
   if (c->ev_pack) (void)hipEventDestroy(c->ev_pack);
   delete c;
@@ -313,7 +351,10 @@ ad_status ad_component_forward(ad_ctx* ctx, int comp, int lane, const void* cons
   bool needs_text = false;
   for (int i = cp.first; i <= cp.last; ++i) needs_text |= c.units[i].info.kind == AD_UNIT_TFM;
   if (needs_text && !text_emb) AD_FAIL(AD_ERR_INVALID, "text_emb is null");
-  return run_component(c, comp, lane, hidden_in, c.taus[t_index], latent_scale, text_emb, pooled_emb, hidden_out, (hipStream_t)stream);
+  set_profiler(prof_of(c));
+  ad_status st = run_component(c, comp, lane, hidden_in, c.taus[t_index], latent_scale, text_emb, pooled_emb, hidden_out, (hipStream_t)stream);
+  set_profiler(nullptr);
+  return st;
 }
 
 ad_status ad_ddim_update(ad_ctx* ctx, void* x, const void* eps, int step_index, float cfg_scale, ad_stream stream) {
@@ -324,7 +365,10 @@ ad_status ad_ddim_update(ad_ctx* ctx, void* x, const void* eps, int step_index, 
   double cx, ce, s0, s1;
   sampler_coeffs(c, step_index, &cx, &ce, &s0, &s1);
   const size_t n = (size_t)c.cfg.latent_channels * c.cfg.height * c.cfg.width;
-  return launch_sampler((float*)x, (const float*)eps, n, c.cfg.batch, (float)cx, (float)ce, cfg_scale, (hipStream_t)stream);
+  set_profiler(prof_of(c));
+  ad_status st = launch_sampler((float*)x, (const float*)eps, n, c.cfg.batch, (float)cx, (float)ce, cfg_scale, (hipStream_t)stream);
+  set_profiler(nullptr);
+  return st;
 }
 
 ad_status ad_get_slot_tensor(const ad_ctx* ctx, int slot, int unit, void** ptr, size_t* bytes) {
@@ -362,6 +406,7 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
     if (steps_done) *steps_done = c.steps_done;
     return AD_ERR_DONE;
   }
+  struct ProfGuard { ProfGuard(Profiler* p) { set_profiler(p); } ~ProfGuard() { set_profiler(nullptr); } } guard(prof_of(c));
   const int max_par = c.N + c.stride - 1;
   const int ns = n_streams < max_par ? n_streams : max_par;
   // events: [0..ns) end-of-round per stream, [ns..2ns) scratch for this round

@@ -1,0 +1,247 @@
+"""Kernel-level parity: every HIP kernel against the oracle's plain definition, through the C ABI."""
+import ctypes as C
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as SI
+from gpu_util import (DEV, TOL, dev, dev_bytes, dev_f32, host, nchw_to_nhwc, nhwc_to_nchw, p, quantize, rel_l2, stream_ptr, tdtype)
+from oracle import primitives as P
+from oracle import sampler as SM
+from paper_2406_06911_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+lib = B.lib
+DT = [B.AD_F32, B.AD_BF16]
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------------------------------
+def run_conv(dtype, x0, x1, w, bias, stride=1, up=0, rowvec=None, residual=None, mode=B.OUT_ROWMAJOR, geglu=False):
+    """x0/x1 NCHW float arrays (already quantised); returns the device result as float64 array."""
+    n, c0, hs, ws = x0.shape
+    c1 = x1.shape[1] if x1 is not None else 0
+    k = w.shape[2]
+    n_out = w.shape[0]
+    d0 = dev(nchw_to_nhwc(x0), dtype)
+    d1 = dev(nchw_to_nhwc(x1), dtype) if x1 is not None else None
+    wp = dev_bytes(B.pack_conv_weight(dtype, w, geglu))
+    nb = (n_out + 127) // 128 * 128
+    bpad = np.zeros(nb, np.float32)
+    if bias is not None:
+        bb = np.asarray(bias, np.float32)
+        if geglu:
+            half = n_out // 2
+            idx = [(r // 64) * 32 + r % 64 if r % 64 < 32 else half + (r // 64) * 32 + r % 64 - 32 for r in range(n_out)]
+            bb = bb[idx]
+        bpad[:n_out] = bb
+    db = dev_f32(bpad) if bias is not None else None
+    hin, win = hs << up, ws << up
+    pad = k // 2
+    ho, wo = (hin + 2 * pad - k) // stride + 1, (win + 2 * pad - k) // stride + 1
+    drow = dev_f32(rowvec) if rowvec is not None else None
+    dres = dev(residual, dtype) if residual is not None else None
+    if mode == B.OUT_ROWMAJOR:
+        out = torch.full((n, ho, wo, n_out), float("nan"), device=DEV, dtype=tdtype(dtype))
+        ld_t = 0
+    elif mode == B.OUT_GEGLU:
+        out = torch.full((n, ho, wo, n_out // 2), float("nan"), device=DEV, dtype=tdtype(dtype))
+        ld_t = 0
+    else:
+        ld_t = (ho * wo + 63) // 64 * 64
+        out = torch.full((n, n_out, ld_t), float("nan"), device=DEV, dtype=tdtype(dtype) if mode == B.OUT_TRANSPOSED else torch.float32)
+    B.check(lib.ad_conv_forward(dtype, p(d0), p(d1), c0, c1, n, hs, ws, up, k, stride, p(wp), n_out, p(db), p(drow), p(dres),
+                                p(out), mode, ld_t, stream_ptr()))
+    sync()
+    return host(out), (ho, wo)
+
+
+CONV_CASES = [
+    # name, batch, c0, c1, hs, ws, n_out, k, stride, up
+    ("3x3_multi_tile_ragged", 2, 64, 0, 13, 11, 192, 3, 1, 0),
+    ("3x3_stride2", 2, 64, 0, 12, 10, 64, 3, 2, 0),
+    ("3x3_upsampled", 1, 64, 0, 7, 9, 128, 3, 1, 1),
+    ("3x3_concat", 2, 64, 128, 9, 9, 64, 3, 1, 0),
+    ("1x1_concat", 2, 128, 64, 10, 9, 320, 1, 1, 0),
+    ("3x3_small_n", 2, 64, 0, 8, 8, 4, 3, 1, 0),
+    ("3x3_big_tiles", 2, 64, 0, 96, 96, 320, 3, 1, 0),
+]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("case", CONV_CASES, ids=[c[0] for c in CONV_CASES])
+def test_conv_matches_direct_summation(dtype, case):
+    name, n, c0, c1, hs, ws, n_out, k, stride, up = case
+    x0 = quantize(SI.make_array((n, c0, hs, ws), 11), dtype)
+    x1 = quantize(SI.make_array((n, c1, hs, ws), 12), dtype) if c1 else None
+    w = quantize(SI.make_array((n_out, c0 + c1, k, k), 13, 0.05), dtype)
+    bias = SI.make_array((n_out,), 14, 0.1)
+    got, (ho, wo) = run_conv(dtype, x0, x1, w, bias, stride, up)
+    xin = x0 if x1 is None else np.concatenate([x0, x1], 1)
+    if up:
+        xin = P.upsample_nearest2x(xin)
+    if name == "3x3_big_tiles":
+        # full size of the first level of the 768px model: compare sampled outputs computed one by one
+        rng = np.random.default_rng(5)
+        xp = np.pad(xin.astype(np.float64), ((0, 0), (0, 0), (1, 1), (1, 1)))
+        errs, refs = [], []
+        for _ in range(400):
+            b, o, i, j = int(rng.integers(n)), int(rng.integers(n_out)), int(rng.integers(ho)), int(rng.integers(wo))
+            ref = bias[o] + float(np.sum(w[o].astype(np.float64) * xp[b, :, i:i + 3, j:j + 3]))
+            errs.append(got[b, i, j, o] - ref); refs.append(ref)
+        assert np.linalg.norm(errs) / np.linalg.norm(refs) < TOL[dtype]
+        return
+    ref = P.conv2d(xin, w, bias, stride=stride)
+    assert got.shape == (n, ho, wo, n_out)
+    assert rel_l2(nhwc_to_nchw(got), ref) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_conv_epilogues(dtype):
+    n, c, h, wd, n_out = 2, 64, 9, 7, 192
+    x = quantize(SI.make_array((n, c, h, wd), 21), dtype)
+    w = quantize(SI.make_array((n_out, c, 3, 3), 22, 0.05), dtype)
+    bias = SI.make_array((n_out,), 23, 0.1)
+    rowvec = SI.make_array((n, n_out), 24)
+    res = quantize(SI.make_array((n, h, wd, n_out), 25), dtype)
+    got, _ = run_conv(dtype, x, None, w, bias, rowvec=rowvec, residual=res)
+    ref = P.conv2d(x, w, bias) + rowvec[:, :, None, None] + nhwc_to_nchw(res)
+    assert rel_l2(nhwc_to_nchw(got), ref) < TOL[dtype]
+    # transposed outputs (storage dtype and fp32)
+    for mode in (B.OUT_TRANSPOSED, B.OUT_TRANSPOSED_F32):
+        got, (ho, wo) = run_conv(dtype, x, None, w, bias, mode=mode)
+        ref = P.conv2d(x, w, bias).reshape(n, n_out, ho * wo)
+        assert rel_l2(got[:, :, :ho * wo], ref) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_linear_and_geglu(dtype):
+    rows, cin, cff = 200, 64, 256                      # GEGLU: 64 -> 2*256, value * gelu(gate)
+    x = quantize(SI.make_array((1, cin, rows, 1), 31), dtype)
+    w1 = quantize(SI.make_array((2 * cff, cin), 32, 0.2), dtype)
+    b1 = SI.make_array((2 * cff,), 33, 0.1)
+    got, _ = run_conv(dtype, x, None, w1[:, :, None, None], b1, mode=B.OUT_GEGLU, geglu=True)
+    tok = x[0, :, :, 0].T
+    hcat = P.linear(tok, w1, b1)
+    ref = hcat[:, :cff] * P.gelu(hcat[:, cff:])
+    assert rel_l2(got.reshape(rows, cff), ref) < TOL[dtype]
+    w2 = quantize(SI.make_array((96, cin), 34, 0.2), dtype)
+    got, _ = run_conv(dtype, x, None, w2[:, :, None, None], None)
+    assert rel_l2(got.reshape(rows, 96), P.linear(tok, w2)) < TOL[dtype]
+
+
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("shape", [(2, 64, 0, 16, 16, 8, 1), (2, 320, 0, 24, 24, 32, 1), (1, 64, 32, 9, 7, 8, 0),
+                                   (2, 640, 320, 12, 12, 32, 1), (2, 2560, 0, 6, 6, 32, 1)])
+def test_groupnorm_silu(dtype, shape):
+    n, c0, c1, h, w, groups, silu = shape
+    x0 = quantize(SI.make_array((n, c0, h, w), 41) * 2 + 0.5, dtype)
+    x1 = quantize(SI.make_array((n, c1, h, w), 42) - 1.0, dtype) if c1 else None
+    gam, bet = 1 + SI.make_array((c0 + c1,), 43, 0.3), SI.make_array((c0 + c1,), 44, 0.3)
+    d0 = dev(nchw_to_nhwc(x0), dtype)
+    d1 = dev(nchw_to_nhwc(x1), dtype) if c1 else None
+    out = torch.full((n, h, w, c0 + c1), float("nan"), device=DEV, dtype=tdtype(dtype))
+    scratch = torch.zeros(lib.ad_groupnorm_scratch_bytes(n, h * w, c0 + c1), dtype=torch.uint8, device=DEV)
+    dg, dbt = dev_f32(gam), dev_f32(bet)
+    B.check(lib.ad_groupnorm_forward(dtype, p(d0), p(d1), c0, c1, n, h * w, groups, p(dg), p(dbt), 1e-5, silu, p(out), p(scratch), stream_ptr()))
+    sync()
+    xin = x0 if x1 is None else np.concatenate([x0, x1], 1)
+    ref = P.group_norm(xin, groups, gam, bet, 1e-5)
+    if silu:
+        ref = P.silu(ref)
+    assert rel_l2(nhwc_to_nchw(host(out)), ref) < (1e-5 if dtype == B.AD_F32 else 5e-3)
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("rows,c", [(7, 64), (300, 320), (33, 1280)])
+def test_layernorm(dtype, rows, c):
+    x = quantize(SI.make_array((rows, c), 51) * 3 + 1, dtype)
+    gam, bet = 1 + SI.make_array((c,), 52, 0.3), SI.make_array((c,), 53, 0.3)
+    dx, out = dev(x, dtype), torch.full((rows, c), float("nan"), device=DEV, dtype=tdtype(dtype))
+    dg, dbt = dev_f32(gam), dev_f32(bet)
+    B.check(lib.ad_layernorm_forward(dtype, p(dx), rows, c, p(dg), p(dbt), 1e-5, p(out), stream_ptr()))
+    sync()
+    assert rel_l2(host(out), P.layer_norm(x, gam, bet, 1e-5)) < (1e-5 if dtype == B.AD_F32 else 5e-3)
+
+
+# ---------------------------------------------------------------------------------------------------
+def run_attention(dtype, q, k, v, heads, transposed):
+    bsz, l, c = q.shape
+    lk = k.shape[1]
+    d = c // heads
+    dq, dk = dev(q, dtype), dev(k, dtype)
+    if transposed:
+        ldv = (lk + 63) // 64 * 64
+        vt = np.full((bsz, c, ldv), np.nan, np.float32)          # the pad must never be read as data
+        vt[:, :, :lk] = np.transpose(v, (0, 2, 1))
+        dv = dev(vt, dtype)
+    else:
+        ldv = c
+        dv = dev(v, dtype)
+    out = torch.full((bsz, l, c), float("nan"), device=DEV, dtype=tdtype(dtype))
+    B.check(lib.ad_attention_forward(dtype, p(dq), p(dk), p(dv), int(transposed), bsz, l, lk, c, d, c, c, ldv, c, p(out), stream_ptr()))
+    sync()
+    return host(out)
+
+
+ATT_CASES = [
+    # dtype, batch, l, lk, heads, d, transposed
+    (B.AD_F32, 1, 64, 64, 4, 16, False), (B.AD_F32, 2, 37, 8, 2, 16, False), (B.AD_F32, 1, 70, 130, 1, 64, False),
+    (B.AD_BF16, 2, 37, 77, 2, 16, False), (B.AD_BF16, 1, 20, 77, 1, 128, True),
+    (B.AD_BF16, 2, 200, 200, 3, 64, True), (B.AD_BF16, 2, 144, 77, 2, 64, True), (B.AD_BF16, 1, 576, 576, 5, 64, True),
+    (B.AD_BF16, 1, 130, 1, 1, 64, True),
+]
+
+
+@pytest.mark.parametrize("case", ATT_CASES, ids=[f"{'bf16' if c[0] else 'f32'}_l{c[2]}_lk{c[3]}_h{c[4]}_d{c[5]}_{'vt' if c[6] else 'v'}" for c in ATT_CASES])
+def test_attention(case):
+    dtype, bsz, l, lk, heads, d, tr = case
+    c = heads * d
+    q, k, v = (quantize(SI.make_array(s, sd), dtype) for s, sd in (((bsz, l, c), 61), ((bsz, lk, c), 62), ((bsz, lk, c), 63)))
+    got = run_attention(dtype, q, k, v, heads, tr)
+    assert rel_l2(got, P.attention(q, k, v, heads)) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,tr", [(B.AD_F32, False), (B.AD_BF16, True)])
+def test_attention_peaky_softmax(dtype, tr):
+    """Scores far from uniform (scaled q, k) so that a mistake in the running max / rescaling shows."""
+    bsz, l, lk, heads, d = 1, 96, 200, 2, 64
+    c = heads * d
+    q = quantize(SI.make_array((bsz, l, c), 71) * 3, dtype)
+    k = quantize(SI.make_array((bsz, lk, c), 72) * 3, dtype)
+    v = quantize(SI.make_array((bsz, lk, c), 73), dtype)
+    # put the dominant key of some queries in the last tile so that the maximum moves late
+    k[0, lk - 1] = q[0, 5] * 0.5
+    got = run_attention(dtype, q, k, v, heads, tr)
+    ref = P.attention(q, k, v, heads)
+    assert rel_l2(got, ref) < TOL[dtype]
+    pmax = P.softmax_rows(q[0, :, :d] @ k[0, :, :d].T / math.sqrt(d)).max(axis=1)
+    assert np.median(pmax) > 0.5
+
+
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("batch", [1, 2])
+def test_sampler_update(batch):
+    T, n = 50, 4 * 24 * 24
+    taus, acp = SM.timesteps(T), SM.alphas_cumprod()
+    x = SI.make_array((n,), 81)
+    eps = SI.make_array((batch, n), 82)
+    for i, sampler in [(0, B.AD_DDIM), (17, B.AD_DDIM), (49, B.AD_DDIM), (3, B.AD_EULER)]:
+        e = SM.cfg_combine(eps.astype(np.float64), 7.5)
+        if sampler == B.AD_DDIM:
+            ref = SM.ddim_step(x, e, i, taus, acp)
+            a, a2 = acp[taus[i]], (acp[taus[i + 1]] if i + 1 < T else 1.0)
+            cx, ce = math.sqrt(a2 / a), math.sqrt(1 - a2) - math.sqrt(a2) * math.sqrt(1 - a) / math.sqrt(a)
+        else:
+            ref = SM.euler_step(x, e, i, taus, acp)
+            cx, ce = 1.0, SM.sigma(i + 1, taus, acp) - SM.sigma(i, taus, acp)
+        dx, de = dev_f32(x), dev_f32(eps)
+        B.check(lib.ad_sampler_update_raw(p(dx), p(de), n, batch, cx, ce, 7.5, stream_ptr()))
+        sync()
+        assert rel_l2(host(dx), ref) < 1e-6
