@@ -38,6 +38,7 @@ def main():
     ap.add_argument("--config", default="sd21_768")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams for the timed region (0 = one per concurrent evaluation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--shapes", action="store_true", help="print the per-shape GEMM/attention timings of the instrumented round to stderr")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the N components on ONE GPU (separate HIP streams); --gpus must be 1", file=sys.stderr)
@@ -114,7 +115,11 @@ def main():
     recs = m.profile_records()
     m.profile(False)
     agg = {}
-    for name, fl, by, ms in recs:
+    shapes = {}
+    for name, fl, by, ms, mnk in recs:
+        if mnk[0]:
+            sh = shapes.setdefault((name,) + tuple(mnk), [0, 0.0, 0.0])
+            sh[0] += 1; sh[1] += ms; sh[2] += fl
         a = agg.setdefault(name, dict(calls=0, ms=0.0, flops=0.0, bytes=0.0))
         a["calls"] += 1; a["ms"] += ms; a["flops"] += fl; a["bytes"] += by
     kernels = {}
@@ -127,6 +132,9 @@ def main():
             e["gbs"] = round(a["bytes"] / (a["ms"] * 1e-3) / 1e9, 1)
             e["frac_hbm_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
         kernels[name] = e
+    if args.shapes:
+        for key, (cnt, ms, fl) in sorted(shapes.items(), key=lambda kv: -kv[1][1]):
+            log(f"{key[0]:22s} M={key[1]:6d} N={key[2]:5d} K={key[3]:6d} calls={cnt:3d} total_ms={ms:8.3f} avg_us={ms / cnt * 1e3:8.1f} TFLOP/s={fl / (ms * 1e-3) / 1e12:7.1f}")
     dom = max(agg.items(), key=lambda kv: kv[1]["ms"])
     dname, da = dom
     if da["flops"] > 0:

@@ -203,6 +203,7 @@ typedef struct ad_profile_rec {
   double flops;     /* algorithmic floating-point operations of the launch (2 per multiply-accumulate) */
   double bytes;     /* algorithmic HBM bytes of the launch (operands read once, results written once) */
   float ms;         /* duration between the two events */
+  int m, n, k;      /* GEMM view of the launch (attention: queries, keys, channels); 0 otherwise */
 } ad_profile_rec;
 ad_status ad_profile_enable(ad_ctx* ctx, int on);
 ad_status ad_profile_clear(ad_ctx* ctx);
@@ -218,11 +219,18 @@ ad_status ad_profile_get(const ad_ctx* ctx, int index, ad_profile_rec* out); /* 
  *   ksize 1|3, stride 1|2, padding ksize/2;  w_packed: weights as produced by ad_pack_conv_weight;
  *   bias fp32 [n] or NULL; rowvec fp32 [batch][n] or NULL; residual [m][n] or NULL;
  *   out_mode 0: [m][n] dtype; 1: GEGLU (weights packed with geglu=1) -> [m][n/2]; 2: transposed
- *   [batch][n][ld_t] in dtype; 3: transposed fp32 [batch][n][ld_t]. */
+ *   [batch][n][ld_t] in dtype; 3: transposed fp32 [batch][n][ld_t].
+ *   splitk_ws: optional fp32 scratch of splitk_bytes (ad_conv_workspace_bytes); with it, GEMMs with few output
+ *   tiles and a long K are split along K and reduced in a second kernel (fixed summation order). */
+size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n_out, int c_in_total, int ksize, int out_mode);
 ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hs, int ws,
                           int up, int ksize, int stride, const void* w_packed, int n_out, const float* bias,
                           const float* rowvec, const void* residual, void* out, int out_mode, int ld_t,
-                          ad_stream stream);
+                          void* splitk_ws, size_t splitk_bytes, ad_stream stream);
+/* Tuning knob for measurements: forces the block tile of ad_conv_forward and of every convolution / linear
+ * layer of the process (0: 256x128, 1: 128x128, 2: 128x64, 3: 64x64, -1: automatic choice, the default).
+ * Results are the same up to rounding order. */
+ad_status ad_tune_conv_tile(int tile);
 /* Packs HOST fp32 weights [n_out][c_in][k][k] into the kernel layout (HOST out, dtype elements).
  * Returns the packed size in bytes through *bytes when out == NULL. */
 ad_status ad_pack_conv_weight(int dtype, const float* w, int n_out, int c_in, int ksize, int geglu, void* out, size_t* bytes);

@@ -62,7 +62,7 @@ class SchedRow(C.Structure):
 
 
 class ProfileRec(C.Structure):
-    _fields_ = [("kernel", C.c_char * 32), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float)]
+    _fields_ = [("kernel", C.c_char * 32), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float), ("m", C.c_int), ("n", C.c_int), ("k", C.c_int)]
 
 
 EXPORTS = [
@@ -70,8 +70,8 @@ EXPORTS = [
     "ad_tensor_shape", "ad_num_weights", "ad_get_weight", "ad_device_bytes", "ad_bind_device_memory", "ad_load_weights",
     "ad_reset", "ad_get_timesteps", "ad_num_sched_rows", "ad_get_schedule", "ad_get_sampler_coeffs",
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
-    "ad_conv_forward", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
-    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get",
+    "ad_conv_forward", "ad_conv_workspace_bytes", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
+    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile",
 ]
 
 
@@ -106,12 +106,14 @@ def _load():
     L.ad_sampler_update_raw.argtypes = [vp, vp, sz, ci, cf, cf, cf, vp]
     L.ad_get_slot_tensor.argtypes = [vp, ci, ci, P(vp), P(sz)]
     L.ad_get_eps_buffer.argtypes = [vp, ci, P(vp), P(sz)]
-    L.ad_conv_forward.argtypes = [ci, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp, ci, ci, vp]
+    L.ad_conv_forward.argtypes = [ci, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp, ci, ci, vp, sz, vp]
+    L.ad_conv_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci]; L.ad_conv_workspace_bytes.restype = sz
     L.ad_pack_conv_weight.argtypes = [ci, vp, ci, ci, ci, ci, vp, P(sz)]
     L.ad_groupnorm_scratch_bytes.argtypes = [ci, ci, ci]; L.ad_groupnorm_scratch_bytes.restype = sz
     L.ad_groupnorm_forward.argtypes = [ci, vp, vp, ci, ci, ci, ci, ci, vp, vp, cf, ci, vp, vp, vp]
     L.ad_layernorm_forward.argtypes = [ci, vp, ci, ci, vp, vp, cf, vp, vp]
     L.ad_attention_forward.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
+    L.ad_tune_conv_tile.argtypes = [ci]
     L.ad_profile_enable.argtypes = [vp, ci]
     L.ad_profile_clear.argtypes = [vp]
     L.ad_profile_count.argtypes = [vp]
@@ -260,7 +262,7 @@ class AsyncDiff:
         r = ProfileRec()
         for i in range(lib.ad_profile_count(self._h)):
             check(lib.ad_profile_get(self._h, i, C.byref(r)))
-            out.append((r.kernel.decode(), r.flops, r.bytes, r.ms))
+            out.append((r.kernel.decode(), r.flops, r.bytes, r.ms, (r.m, r.n, r.k)))
         if clear:
             check(lib.ad_profile_clear(self._h))
         return out

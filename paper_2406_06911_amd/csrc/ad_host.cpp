@@ -8,6 +8,7 @@
 #include <limits>
 
 #include "ad_internal.h"
+#include "ad_kernels.h"
 
 namespace ad {
 
@@ -379,13 +380,18 @@ static void plan_work(Ctx& c) {
       const ad_unit_info& u = c.units[ui].info;
       const size_t B = g.batch;
       const size_t m_in = B * u.h_in * u.w_in, m_out = B * u.h_out * u.w_out;
+      auto gemm = [&](size_t m, int n, int k, int mode = OUT_ROWMAJOR) { want(9, conv_workspace_bytes(g.dtype, (long long)m, n, k, mode)); };
       switch (u.kind) {
         case AD_UNIT_CONV_IN: want(0, m_out * kConvInK * es); break;
-        case AD_UNIT_OUT: want(0, m_in * u.c_in * es); break;
+        case AD_UNIT_DOWN: case AD_UNIT_UP: gemm(m_out, u.c_out, 9 * u.c_in); break;
+        case AD_UNIT_OUT: want(0, m_in * u.c_in * es); gemm(m_out, u.c_out, 9 * u.c_in); break;
         case AD_UNIT_RES:
           want(0, m_in * std::max(u.c_in + u.c_skip, u.c_out) * es);
           want(1, m_out * u.c_out * es);
           want(2, m_out * u.c_out * es);
+          gemm(m_out, u.c_out, 9 * (u.c_in + u.c_skip));
+          gemm(m_out, u.c_out, 9 * u.c_out);
+          gemm(m_out, u.c_out, u.c_in + u.c_skip);
           break;
         case AD_UNIT_TFM: {
           const size_t L = (size_t)u.h_in * u.w_in, C = u.c_in;
@@ -395,6 +401,9 @@ static void plan_work(Ctx& c) {
           want(6, m_in * 4 * C * es);
           want(7, B * g.ctx_len * C * es);
           want(8, B * C * lkp * es);
+          gemm(m_in, (int)C, (int)C);
+          gemm(m_in, (int)C, (int)(4 * C));
+          gemm(B * g.ctx_len, (int)C, g.ctx_dim);
           break;
         }
         default: break;

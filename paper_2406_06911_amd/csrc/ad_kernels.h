@@ -13,6 +13,7 @@ struct ProfRec {
   double flops;      // algorithmic floating-point operations of the launch
   double bytes;      // algorithmic HBM bytes of the launch
   hipEvent_t start, stop;
+  int m = 0, n = 0, k = 0;   // GEMM view of the launch (attention: queries, keys, channels), else 0
 };
 struct Profiler {
   bool on = false;
@@ -20,7 +21,7 @@ struct Profiler {
 };
 void set_profiler(Profiler* p);   // per host thread; nullptr removes it
 struct ProfLaunch {
-  ProfLaunch(const char* name, double flops, double bytes, hipStream_t s);
+  ProfLaunch(const char* name, double flops, double bytes, hipStream_t s, int m = 0, int n = 0, int k = 0);
   ~ProfLaunch();
   hipEvent_t stop_ = nullptr;
   hipStream_t s_ = nullptr;
@@ -38,10 +39,15 @@ struct ConvArgs {
   const float* bias; const float* rowvec; int rowvec_ld;   // rowvec [batch][rowvec_ld]
   const void* residual;
   void* out; int out_mode; int ld_t;
+  void* splitk_ws = nullptr;            // fp32 scratch for split-K partial sums (optional)
+  size_t splitk_bytes = 0;
 };
 enum { OUT_ROWMAJOR = 0, OUT_GEGLU = 1, OUT_TRANSPOSED = 2, OUT_TRANSPOSED_F32 = 3 };
 
 ad_status launch_conv(const ConvArgs& a, hipStream_t s);
+void set_tile_override(int tile);   // -1 = choose automatically
+// scratch a convolution of this shape wants for split-K (0 = it will not split); k = taps * channels
+size_t conv_workspace_bytes(int dtype, long long m, int n, int k, int out_mode);
 
 ad_status launch_groupnorm(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw, int groups,
                            const float* gamma, const float* beta, float eps, int silu, void* out, void* scratch,

@@ -10,16 +10,18 @@
 //   k_sampler      guidance combination + DDIM / Euler latent update
 #include "ad_kernels.h"
 
+#include <algorithm>
+
 namespace ad {
 
 static thread_local Profiler* g_prof = nullptr;
 void set_profiler(Profiler* p) { g_prof = p; }
-ProfLaunch::ProfLaunch(const char* name, double flops, double bytes, hipStream_t s) {
+ProfLaunch::ProfLaunch(const char* name, double flops, double bytes, hipStream_t s, int m, int n, int k) {
   if (!g_prof || !g_prof->on) return;
   hipEvent_t a = nullptr, b = nullptr;
   if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
   (void)hipEventRecord(a, s);
-  g_prof->recs.push_back(ProfRec{name, flops, bytes, a, b});
+  g_prof->recs.push_back(ProfRec{name, flops, bytes, a, b, m, n, k});
   stop_ = b;
   s_ = s;
 }
@@ -84,6 +86,9 @@ struct IgemmParams {
   int M, N, Kp, tiles_n, ktiles;
   const void* w; const float* bias; const float* rowvec; const void* residual;
   void* out; int out_mode; int ld_t; int rowvec_ld;
+  unsigned bytes0, bytes1, bytes_w;   // sizes of the two sources and of the packed weights
+  int kt_per_split;                   // k-tiles handled by one workgroup along grid.y (split-K), else ktiles
+  float* partial;                     // split-K: fp32 partial sums [splits][M][N]; nullptr otherwise
 };
 
 constexpr int kPitch = kRowBytes + 16;   // LDS row pitch in bytes
@@ -102,24 +107,41 @@ template <> struct Mma<float> {
   }
 };
 
-template <typename T, int BM, int BN>
+// 16-byte loads through a buffer resource: lanes whose offset is kOob (beyond num_records) read zeros
+// without touching memory, which is how padding taps and rows past M are produced without branches.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr unsigned kOob = 0x80000000u;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+template <typename V>
+__device__ __forceinline__ V buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned voffset, unsigned soffset) {
+  const u32x4 raw = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voffset, (int)soffset, 0);
+  return __builtin_bit_cast(V, raw);
+}
+
+template <typename T, int BM, int BN, int WGM, int WGN, int NSET>
 __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
   typedef typename Vec<T>::type V;
-  constexpr int VN = Vec<T>::N;
   constexpr int BK = kRowBytes / (int)sizeof(T);
-  constexpr int TM = BM / 64, TN = BN / 64;
-  constexpr int AV = BM / 32, BV = BN / 32;     // 16-byte vectors per thread per k-tile
-  __shared__ __attribute__((aligned(16))) char lds[(BM + BN) * kPitch];
-  char* As = lds;
-  char* Bs = lds + BM * kPitch;
+  constexpr int ES = (int)sizeof(T);
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wavefront tile
+  constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 MFMA tiles per wavefront
+  constexpr int AV = BM / 32, BV = BN / 32;      // 16-byte vectors per thread per k-tile
+  constexpr int STAGE = (BM + BN) * kPitch;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int wave_m = wave >> 1, wave_n = wave & 1;
+  const int wave_m = wave / WGN, wave_n = wave % WGN;
   const int tile = xcd_remap(blockIdx.x, gridDim.x);
   const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
 
-  // per-thread A rows: row = tid/8 + 32 i, 16-byte column = tid%8
+  const __amdgpu_buffer_rsrc_t rs0 = make_rsrc(p.src0, p.bytes0);
+  const __amdgpu_buffer_rsrc_t rs1 = make_rsrc(p.src1, p.bytes1);
+  const __amdgpu_buffer_rsrc_t rsw = make_rsrc(p.w, p.bytes_w);
+
+  // per-thread rows of the A tile: row = tid/8 + 32 i, 16-byte column = tid%8
   const int vcol = tid & 7, vrow = tid >> 3;
   int a_iy0[AV], a_ix0[AV], a_b[AV];
 #pragma unroll
@@ -128,41 +150,64 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
     if (m < p.M) {
       const int b = m / p.hw_out, r = m - b * p.hw_out;
       const int oy = r / p.wout, ox = r - oy * p.wout;
-      a_b[i] = b; a_iy0[i] = oy * p.stride - p.pad; a_ix0[i] = ox * p.stride - p.pad;
+      a_b[i] = b * p.hs; a_iy0[i] = oy * p.stride - p.pad; a_ix0[i] = ox * p.stride - p.pad;
     } else {
       a_b[i] = -1; a_iy0[i] = 0; a_ix0[i] = 0;
     }
   }
-  const T* wbase = (const T*)p.w + (size_t)(n0 + vrow) * p.Kp + vcol * VN;
+  unsigned b_off[BV];
+#pragma unroll
+  for (int i = 0; i < BV; ++i) b_off[i] = (unsigned)((n0 + vrow + 32 * i) * p.Kp + vcol * (16 / ES)) * ES;
 
-  V areg[AV], breg[BV];
-  auto fetch = [&](int kt) {
-    const int k0 = kt * BK;
-    const int tap = k0 / p.ctot, cc = k0 - tap * p.ctot;
+  // byte offsets of this thread's A vectors for the tap being fetched (kOob = reads zeros)
+  unsigned a_off0[AV], a_off1[AV];
+  auto set_tap = [&](int tap) {
     const int u = tap / p.ksize, v = tap - u * p.ksize;
-    const bool second = cc >= p.c0;
-    const T* src = (const T*)(second ? p.src1 : p.src0);
-    const int cs = second ? p.c1 : p.c0, coff = (second ? cc - p.c0 : cc) + vcol * VN;
 #pragma unroll
     for (int i = 0; i < AV; ++i) {
       const int iy = a_iy0[i] + u, ix = a_ix0[i] + v;
-      V val;
+      const bool ok = a_b[i] >= 0 && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
+      const unsigned pix = (unsigned)((a_b[i] + (iy >> p.up)) * p.ws + (ix >> p.up));
+      a_off0[i] = ok ? (pix * (unsigned)p.c0 + vcol * (16 / ES)) * ES : kOob;
+      a_off1[i] = ok ? (pix * (unsigned)p.c1 + vcol * (16 / ES)) * ES : kOob;
+    }
+  };
+
+  // NSET register sets hold the k-tiles in flight: a tile is requested NSET iterations before it is
+  // multiplied, which is what hides the latency of the memory system at the low occupancy these
+  // problem sizes allow.
+  V areg[NSET][AV], breg[NSET][BV];
+  // this workgroup's range of k-tiles (all of them unless the launch splits K along grid.y)
+  const int kt_begin = blockIdx.y * p.kt_per_split;
+  const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
+  int f_k0 = kt_begin * BK;              // position of the next k-tile to fetch
+  int f_tap = f_k0 / p.ctot, f_cc = f_k0 - f_tap * p.ctot;
+  set_tap(f_tap);
+  auto fetch = [&](V (&ar)[AV], V (&br)[BV]) {
+    if (f_cc < p.c0) {
 #pragma unroll
-      for (int e = 0; e < VN; ++e) val[e] = from_f<T>(0.f);
-      if (a_b[i] >= 0 && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win) {
-        const size_t pix = ((size_t)a_b[i] * p.hs + (iy >> p.up)) * p.ws + (ix >> p.up);
-        val = *(const V*)(src + pix * cs + coff);
-      }
-      areg[i] = val;
+      for (int i = 0; i < AV; ++i) ar[i] = buffer_load16<V>(rs0, a_off0[i], (unsigned)(f_cc * ES));
+    } else {
+#pragma unroll
+      for (int i = 0; i < AV; ++i) ar[i] = buffer_load16<V>(rs1, a_off1[i], (unsigned)((f_cc - p.c0) * ES));
     }
 #pragma unroll
-    for (int i = 0; i < BV; ++i) breg[i] = *(const V*)(wbase + (size_t)(32 * i) * p.Kp + k0);
+    for (int i = 0; i < BV; ++i) br[i] = buffer_load16<V>(rsw, b_off[i], (unsigned)(f_k0 * ES));
+    f_k0 += BK;
+    f_cc += BK;
+    if (f_cc >= p.ctot) {
+      f_cc = 0;
+      ++f_tap;
+      if (f_tap < p.ksize * p.ksize) set_tap(f_tap);
+    }
   };
-  auto stash = [&]() {
+  auto stash = [&](int stage, const V (&ar)[AV], const V (&br)[BV]) {
+    char* As = lds + stage * STAGE;
+    char* Bs = As + BM * kPitch;
 #pragma unroll
-    for (int i = 0; i < AV; ++i) *(V*)(As + (vrow + 32 * i) * kPitch + vcol * 16) = areg[i];
+    for (int i = 0; i < AV; ++i) *(V*)(As + (vrow + 32 * i) * kPitch + vcol * 16) = ar[i];
 #pragma unroll
-    for (int i = 0; i < BV; ++i) *(V*)(Bs + (vrow + 32 * i) * kPitch + vcol * 16) = breg[i];
+    for (int i = 0; i < BV; ++i) *(V*)(Bs + (vrow + 32 * i) * kPitch + vcol * 16) = br[i];
   };
 
   f32x16 acc[TM][TN];
@@ -173,53 +218,85 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  fetch(0);
-  stash();
+  // tile t travels in register set t % NSET; LDS stage t & 1 is written while stage (t-1) & 1 is multiplied
+  fetch(areg[0], breg[0]);
+  stash(0, areg[0], breg[0]);
+#pragma unroll
+  for (int t = 1; t <= NSET; ++t)
+    if (t < nkt) fetch(areg[t % NSET], breg[t % NSET]);
   __syncthreads();
-  const char* a_rd = As + (wave_m * (BM / 2) + l32) * kPitch + half * 16;
-  const char* b_rd = Bs + (wave_n * (BN / 2) + l32) * kPitch + half * 16;
-  for (int kt = 0; kt < p.ktiles; ++kt) {
-    if (kt + 1 < p.ktiles) fetch(kt + 1);
+  const int a_rd = (wave_m * WTM + l32) * kPitch + half * 16;
+  const int b_rd = BM * kPitch + (wave_n * WTN + l32) * kPitch + half * 16;
+  for (int kt0 = 0; kt0 < nkt; kt0 += NSET) {
 #pragma unroll
-    for (int ks = 0; ks < kRowBytes / 32; ++ks) {
-      V af[TM], bf[TN];
+    for (int u = 0; u < NSET; ++u) {
+      const int kt = kt0 + u;
+      if (kt >= nkt) break;
+      const char* st = lds + (kt & 1) * STAGE;
+      if (kt + 1 < nkt) {
+        stash((kt + 1) & 1, areg[(u + 1) % NSET], breg[(u + 1) % NSET]);
+        if (kt + 1 + NSET < nkt) fetch(areg[(u + 1) % NSET], breg[(u + 1) % NSET]);
+      }
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *(const V*)(a_rd + i * 32 * kPitch + ks * 32);
+      for (int ks = 0; ks < kRowBytes / 32; ++ks) {
+        V af[TM], bf[TN];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bf[j] = *(const V*)(b_rd + j * 32 * kPitch + ks * 32);
+        for (int i = 0; i < TM; ++i) af[i] = *(const V*)(st + a_rd + i * 32 * kPitch + ks * 32);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j) bf[j] = *(const V*)(st + b_rd + j * 32 * kPitch + ks * 32);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) Mma<T>::run(af[i], bf[j], acc[i][j]);
-    }
-    __syncthreads();
-    if (kt + 1 < p.ktiles) {
-      stash();
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) Mma<T>::run(af[i], bf[j], acc[i][j]);
+      }
       __syncthreads();
     }
   }
 
   // epilogue: lane holds column l32 of each 32x32 tile; register r is row 8*(r/4) + 4*half + r%4
-  const int row_base = m0 + wave_m * (BM / 2) + 4 * half;
-  const int col_base = n0 + wave_n * (BN / 2) + l32;
+  const int row_base = m0 + wave_m * WTM + 4 * half;
+  const int col_base = n0 + wave_n * WTN + l32;
+  if (p.partial) {
+    float* dst = p.partial + (size_t)blockIdx.y * p.M * p.N;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = col_base + j * 32;
+      if (col >= p.N) continue;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < p.M) dst[(size_t)row * p.N + col] = acc[i][j][r];
+        }
+    }
+    return;
+  }
   if (p.out_mode == OUT_GEGLU) {
-    if constexpr (TN == 2) {
+    if constexpr (TN % 2 == 0) {
       const int half_n = p.N >> 1;
-      const int oc = ((n0 + wave_n * (BN / 2)) >> 1) + l32;      // packed columns: 32 value, 32 gate
-      if (oc < half_n) {
-        const float bv = p.bias ? p.bias[col_base] : 0.f, bg = p.bias ? p.bias[col_base + 32] : 0.f;
+#pragma unroll
+      for (int j = 0; j < TN; j += 2) {
+        const int oc = ((n0 + wave_n * WTN + j * 32) >> 1) + l32;      // packed columns: 32 value, 32 gate
+        if (oc >= half_n) continue;
+        const int cv = col_base + j * 32;
+        const float bv = p.bias ? p.bias[cv] : 0.f, bg = p.bias ? p.bias[cv + 32] : 0.f;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
             if (row < p.M)
-              ((T*)p.out)[(size_t)row * half_n + oc] = from_f<T>((acc[i][0][r] + bv) * gelu_f(acc[i][1][r] + bg));
+              ((T*)p.out)[(size_t)row * half_n + oc] = from_f<T>((acc[i][j][r] + bv) * gelu_f(acc[i][j + 1][r] + bg));
           }
       }
     }
     return;
   }
+  const bool need_b = p.rowvec != nullptr || p.out_mode != OUT_ROWMAJOR;
+  const int b0 = need_b ? m0 / p.hw_out : 0;
+  const int bnd = (b0 + 1) * p.hw_out;
+  const bool one_step = p.hw_out >= BM;         // a tile then spans at most two samples
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int col = col_base + j * 32;
@@ -232,7 +309,8 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
         const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
         if (row >= p.M) continue;
         float v = acc[i][j][r] + bias;
-        const int b = row / p.hw_out;
+        int b = 0;
+        if (need_b) b = one_step ? b0 + (row >= bnd ? 1 : 0) : row / p.hw_out;
         if (p.rowvec) v += p.rowvec[(size_t)b * p.rowvec_ld + col];
         if (p.out_mode == OUT_ROWMAJOR) {
           if (p.residual) v += to_f(((const T*)p.residual)[(size_t)row * p.N + col]);
@@ -246,19 +324,91 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
   }
 }
 
-template <typename T, int BM, int BN>
-static ad_status run_igemm(const IgemmParams& p0, hipStream_t s) {
+template <typename T, int BM, int BN, int WGM, int WGN, int NSET>
+static ad_status run_igemm(const IgemmParams& p0, const char* name, hipStream_t s) {
   IgemmParams p = p0;
   p.tiles_n = (p.N + BN - 1) / BN;
   const int tiles_m = (p.M + BM - 1) / BM;
-  const char* name = sizeof(T) == 2 ? (BM == 128 ? "igemm_bf16_128x128" : "igemm_bf16_64x64")
-                                    : (BM == 128 ? "igemm_f32_128x128" : "igemm_f32_64x64");
+  constexpr int lds_bytes = 2 * (BM + BN) * kPitch;
+  static bool attr_set = false;     // LDS above 64 KiB has to be requested once per kernel
+  if (!attr_set) {
+    AD_HIP(hipFuncSetAttribute((const void*)k_igemm<T, BM, BN, WGM, WGN, NSET>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    attr_set = true;
+  }
   const double in_bytes = (double)p.M * p.ctot * sizeof(T) * (p.stride == 2 ? 4 : 1) / (p.up ? 4 : 1);
   const double out_cols = p.out_mode == OUT_GEGLU ? p.N / 2 : p.N;
-  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s);
-  hipLaunchKernelGGL((k_igemm<T, BM, BN>), dim3(p.tiles_n * tiles_m), dim3(256), 0, s, p);
+  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
+  const int splits = (p.ktiles + p.kt_per_split - 1) / p.kt_per_split;
+  hipLaunchKernelGGL((k_igemm<T, BM, BN, WGM, WGN, NSET>), dim3(p.tiles_n * tiles_m, splits), dim3(256), lds_bytes, s, p);
   AD_HIP(hipGetLastError());
   return AD_OK;
+}
+
+// Split-K second pass: sums the fp32 partials in a fixed order and applies the epilogue.
+template <typename T>
+__global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__ partial, int splits, int M, int N, int hw_out,
+                                                       const float* __restrict__ bias, const float* __restrict__ rowvec,
+                                                       int rowvec_ld, const T* __restrict__ residual, void* __restrict__ out,
+                                                       int out_mode, int ld_t) {
+  const int n4 = N / 4;
+  const long long total = (long long)M * n4;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+    const int row = (int)(i / n4), col = (int)(i - (long long)row * n4) * 4;
+    f32x4 v = *(const f32x4*)(partial + (size_t)row * N + col);
+    for (int z = 1; z < splits; ++z) v += *(const f32x4*)(partial + ((size_t)z * M + row) * N + col);
+    const int b = row / hw_out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float x = v[e];
+      if (bias) x += bias[col + e];
+      if (rowvec) x += rowvec[(size_t)b * rowvec_ld + col + e];
+      if (out_mode == OUT_ROWMAJOR) {
+        if (residual) x += to_f(residual[(size_t)row * N + col + e]);
+        ((T*)out)[(size_t)row * N + col + e] = from_f<T>(x);
+      } else {
+        const size_t o = ((size_t)b * N + col + e) * ld_t + (row - b * hw_out);
+        if (out_mode == OUT_TRANSPOSED) ((T*)out)[o] = from_f<T>(x);
+        else ((float*)out)[o] = x;
+      }
+    }
+  }
+}
+
+// Tile shapes: block tile BM x BN, wavefront grid WGM x WGN (4 wavefronts).
+enum { TILE_256x128 = 0, TILE_128x128 = 1, TILE_128x64 = 2, TILE_64x64 = 3, TILE_AUTO = -1 };
+static int g_tile_override = TILE_AUTO;
+
+static int choose_tile(long long m, int n, int out_mode) {
+  const bool geglu = out_mode == OUT_GEGLU;   // needs a value and a gate tile in the same wavefront
+  if (g_tile_override != TILE_AUTO && !(geglu && g_tile_override >= TILE_128x64)) return g_tile_override;
+  // Measured on the GEMM shapes of the SD-sized models (M <= 18432): the machine is far from full with
+  // large tiles, and the 64x64 tile (most workgroups, shortest dependent chain per k-tile) is fastest
+  // except for GEMMs wide enough to give 128x128 tiles at least two workgroups per CU.
+  const long long tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
+  int best = (geglu || tiles128 >= 1024) ? TILE_128x128 : TILE_64x64;
+  return best;
+}
+
+// Split-K: GEMMs with few output tiles and a long K (the deep levels of the UNet: M = 288 .. 1152,
+// K up to 23040) are cut along K so that a few hundred workgroups exist.
+static int choose_splits(long long m, int n, int ktiles, int out_mode, int tile) {
+  if (out_mode == OUT_GEGLU || n % 4) return 1;
+  const int bm = tile == TILE_64x64 ? 64 : (tile == TILE_256x128 ? 256 : 128);
+  const int bn = (tile == TILE_64x64 || tile == TILE_128x64) ? 64 : 128;
+  const long long tiles = ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
+  if (tiles >= 512 || ktiles < 16) return 1;
+  int splits = (int)((1024 + tiles - 1) / tiles);
+  if (splits > ktiles / 8) splits = ktiles / 8;
+  if (splits > 16) splits = 16;
+  if (splits < 2) return 1;
+  const int per = (ktiles + splits - 1) / splits;
+  return (ktiles + per - 1) / per;
+}
+
+size_t conv_workspace_bytes(int dtype, long long m, int n, int k, int out_mode) {
+  const int ktiles = k / bk_elems(dtype);
+  const int splits = choose_splits(m, n, ktiles, out_mode, choose_tile(m, n, out_mode));
+  return splits > 1 ? (size_t)splits * m * n * 4 : 0;
 }
 
 ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
@@ -288,12 +438,50 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   if (a.out_mode < OUT_ROWMAJOR || a.out_mode > OUT_TRANSPOSED_F32) AD_FAIL(AD_ERR_INVALID, "conv: bad out_mode");
   if (a.out_mode == OUT_GEGLU && (a.n_out % 64 || a.residual || a.rowvec)) AD_FAIL(AD_ERR_INVALID, "conv: bad GEGLU use");
   if (a.out_mode >= OUT_TRANSPOSED && (a.ld_t < p.hw_out || a.residual)) AD_FAIL(AD_ERR_INVALID, "conv: bad transposed output");
-  // small problems use 64x64 tiles so that more than a handful of workgroups exist
-  const long long big_tiles = ((m + 127) / 128) * ((a.n_out + 127) / 128);
-  const bool small = a.out_mode != OUT_GEGLU && big_tiles < 256;
-  if (a.dtype == AD_BF16) return small ? run_igemm<bf16, 64, 64>(p, s) : run_igemm<bf16, 128, 128>(p, s);
-  return small ? run_igemm<float, 64, 64>(p, s) : run_igemm<float, 128, 128>(p, s);
+  const long long in_elems = (long long)a.batch * a.hs * a.ws;
+  const long long w_bytes = (long long)round_up(a.n_out, kNPad) * p.Kp * (long long)esize(a.dtype);
+  if (in_elems * std::max(a.c0, a.c1) * (long long)esize(a.dtype) >= 0x7fffffffLL || w_bytes >= 0x7fffffffLL)
+    AD_FAIL(AD_ERR_INVALID, "conv: operands of 2 GiB or more are not supported");
+  p.bytes0 = (unsigned)(in_elems * a.c0 * esize(a.dtype));
+  p.bytes1 = a.c1 ? (unsigned)(in_elems * a.c1 * esize(a.dtype)) : p.bytes0;
+  p.bytes_w = (unsigned)w_bytes;
+  const int tile = choose_tile(m, a.n_out, a.out_mode);
+  int splits = choose_splits(m, a.n_out, p.ktiles, a.out_mode, tile);
+  if (splits > 1 && (!a.splitk_ws || a.splitk_bytes < (size_t)splits * m * a.n_out * 4)) splits = 1;   // no scratch: plain launch
+  p.kt_per_split = splits > 1 ? (p.ktiles + splits - 1) / splits : p.ktiles;
+  p.partial = splits > 1 ? (float*)a.splitk_ws : nullptr;
+  ad_status st;
+  if (a.dtype == AD_BF16) {
+    switch (tile) {
+      case TILE_256x128: st = run_igemm<bf16, 256, 128, 2, 2, 1>(p, "igemm_bf16_256x128", s); break;
+      case TILE_128x128: st = run_igemm<bf16, 128, 128, 2, 2, 1>(p, "igemm_bf16_128x128", s); break;
+      case TILE_128x64: st = run_igemm<bf16, 128, 64, 2, 2, 1>(p, "igemm_bf16_128x64", s); break;
+      default: st = run_igemm<bf16, 64, 64, 2, 2, 1>(p, splits > 1 ? "igemm_bf16_64x64_splitk" : "igemm_bf16_64x64", s); break;
+    }
+  } else {
+    switch (tile) {
+      case TILE_256x128: st = run_igemm<float, 256, 128, 2, 2, 1>(p, "igemm_f32_256x128", s); break;
+      case TILE_128x128: st = run_igemm<float, 128, 128, 2, 2, 1>(p, "igemm_f32_128x128", s); break;
+      case TILE_128x64: st = run_igemm<float, 128, 64, 2, 2, 1>(p, "igemm_f32_128x64", s); break;
+      default: st = run_igemm<float, 64, 64, 2, 2, 1>(p, splits > 1 ? "igemm_f32_64x64_splitk" : "igemm_f32_64x64", s); break;
+    }
+  }
+  if (st != AD_OK || splits <= 1) return st;
+  const long long quads = m * (a.n_out / 4);
+  const int blocks = (int)((quads + 255) / 256 < 2048 ? (quads + 255) / 256 : 2048);
+  const int rowvec_ld = a.rowvec_ld > 0 ? a.rowvec_ld : a.n_out;
+  ProfLaunch pl("splitk_reduce", 0, (double)splits * m * a.n_out * 4 + (double)m * a.n_out * esize(a.dtype), s);
+  if (a.dtype == AD_BF16)
+    hipLaunchKernelGGL(k_splitk_reduce<bf16>, dim3(blocks), dim3(256), 0, s, p.partial, splits, p.M, p.N, p.hw_out, a.bias, a.rowvec,
+                       rowvec_ld, (const bf16*)a.residual, a.out, a.out_mode, a.ld_t);
+  else
+    hipLaunchKernelGGL(k_splitk_reduce<float>, dim3(blocks), dim3(256), 0, s, p.partial, splits, p.M, p.N, p.hw_out, a.bias, a.rowvec,
+                       rowvec_ld, (const float*)a.residual, a.out, a.out_mode, a.ld_t);
+  AD_HIP(hipGetLastError());
+  return AD_OK;
 }
+
+void set_tile_override(int tile) { g_tile_override = tile; }
 
 // =================================================================================================
 // Fused attention for bf16, head_dim 64.  A workgroup handles 128 queries of one (batch, head); each
@@ -482,7 +670,7 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
   const float scale = 1.f / sqrtf((float)head_dim);
   if (dtype == AD_BF16 && head_dim == 64 && v_t) {
     if (ldv < round_up(lk, 64) || (ldq | ldk | ldv | ldo) % 8) AD_FAIL(AD_ERR_INVALID, "attention: MFMA path needs padded, 8-aligned strides");
-    ProfLaunch pl("attn_mfma_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s);
+    ProfLaunch pl("attn_mfma_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s, batch * l, lk, c);
     hipLaunchKernelGGL(k_attn_mfma, dim3((l + 127) / 128, heads, batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
                        (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, scale * 1.44269504088896341f);
   } else if (dtype == AD_BF16) {
@@ -859,8 +1047,9 @@ extern "C" {
 
 ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hs, int ws,
                           int up, int ksize, int stride, const void* w_packed, int n_out, const float* bias,
-                          const float* rowvec, const void* residual, void* out, int out_mode, int ld_t, ad_stream stream) {
-  ConvArgs a{dtype, src0, src1, c0, c1, batch, hs, ws, up, ksize, stride, w_packed, n_out, bias, rowvec, n_out, residual, out, out_mode, ld_t};
+                          const float* rowvec, const void* residual, void* out, int out_mode, int ld_t, void* splitk_ws,
+                          size_t splitk_bytes, ad_stream stream) {
+  ConvArgs a{dtype, src0, src1, c0, c1, batch, hs, ws, up, ksize, stride, w_packed, n_out, bias, rowvec, n_out, residual, out, out_mode, ld_t, splitk_ws, splitk_bytes};
   return launch_conv(a, (hipStream_t)stream);
 }
 
@@ -880,6 +1069,16 @@ ad_status ad_attention_forward(int dtype, const void* q, const void* k, const vo
                                int l, int lk, int c, int head_dim, int ldq, int ldk, int ldv, int ldo, void* out,
                                ad_stream stream) {
   return launch_attention(dtype, q, k, v, v_is_transposed, batch, l, lk, c, head_dim, ldq, ldk, ldv, ldo, out, (hipStream_t)stream);
+}
+
+size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n_out, int c_in_total, int ksize, int out_mode) {
+  return conv_workspace_bytes(dtype, (long long)batch * h_out * w_out, n_out, ksize * ksize * c_in_total, out_mode);
+}
+
+ad_status ad_tune_conv_tile(int tile) {
+  if (tile < -1 || tile > 3) AD_FAIL(AD_ERR_INVALID, "tile must be -1..3");
+  set_tile_override(tile);
+  return AD_OK;
 }
 
 ad_status ad_sampler_update_raw(void* x, const void* eps, size_t n, int batch, float c_x, float c_eps, float cfg_scale,

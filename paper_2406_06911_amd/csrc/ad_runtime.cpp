@@ -38,7 +38,7 @@ struct Eval {
   int proj_ld = 0;
 
   char* work(size_t off) const { return c.work_dev + off; }
-  void* temp(int t) const { return work(ws.temp_off[t]); }
+  void* temp(int t) const { return ws.temp_bytes[t] ? work(ws.temp_off[t]) : nullptr; }
   float* f32area() const { return (float*)work(ws.f32_off); }
 
   // tensor produced by `unit` (may live outside this component)
@@ -61,7 +61,7 @@ struct Eval {
                  int ld_t = 0) const {
     WView wv{c};
     ConvArgs a{dt, src0, src1, c0, c1, c.cfg.batch, hs, wsz, up, ksize, stride, wv.at(w_idx), c.weights[w_idx].info.shape[0],
-               b_idx >= 0 ? wv.f32(b_idx) : nullptr, rowvec, proj_ld, residual, dst, mode, ld_t};
+               b_idx >= 0 ? wv.f32(b_idx) : nullptr, rowvec, proj_ld, residual, dst, mode, ld_t, temp(9), ws.temp_bytes[9]};
     return launch_conv(a, s);
   }
   // linear layer on a [rows][cin] matrix
@@ -69,7 +69,7 @@ struct Eval {
                    int mode = OUT_ROWMAJOR, int batch = 1, int ld_t = 0) const {
     WView wv{c};
     ConvArgs a{dt, src, nullptr, cin, 0, batch, rows / batch, 1, 0, 1, 1, wv.at(w_idx), c.weights[w_idx].info.shape[0],
-               b_idx >= 0 ? wv.f32(b_idx) : nullptr, nullptr, 0, residual, dst, mode, ld_t};
+               b_idx >= 0 ? wv.f32(b_idx) : nullptr, nullptr, 0, residual, dst, mode, ld_t, temp(9), ws.temp_bytes[9]};
     return launch_conv(a, s);
   }
   ad_status gn(const void* src0, const void* src1, int c0, int c1, int hw, int g_idx, int silu, void* dst) const {
@@ -247,6 +247,7 @@ ad_status ad_profile_get(const ad_ctx* ctx, int index, ad_profile_rec* out) {
   AD_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
   std::snprintf(out->kernel, sizeof(out->kernel), "%s", r.name);
   out->flops = r.flops; out->bytes = r.bytes; out->ms = ms;
+  out->m = r.m; out->n = r.n; out->k = r.k;
   return AD_OK;
 }
 

@@ -22,7 +22,7 @@ def sync():
 
 
 # ---------------------------------------------------------------------------------------------------
-def run_conv(dtype, x0, x1, w, bias, stride=1, up=0, rowvec=None, residual=None, mode=B.OUT_ROWMAJOR, geglu=False):
+def run_conv(dtype, x0, x1, w, bias, stride=1, up=0, rowvec=None, residual=None, mode=B.OUT_ROWMAJOR, geglu=False, splitk=False):
     """x0/x1 NCHW float arrays (already quantised); returns the device result as float64 array."""
     n, c0, hs, ws = x0.shape
     c1 = x1.shape[1] if x1 is not None else 0
@@ -55,8 +55,11 @@ def run_conv(dtype, x0, x1, w, bias, stride=1, up=0, rowvec=None, residual=None,
     else:
         ld_t = (ho * wo + 63) // 64 * 64
         out = torch.full((n, n_out, ld_t), float("nan"), device=DEV, dtype=tdtype(dtype) if mode == B.OUT_TRANSPOSED else torch.float32)
+    ws_bytes = lib.ad_conv_workspace_bytes(dtype, n, ho, wo, n_out, c0 + c1, k, mode) if splitk else 0
+    wsb = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=DEV)
     B.check(lib.ad_conv_forward(dtype, p(d0), p(d1), c0, c1, n, hs, ws, up, k, stride, p(wp), n_out, p(db), p(drow), p(dres),
-                                p(out), mode, ld_t, stream_ptr()))
+                                p(out), mode, ld_t, p(wsb) if ws_bytes else None, ws_bytes, stream_ptr()))
+    run_conv.last_ws_bytes = ws_bytes
     sync()
     return host(out), (ho, wo)
 
@@ -117,6 +120,25 @@ def test_conv_epilogues(dtype):
         got, (ho, wo) = run_conv(dtype, x, None, w, bias, mode=mode)
         ref = P.conv2d(x, w, bias).reshape(n, n_out, ho * wo)
         assert rel_l2(got[:, :, :ho * wo], ref) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_conv_split_k(dtype):
+    """Deep-level shapes (few output positions, long K) take the split-K path when scratch is supplied."""
+    n, c, h, wd, n_out = 2, 640, 6, 6, 192
+    x = quantize(SI.make_array((n, c, h, wd), 26), dtype)
+    w = quantize(SI.make_array((n_out, c, 3, 3), 27, 0.02), dtype)
+    bias = SI.make_array((n_out,), 28, 0.1)
+    rowvec = SI.make_array((n, n_out), 29)
+    res = quantize(SI.make_array((n, h, wd, n_out), 30), dtype)
+    ref = P.conv2d(x, w, bias) + rowvec[:, :, None, None] + nhwc_to_nchw(res)
+    got, _ = run_conv(dtype, x, None, w, bias, rowvec=rowvec, residual=res, splitk=True)
+    assert run_conv.last_ws_bytes > 0, "shape was expected to split"
+    assert rel_l2(nhwc_to_nchw(got), ref) < TOL[dtype]
+    plain, _ = run_conv(dtype, x, None, w, bias, rowvec=rowvec, residual=res, splitk=False)
+    assert rel_l2(plain, got) < TOL[dtype]
+    got, (ho, wo) = run_conv(dtype, x, None, w, bias, mode=B.OUT_TRANSPOSED_F32, splitk=True)
+    assert rel_l2(got[:, :, :ho * wo], P.conv2d(x, w, bias).reshape(n, n_out, ho * wo)) < TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype", DT)
