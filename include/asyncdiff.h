@@ -168,6 +168,12 @@ ad_status ad_component_forward(ad_ctx* ctx, int comp, int lane, const void* cons
                                float latent_scale, const void* text_emb, const void* pooled_emb,
                                void* const* hidden_out, ad_stream stream);
 
+/* The cross-attention keys and values depend only on the text embedding, not on the step: this call
+ * computes them once into the work arena.  ad_step does it by itself at the first round of a run;
+ * ad_component_forward uses the cache when it is called with the same text_emb pointer and recomputes
+ * the projections otherwise.  ad_reset drops the cache.  text_emb: DEVICE. */
+ad_status ad_precompute_text(ad_ctx* ctx, const void* text_emb, ad_stream stream);
+
 /* One parallel round of the schedule (one step during warm-up, `stride` steps afterwards, fewer in a
  * trailing partial round): evaluates the round's components concurrently on the given streams
  * (evaluation e runs on streams[e % n_streams]; n_streams = 1 gives the serial order), stores their
@@ -228,7 +234,7 @@ ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0,
                           const float* rowvec, const void* residual, void* out, int out_mode, int ld_t,
                           void* splitk_ws, size_t splitk_bytes, ad_stream stream);
 /* Tuning knob for measurements: forces the block tile of ad_conv_forward and of every convolution / linear
- * layer of the process (0: 256x128, 1: 128x128, 2: 128x64, 3: 64x64, -1: automatic choice, the default).
+ * layer of the process (1: 128x128, 3: 64x64, -1: automatic choice, the default).
  * Results are the same up to rounding order. */
 ad_status ad_tune_conv_tile(int tile);
 /* Packs HOST fp32 weights [n_out][c_in][k][k] into the kernel layout (HOST out, dtype elements).

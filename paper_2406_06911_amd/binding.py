@@ -71,7 +71,7 @@ EXPORTS = [
     "ad_reset", "ad_get_timesteps", "ad_num_sched_rows", "ad_get_schedule", "ad_get_sampler_coeffs",
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
     "ad_conv_forward", "ad_conv_workspace_bytes", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
-    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile",
+    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text",
 ]
 
 
@@ -114,6 +114,7 @@ def _load():
     L.ad_layernorm_forward.argtypes = [ci, vp, ci, ci, vp, vp, cf, vp, vp]
     L.ad_attention_forward.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
     L.ad_tune_conv_tile.argtypes = [ci]
+    L.ad_precompute_text.argtypes = [vp, vp, vp]
     L.ad_profile_enable.argtypes = [vp, ci]
     L.ad_profile_clear.argtypes = [vp]
     L.ad_profile_count.argtypes = [vp]
@@ -249,6 +250,9 @@ class AsyncDiff:
             return None
         check(st)
         return done.value
+
+    def precompute_text(self, text_emb, stream):
+        check(lib.ad_precompute_text(self._h, _ptr(text_emb), C.c_void_p(stream.cuda_stream)))
 
     def ddim_update(self, x, eps, step_index, cfg_scale, stream):
         check(lib.ad_ddim_update(self._h, _ptr(x), _ptr(eps), step_index, float(cfg_scale), C.c_void_p(stream.cuda_stream)))

@@ -255,8 +255,8 @@ static void build_manifest(Ctx& c) {
         for (int k = 0; k < f.depth; ++k) {
           const std::string p = n + "." + std::to_string(k);
           add_w(c, p + ".ln1.g", W_VEC_F32, {C}); add_w(c, p + ".ln1.b", W_VEC_F32, {C});
-          add_w(c, p + ".attn1.q.w", W_CONV1, {C, C}); add_w(c, p + ".attn1.k.w", W_CONV1, {C, C});
-          add_w(c, p + ".attn1.v.w", W_CONV1, {C, C});
+          add_w(c, p + ".attn1.q.w", W_QKV_Q, {C, C}); add_w(c, p + ".attn1.k.w", W_QKV_KV, {C, C});
+          add_w(c, p + ".attn1.v.w", W_QKV_KV, {C, C});
           add_w(c, p + ".attn1.o.w", W_CONV1, {C, C}); add_w(c, p + ".attn1.o.b", W_VEC_F32, {C});
           add_w(c, p + ".ln2.g", W_VEC_F32, {C}); add_w(c, p + ".ln2.b", W_VEC_F32, {C});
           add_w(c, p + ".attn2.q.w", W_CONV1, {C, C}); add_w(c, p + ".attn2.k.w", W_CONV1, {C, g.ctx_dim});
@@ -338,7 +338,8 @@ static void plan_weights(Ctx& c) {
         bytes = packed_conv_bytes(dt, s[0], s[1], 1); w.n_pad = round_up(s[0], kNPad); w.k_pad = round_up(s[1], bk_elems(dt)); break;
       case W_CONV_IN: w.n_pad = round_up(s[0], kNPad); w.k_pad = kConvInK; bytes = (size_t)w.n_pad * kConvInK * esize(dt); break;
       case W_SMALL:   bytes = (size_t)s[0] * s[1] * esize(dt); break;
-      case W_TEMB: case W_TEMB_BIAS: bytes = 0; break;   // live in the fused matrix below
+      case W_TEMB: case W_TEMB_BIAS: case W_QKV_KV: bytes = 0; break;   // live in a fused matrix
+      case W_QKV_Q: bytes = packed_conv_bytes(dt, 3 * s[0], s[1], 1); w.n_pad = round_up(3 * s[0], kNPad); w.k_pad = round_up(s[1], bk_elems(dt)); break;
       case W_VEC_F32: case W_GEGLU_BIAS: bytes = (size_t)round_up(s[0], kNPad) * 4; break;
     }
     w.dev_off = off;
@@ -366,6 +367,17 @@ static void plan_work(Ctx& c) {
         for (int s = 0; s < 2; ++s) c.slot_off[s][u] = take(tensor_bytes(c, u));
   c.eps_off.clear();
   for (int j = 0; j < c.stride; ++j) c.eps_off.push_back(take(tensor_bytes(c, nu - 1)));
+  c.text_k_off.assign(nu, {});
+  c.text_v_off.assign(nu, {});
+  for (int ui = 0; ui < nu; ++ui) {
+    const ad_unit_info& u = c.units[ui].info;
+    if (u.kind != AD_UNIT_TFM) continue;
+    const bool vt = g.dtype == AD_BF16 && g.head_dim == 64;
+    for (int k = 0; k < u.depth; ++k) {
+      c.text_k_off[ui].push_back(take((size_t)g.batch * g.ctx_len * u.c_in * es));
+      c.text_v_off[ui].push_back(take(vt ? (size_t)g.batch * u.c_in * round_up(g.ctx_len, 64) * es : (size_t)g.batch * g.ctx_len * u.c_in * es));
+    }
+  }
   // per (component, lane) activation workspaces
   int cmax = 0;
   for (const Unit& u : c.units) cmax = std::max(cmax, std::max(u.info.c_in + u.info.c_skip, u.info.c_out));
@@ -402,6 +414,7 @@ static void plan_work(Ctx& c) {
           want(7, B * g.ctx_len * C * es);
           want(8, B * C * lkp * es);
           gemm(m_in, (int)C, (int)C);
+          gemm(m_in, (int)(3 * C), (int)C, OUT_QKV);
           gemm(m_in, (int)C, (int)(4 * C));
           gemm(B * g.ctx_len, (int)C, g.ctx_dim);
           break;
@@ -607,6 +620,7 @@ ad_status ad_reset(ad_ctx* ctx, int T, int sampler_kind, int beta_kind, float cf
   build_schedule(T, c.N, c.warmup, c.stride, c.time_shift != 0, c.rows);
   c.next_row = 0;
   c.steps_done = 0;
+  c.text_cached = nullptr;
   return AD_OK;
 }
 

@@ -54,7 +54,9 @@ enum WeightRole {
   W_TEMB,        // ResBlock time projection, rows gathered into one matrix
   W_VEC_F32,     // bias / gamma / beta, fp32 (padded to kNPad when used as a GEMM bias)
   W_GEGLU_BIAS,  // ff1 bias, interleaved like its weight
-  W_TEMB_BIAS
+  W_TEMB_BIAS,
+  W_QKV_Q,       // self-attention q: holds the fused [q; k; v] GEMM operand
+  W_QKV_KV       // self-attention k and v: stored inside the fused operand of q
 };
 
 struct Weight {
@@ -95,6 +97,9 @@ struct Ctx {
   size_t weight_bytes = 0, work_bytes = 0;
   std::vector<size_t> slot_off[2];     // per unit; SIZE_MAX when the unit's output never crosses components
   std::vector<size_t> eps_off;         // per stride lane
+  // cross-attention keys / values of the text embedding (constant over the steps): per unit, per layer
+  std::vector<std::vector<size_t>> text_k_off, text_v_off;
+  const void* text_cached = nullptr;   // text embedding the cache was computed from
   std::vector<std::vector<Workspace>> ws;   // [component][lane]
   size_t f32_bytes = 0, gn_bytes = 0;
 

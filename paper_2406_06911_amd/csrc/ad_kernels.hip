@@ -89,6 +89,7 @@ struct IgemmParams {
   unsigned bytes0, bytes1, bytes_w;   // sizes of the two sources and of the packed weights
   int kt_per_split;                   // k-tiles handled by one workgroup along grid.y (split-K), else ktiles
   float* partial;                     // split-K: fp32 partial sums [splits][M][N]; nullptr otherwise
+  void* out2; void* out3;             // OUT_QKV
 };
 
 constexpr int kPitch = kRowBytes + 16;   // LDS row pitch in bytes
@@ -120,7 +121,9 @@ __device__ __forceinline__ V buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned vo
   return __builtin_bit_cast(V, raw);
 }
 
-template <typename T, int BM, int BN, int WGM, int WGN, int NSET>
+// MODE: epilogue selected at compile time (the OUT_* value, or OUT_PARTIAL for split-K partial sums)
+constexpr int OUT_PARTIAL = 5;
+template <typename T, int BM, int BN, int WGM, int WGN, int NSET, int MODE>
 __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
   typedef typename Vec<T>::type V;
   constexpr int BK = kRowBytes / (int)sizeof(T);
@@ -256,7 +259,7 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
   // epilogue: lane holds column l32 of each 32x32 tile; register r is row 8*(r/4) + 4*half + r%4
   const int row_base = m0 + wave_m * WTM + 4 * half;
   const int col_base = n0 + wave_n * WTN + l32;
-  if (p.partial) {
+  if constexpr (MODE == OUT_PARTIAL) {
     float* dst = p.partial + (size_t)blockIdx.y * p.M * p.N;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -270,61 +273,85 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
           if (row < p.M) dst[(size_t)row * p.N + col] = acc[i][j][r];
         }
     }
-    return;
-  }
-  if (p.out_mode == OUT_GEGLU) {
-    if constexpr (TN % 2 == 0) {
-      const int half_n = p.N >> 1;
+  } else if constexpr (MODE == OUT_GEGLU) {
+    static_assert(TN % 2 == 0, "GEGLU needs a value and a gate tile per wavefront");
+    const int half_n = p.N >> 1;
 #pragma unroll
-      for (int j = 0; j < TN; j += 2) {
-        const int oc = ((n0 + wave_n * WTN + j * 32) >> 1) + l32;      // packed columns: 32 value, 32 gate
-        if (oc >= half_n) continue;
-        const int cv = col_base + j * 32;
-        const float bv = p.bias ? p.bias[cv] : 0.f, bg = p.bias ? p.bias[cv + 32] : 0.f;
+    for (int j = 0; j < TN; j += 2) {
+      const int oc = ((n0 + wave_n * WTN + j * 32) >> 1) + l32;      // packed columns: 32 value, 32 gate
+      if (oc >= half_n) continue;
+      const int cv = col_base + j * 32;
+      const float bv = p.bias ? p.bias[cv] : 0.f, bg = p.bias ? p.bias[cv + 32] : 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < p.M)
+            ((T*)p.out)[(size_t)row * half_n + oc] = from_f<T>((acc[i][j][r] + bv) * gelu_f(acc[i][j + 1][r] + bg));
+        }
+    }
+  } else {
+    // sample index of a row: a tile spans at most two samples when a sample has at least BM rows
+    const int b0 = m0 / p.hw_out;
+    const int bnd = (b0 + 1) * p.hw_out;
+    const bool one_step = p.hw_out >= BM;
+    auto sample_of = [&](int row) { return one_step ? b0 + (row >= bnd ? 1 : 0) : row / p.hw_out; };
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = col_base + j * 32;
+      if (col >= p.N) continue;
+      const float bias = p.bias ? p.bias[col] : 0.f;
+      if constexpr (MODE == OUT_ROWMAJOR) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-            if (row < p.M)
-              ((T*)p.out)[(size_t)row * half_n + oc] = from_f<T>((acc[i][j][r] + bv) * gelu_f(acc[i][j + 1][r] + bg));
+            if (row >= p.M) continue;
+            float v = acc[i][j][r] + bias;
+            if (p.rowvec) v += p.rowvec[(size_t)sample_of(row) * p.rowvec_ld + col];
+            if (p.residual) v += to_f(((const T*)p.residual)[(size_t)row * p.N + col]);
+            ((T*)p.out)[(size_t)row * p.N + col] = from_f<T>(v);
+          }
+      } else if constexpr (MODE == OUT_QKV) {
+        const int c3 = p.N / 3, which = col / c3, cc = col - which * c3;
+        T* dst = (T*)(which == 0 ? p.out : which == 1 ? p.out2 : p.out3);
+        const bool transposed = which == 2 && p.ld_t > 0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+            if (row >= p.M) continue;
+            const float v = acc[i][j][r] + bias;
+            if (transposed) {
+              const int b = sample_of(row);
+              dst[((size_t)b * c3 + cc) * p.ld_t + (row - b * p.hw_out)] = from_f<T>(v);
+            } else {
+              dst[(size_t)row * c3 + cc] = from_f<T>(v);
+            }
+          }
+      } else {   // OUT_TRANSPOSED, OUT_TRANSPOSED_F32
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+            if (row >= p.M) continue;
+            const int b = sample_of(row);
+            float v = acc[i][j][r] + bias;
+            if (p.rowvec) v += p.rowvec[(size_t)b * p.rowvec_ld + col];
+            const size_t o = ((size_t)b * p.N + col) * p.ld_t + (row - b * p.hw_out);
+            if constexpr (MODE == OUT_TRANSPOSED) ((T*)p.out)[o] = from_f<T>(v);
+            else ((float*)p.out)[o] = v;
           }
       }
     }
-    return;
-  }
-  const bool need_b = p.rowvec != nullptr || p.out_mode != OUT_ROWMAJOR;
-  const int b0 = need_b ? m0 / p.hw_out : 0;
-  const int bnd = (b0 + 1) * p.hw_out;
-  const bool one_step = p.hw_out >= BM;         // a tile then spans at most two samples
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int col = col_base + j * 32;
-    if (col >= p.N) continue;
-    const float bias = p.bias ? p.bias[col] : 0.f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-        if (row >= p.M) continue;
-        float v = acc[i][j][r] + bias;
-        int b = 0;
-        if (need_b) b = one_step ? b0 + (row >= bnd ? 1 : 0) : row / p.hw_out;
-        if (p.rowvec) v += p.rowvec[(size_t)b * p.rowvec_ld + col];
-        if (p.out_mode == OUT_ROWMAJOR) {
-          if (p.residual) v += to_f(((const T*)p.residual)[(size_t)row * p.N + col]);
-          ((T*)p.out)[(size_t)row * p.N + col] = from_f<T>(v);
-        } else {
-          const size_t o = ((size_t)b * p.N + col) * p.ld_t + (row - b * p.hw_out);
-          if (p.out_mode == OUT_TRANSPOSED) ((T*)p.out)[o] = from_f<T>(v);
-          else ((float*)p.out)[o] = v;
-        }
-      }
   }
 }
 
-template <typename T, int BM, int BN, int WGM, int WGN, int NSET>
+template <typename T, int BM, int BN, int WGM, int WGN, int NSET, int MODE>
 static ad_status run_igemm(const IgemmParams& p0, const char* name, hipStream_t s) {
   IgemmParams p = p0;
   p.tiles_n = (p.N + BN - 1) / BN;
@@ -332,14 +359,14 @@ static ad_status run_igemm(const IgemmParams& p0, const char* name, hipStream_t 
   constexpr int lds_bytes = 2 * (BM + BN) * kPitch;
   static bool attr_set = false;     // LDS above 64 KiB has to be requested once per kernel
   if (!attr_set) {
-    AD_HIP(hipFuncSetAttribute((const void*)k_igemm<T, BM, BN, WGM, WGN, NSET>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    AD_HIP(hipFuncSetAttribute((const void*)k_igemm<T, BM, BN, WGM, WGN, NSET, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     attr_set = true;
   }
   const double in_bytes = (double)p.M * p.ctot * sizeof(T) * (p.stride == 2 ? 4 : 1) / (p.up ? 4 : 1);
   const double out_cols = p.out_mode == OUT_GEGLU ? p.N / 2 : p.N;
   ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
   const int splits = (p.ktiles + p.kt_per_split - 1) / p.kt_per_split;
-  hipLaunchKernelGGL((k_igemm<T, BM, BN, WGM, WGN, NSET>), dim3(p.tiles_n * tiles_m, splits), dim3(256), lds_bytes, s, p);
+  hipLaunchKernelGGL((k_igemm<T, BM, BN, WGM, WGN, NSET, MODE>), dim3(p.tiles_n * tiles_m, splits), dim3(256), lds_bytes, s, p);
   AD_HIP(hipGetLastError());
   return AD_OK;
 }
@@ -349,7 +376,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__ partial, int splits, int M, int N, int hw_out,
                                                        const float* __restrict__ bias, const float* __restrict__ rowvec,
                                                        int rowvec_ld, const T* __restrict__ residual, void* __restrict__ out,
-                                                       int out_mode, int ld_t) {
+                                                       void* __restrict__ out2, void* __restrict__ out3, int out_mode, int ld_t) {
   const int n4 = N / 4;
   const long long total = (long long)M * n4;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
@@ -365,6 +392,12 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
       if (out_mode == OUT_ROWMAJOR) {
         if (residual) x += to_f(residual[(size_t)row * N + col + e]);
         ((T*)out)[(size_t)row * N + col + e] = from_f<T>(x);
+      } else if (out_mode == OUT_QKV) {
+        const int c3 = N / 3, which = (col + e) / c3, cc = col + e - which * c3;
+        if (which == 0) ((T*)out)[(size_t)row * c3 + cc] = from_f<T>(x);
+        else if (which == 1) ((T*)out2)[(size_t)row * c3 + cc] = from_f<T>(x);
+        else if (ld_t > 0) ((T*)out3)[((size_t)b * c3 + cc) * ld_t + (row - b * hw_out)] = from_f<T>(x);
+        else ((T*)out3)[(size_t)row * c3 + cc] = from_f<T>(x);
       } else {
         const size_t o = ((size_t)b * N + col + e) * ld_t + (row - b * hw_out);
         if (out_mode == OUT_TRANSPOSED) ((T*)out)[o] = from_f<T>(x);
@@ -375,12 +408,12 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
 }
 
 // Tile shapes: block tile BM x BN, wavefront grid WGM x WGN (4 wavefronts).
-enum { TILE_256x128 = 0, TILE_128x128 = 1, TILE_128x64 = 2, TILE_64x64 = 3, TILE_AUTO = -1 };
+enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_AUTO = -1 };
 static int g_tile_override = TILE_AUTO;
 
 static int choose_tile(long long m, int n, int out_mode) {
   const bool geglu = out_mode == OUT_GEGLU;   // needs a value and a gate tile in the same wavefront
-  if (g_tile_override != TILE_AUTO && !(geglu && g_tile_override >= TILE_128x64)) return g_tile_override;
+  if (g_tile_override != TILE_AUTO && !geglu) return g_tile_override;
   // Measured on the GEMM shapes of the SD-sized models (M <= 18432): the machine is far from full with
   // large tiles, and the 64x64 tile (most workgroups, shortest dependent chain per k-tile) is fastest
   // except for GEMMs wide enough to give 128x128 tiles at least two workgroups per CU.
@@ -393,8 +426,7 @@ static int choose_tile(long long m, int n, int out_mode) {
 // K up to 23040) are cut along K so that a few hundred workgroups exist.
 static int choose_splits(long long m, int n, int ktiles, int out_mode, int tile) {
   if (out_mode == OUT_GEGLU || n % 4) return 1;
-  const int bm = tile == TILE_64x64 ? 64 : (tile == TILE_256x128 ? 256 : 128);
-  const int bn = (tile == TILE_64x64 || tile == TILE_128x64) ? 64 : 128;
+  const int bm = tile == TILE_64x64 ? 64 : 128, bn = bm;
   const long long tiles = ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
   if (tiles >= 512 || ktiles < 16) return 1;
   int splits = (int)((1024 + tiles - 1) / tiles);
@@ -435,9 +467,13 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   p.ktiles = p.Kp / bk;
   p.w = a.w; p.bias = a.bias; p.rowvec = a.rowvec; p.residual = a.residual;
   p.out = a.out; p.out_mode = a.out_mode; p.ld_t = a.ld_t; p.rowvec_ld = a.rowvec_ld > 0 ? a.rowvec_ld : a.n_out;
-  if (a.out_mode < OUT_ROWMAJOR || a.out_mode > OUT_TRANSPOSED_F32) AD_FAIL(AD_ERR_INVALID, "conv: bad out_mode");
+  p.out2 = a.out2; p.out3 = a.out3;
+  if (a.out_mode < OUT_ROWMAJOR || a.out_mode > OUT_QKV) AD_FAIL(AD_ERR_INVALID, "conv: bad out_mode");
+  if (a.out_mode == OUT_QKV && (a.n_out % 3 || !a.out2 || !a.out3 || a.residual || a.rowvec || (a.ld_t > 0 && a.ld_t < p.hw_out)))
+    AD_FAIL(AD_ERR_INVALID, "conv: bad fused q/k/v use");
   if (a.out_mode == OUT_GEGLU && (a.n_out % 64 || a.residual || a.rowvec)) AD_FAIL(AD_ERR_INVALID, "conv: bad GEGLU use");
-  if (a.out_mode >= OUT_TRANSPOSED && (a.ld_t < p.hw_out || a.residual)) AD_FAIL(AD_ERR_INVALID, "conv: bad transposed output");
+  if ((a.out_mode == OUT_TRANSPOSED || a.out_mode == OUT_TRANSPOSED_F32) && (a.ld_t < p.hw_out || a.residual))
+    AD_FAIL(AD_ERR_INVALID, "conv: bad transposed output");
   const long long in_elems = (long long)a.batch * a.hs * a.ws;
   const long long w_bytes = (long long)round_up(a.n_out, kNPad) * p.Kp * (long long)esize(a.dtype);
   if (in_elems * std::max(a.c0, a.c1) * (long long)esize(a.dtype) >= 0x7fffffffLL || w_bytes >= 0x7fffffffLL)
@@ -450,22 +486,31 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   if (splits > 1 && (!a.splitk_ws || a.splitk_bytes < (size_t)splits * m * a.n_out * 4)) splits = 1;   // no scratch: plain launch
   p.kt_per_split = splits > 1 ? (p.ktiles + splits - 1) / splits : p.ktiles;
   p.partial = splits > 1 ? (float*)a.splitk_ws : nullptr;
-  ad_status st;
-  if (a.dtype == AD_BF16) {
-    switch (tile) {
-      case TILE_256x128: st = run_igemm<bf16, 256, 128, 2, 2, 1>(p, "igemm_bf16_256x128", s); break;
-      case TILE_128x128: st = run_igemm<bf16, 128, 128, 2, 2, 1>(p, "igemm_bf16_128x128", s); break;
-      case TILE_128x64: st = run_igemm<bf16, 128, 64, 2, 2, 1>(p, "igemm_bf16_128x64", s); break;
-      default: st = run_igemm<bf16, 64, 64, 2, 2, 1>(p, splits > 1 ? "igemm_bf16_64x64_splitk" : "igemm_bf16_64x64", s); break;
-    }
-  } else {
-    switch (tile) {
-      case TILE_256x128: st = run_igemm<float, 256, 128, 2, 2, 1>(p, "igemm_f32_256x128", s); break;
-      case TILE_128x128: st = run_igemm<float, 128, 128, 2, 2, 1>(p, "igemm_f32_128x128", s); break;
-      case TILE_128x64: st = run_igemm<float, 128, 64, 2, 2, 1>(p, "igemm_f32_128x64", s); break;
-      default: st = run_igemm<float, 64, 64, 2, 2, 1>(p, splits > 1 ? "igemm_f32_64x64_splitk" : "igemm_f32_64x64", s); break;
-    }
+  const int mode = splits > 1 ? OUT_PARTIAL : a.out_mode;
+  const bool big = tile == TILE_128x128;
+  const bool h16 = a.dtype == AD_BF16;
+  const char* name = h16 ? (big ? "igemm_bf16_128x128" : (splits > 1 ? "igemm_bf16_64x64_splitk" : "igemm_bf16_64x64"))
+                         : (big ? "igemm_f32_128x128" : (splits > 1 ? "igemm_f32_64x64_splitk" : "igemm_f32_64x64"));
+  ad_status st = AD_ERR_INVALID;
+#define AD_RUN(TT, BM_, MODE_) st = run_igemm<TT, BM_, BM_, 2, 2, 1, MODE_>(p, name, s)
+#define AD_MODES(TT, BM_)                                              \
+  switch (mode) {                                                      \
+    case OUT_ROWMAJOR: AD_RUN(TT, BM_, OUT_ROWMAJOR); break;           \
+    case OUT_TRANSPOSED: AD_RUN(TT, BM_, OUT_TRANSPOSED); break;       \
+    case OUT_TRANSPOSED_F32: AD_RUN(TT, BM_, OUT_TRANSPOSED_F32); break; \
+    case OUT_QKV: AD_RUN(TT, BM_, OUT_QKV); break;                     \
+    case OUT_PARTIAL: AD_RUN(TT, BM_, OUT_PARTIAL); break;             \
+    default: break;                                                    \
   }
+  if (mode == OUT_GEGLU) {
+    if (h16) AD_RUN(bf16, 128, OUT_GEGLU); else AD_RUN(float, 128, OUT_GEGLU);
+  } else if (h16) {
+    if (big) { AD_MODES(bf16, 128) } else { AD_MODES(bf16, 64) }
+  } else {
+    if (big) { AD_MODES(float, 128) } else { AD_MODES(float, 64) }
+  }
+#undef AD_MODES
+#undef AD_RUN
   if (st != AD_OK || splits <= 1) return st;
   const long long quads = m * (a.n_out / 4);
   const int blocks = (int)((quads + 255) / 256 < 2048 ? (quads + 255) / 256 : 2048);
@@ -473,10 +518,10 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   ProfLaunch pl("splitk_reduce", 0, (double)splits * m * a.n_out * 4 + (double)m * a.n_out * esize(a.dtype), s);
   if (a.dtype == AD_BF16)
     hipLaunchKernelGGL(k_splitk_reduce<bf16>, dim3(blocks), dim3(256), 0, s, p.partial, splits, p.M, p.N, p.hw_out, a.bias, a.rowvec,
-                       rowvec_ld, (const bf16*)a.residual, a.out, a.out_mode, a.ld_t);
+                       rowvec_ld, (const bf16*)a.residual, a.out, a.out2, a.out3, a.out_mode, a.ld_t);
   else
     hipLaunchKernelGGL(k_splitk_reduce<float>, dim3(blocks), dim3(256), 0, s, p.partial, splits, p.M, p.N, p.hw_out, a.bias, a.rowvec,
-                       rowvec_ld, (const float*)a.residual, a.out, a.out_mode, a.ld_t);
+                       rowvec_ld, (const float*)a.residual, a.out, a.out2, a.out3, a.out_mode, a.ld_t);
   AD_HIP(hipGetLastError());
   return AD_OK;
 }
@@ -697,7 +742,7 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
 constexpr int kGnMaxChunks = 128;
 
 static int gn_chunks(int hw) {
-  int n = hw / 32;
+  int n = hw / 8;
   return n < 1 ? 1 : (n > kGnMaxChunks ? kGnMaxChunks : n);
 }
 
@@ -741,30 +786,37 @@ __global__ __launch_bounds__(256) void k_gn_partial(const T* __restrict__ src, i
   }
 }
 
-__global__ __launch_bounds__(64) void k_gn_finalize(const float* __restrict__ partial, int nchunk, int ctot, int groups,
-                                                    int hw, const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                    float eps, float* __restrict__ scale_shift) {
-  const int g = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+__global__ __launch_bounds__(256) void k_gn_finalize(const float* __restrict__ partial, int nchunk, int ctot, int groups,
+                                                     int hw, const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                     float eps, float* __restrict__ scale_shift) {
+  __shared__ double red[8];
+  const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int cpg = ctot / groups;
   double s = 0.0, q = 0.0;
-  for (int i = lane; i < nchunk * cpg; i += 64) {
+  for (int i = tid; i < nchunk * cpg; i += 256) {
     const int ch = i / cpg, j = i - ch * cpg;
     const float* pp = partial + (((size_t)b * nchunk + ch) * ctot + g * cpg + j) * 2;
     s += pp[0]; q += pp[1];
   }
   s = wave_sum_d(s); q = wave_sum_d(q);
+  if (lane == 0) { red[wave * 2] = s; red[wave * 2 + 1] = q; }
+  __syncthreads();
+  s = red[0] + red[2] + red[4] + red[6];      // fixed order: the result does not depend on scheduling
+  q = red[1] + red[3] + red[5] + red[7];
   const double n = (double)hw * cpg;
   const double mean = s / n;
   double var = q / n - mean * mean;
   if (var < 0) var = 0;
   const double rstd = 1.0 / sqrt(var + (double)eps);
-  for (int j = lane; j < cpg; j += 64) {
+  for (int j = tid; j < cpg; j += 256) {
     const int c = g * cpg + j;
     const double sc = rstd * gamma[c];
     scale_shift[((size_t)b * ctot + c) * 2] = (float)sc;
     scale_shift[((size_t)b * ctot + c) * 2 + 1] = (float)(beta[c] - mean * sc);
   }
 }
+
+constexpr int kGnRows = 8;   // rows handled per thread in the apply pass (scale and shift stay in registers)
 
 template <typename T>
 __global__ __launch_bounds__(256) void k_gn_apply(const T* __restrict__ src0, const T* __restrict__ src1, int c0, int c1,
@@ -773,21 +825,35 @@ __global__ __launch_bounds__(256) void k_gn_apply(const T* __restrict__ src0, co
   typedef typename Vec<T>::type V;
   constexpr int VN = Vec<T>::N;
   const int ctot = c0 + c1, nv = ctot / VN;
-  const long long total = rows * nv;
+  const long long groups = (rows + kGnRows - 1) / kGnRows;
+  const long long total = groups * nv;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-    const long long row = i / nv;
-    const int c = (int)(i - row * nv) * VN;
-    const int b = (int)(row / hw);
-    const V v = c < c0 ? *(const V*)(src0 + row * c0 + c) : *(const V*)(src1 + row * c1 + (c - c0));
-    const float* ss = scale_shift + ((size_t)b * ctot + c) * 2;
-    V r;
+    const long long grp = i / nv;
+    const int c = (int)(i - grp * nv) * VN;
+    const long long row0 = grp * kGnRows;
+    int b = -1;
+    float sc[VN], sh[VN];
 #pragma unroll
-    for (int e = 0; e < VN; ++e) {
-      float y = to_f(v[e]) * ss[2 * e] + ss[2 * e + 1];
-      if (silu) y = silu_f(y);
-      r[e] = from_f<T>(y);
+    for (int r = 0; r < kGnRows; ++r) {
+      const long long row = row0 + r;
+      if (row >= rows) break;
+      const int rb = (int)(row / hw);
+      if (rb != b) {
+        b = rb;
+        const float* ss = scale_shift + ((size_t)b * ctot + c) * 2;
+#pragma unroll
+        for (int e = 0; e < VN; ++e) { sc[e] = ss[2 * e]; sh[e] = ss[2 * e + 1]; }
+      }
+      const V v = c < c0 ? *(const V*)(src0 + row * c0 + c) : *(const V*)(src1 + row * c1 + (c - c0));
+      V o;
+#pragma unroll
+      for (int e = 0; e < VN; ++e) {
+        float y = to_f(v[e]) * sc[e] + sh[e];
+        if (silu) y = silu_f(y);
+        o[e] = from_f<T>(y);
+      }
+      *(V*)(out + row * ctot + c) = o;
     }
-    *(V*)(out + row * ctot + c) = r;
   }
 }
 
@@ -809,21 +875,21 @@ static ad_status run_groupnorm(const void* src0, const void* src1, int c0, int c
   float* ss = partial + (size_t)batch * kGnMaxChunks * ctot * 2;
   const long long rows = (long long)batch * hw;
   {
-    ProfLaunch pl("gn_partial", 0, (double)rows * c0 * sizeof(T), s);
+    ProfLaunch pl("gn_partial", 0, (double)rows * c0 * sizeof(T), s, (int)rows, c0, 0);
     hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src0, c0, hw, nchunk, ctot, 0, partial);
   }
   if (c1) {
-    ProfLaunch pl("gn_partial", 0, (double)rows * c1 * sizeof(T), s);
+    ProfLaunch pl("gn_partial", 0, (double)rows * c1 * sizeof(T), s, (int)rows, c1, 0);
     hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src1, c1, hw, nchunk, ctot, c0, partial);
   }
   {
-    ProfLaunch pl("gn_finalize", 0, 0, s);
-    hipLaunchKernelGGL(k_gn_finalize, dim3(groups, batch), dim3(64), 0, s, partial, nchunk, ctot, groups, hw, gamma, beta, eps, ss);
+    ProfLaunch pl("gn_finalize", 0, 0, s, (int)rows, ctot, 0);
+    hipLaunchKernelGGL(k_gn_finalize, dim3(groups, batch), dim3(256), 0, s, partial, nchunk, ctot, groups, hw, gamma, beta, eps, ss);
   }
-  const long long vecs = rows * (ctot / Vec<T>::N);
+  const long long vecs = ((rows + kGnRows - 1) / kGnRows) * (ctot / Vec<T>::N);
   int blocks = (int)((vecs + 255) / 256 < 8192 ? (vecs + 255) / 256 : 8192);
   if (blocks < 1) blocks = 1;
-  ProfLaunch pl("gn_apply", 0, 2.0 * rows * ctot * sizeof(T), s);
+  ProfLaunch pl("gn_apply", 0, 2.0 * rows * ctot * sizeof(T), s, (int)rows, ctot, 0);
   hipLaunchKernelGGL(k_gn_apply<T>, dim3(blocks), dim3(256), 0, s, (const T*)src0, (const T*)src1, c0, c1, rows, hw, ss, silu, (T*)out);
   AD_HIP(hipGetLastError());
   return AD_OK;
@@ -889,7 +955,7 @@ ad_status launch_layernorm(int dtype, const void* src, int rows, int c, const fl
   if (!src || !gamma || !beta || !out) AD_FAIL(AD_ERR_INVALID, "layernorm: null pointer");
   const int vn = dtype == AD_BF16 ? 8 : 4;
   if (rows < 1 || c < vn || c % vn || c > 64 * 8 * vn) AD_FAIL(AD_ERR_INVALID, "layernorm: unsupported width %d", c);
-  ProfLaunch pl("layernorm", 0, 2.0 * rows * c * (dtype == AD_BF16 ? 2 : 4), s);
+  ProfLaunch pl("layernorm", 0, 2.0 * rows * c * (dtype == AD_BF16 ? 2 : 4), s, rows, c, 0);
   if (dtype == AD_BF16)
     hipLaunchKernelGGL(k_layernorm<bf16>, dim3((rows + 3) / 4), dim3(256), 0, s, (const bf16*)src, rows, c, gamma, beta, eps, (bf16*)out);
   else if (dtype == AD_F32)
@@ -1076,7 +1142,7 @@ size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n
 }
 
 ad_status ad_tune_conv_tile(int tile) {
-  if (tile < -1 || tile > 3) AD_FAIL(AD_ERR_INVALID, "tile must be -1..3");
+  if (tile != -1 && tile != 1 && tile != 3) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1 or 3");
   set_tile_override(tile);
   return AD_OK;
 }

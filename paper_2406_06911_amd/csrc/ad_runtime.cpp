@@ -101,6 +101,15 @@ struct Eval {
     }
     return conv(temp(0), nullptr, f.c_out, 0, f.h_in, f.w_in, 0, 3, 1, w0 + 8, w0 + 9, nullptr, shortcut, tensor_out(ui));
   }
+  // cross-attention key / value projections of the text embedding for the layer whose weights start at w
+  ad_status text_kv(int w, void* kdst, void* vdst) const {
+    const int B = c.cfg.batch, Lk = c.cfg.ctx_len, lkp = round_up(Lk, 64);
+    const bool vt = dt == AD_BF16 && c.cfg.head_dim == 64;
+    AD_TRY(linear(text, B * Lk, c.cfg.ctx_dim, w + 10, -1, nullptr, kdst));
+    if (vt) return linear(text, B * Lk, c.cfg.ctx_dim, w + 11, -1, nullptr, vdst, OUT_TRANSPOSED, B, lkp);
+    return linear(text, B * Lk, c.cfg.ctx_dim, w + 11, -1, nullptr, vdst);
+  }
+
   ad_status tfm(const Unit& u, int ui) const {
     const ad_unit_info& f = u.info;
     const int B = c.cfg.batch, L = f.h_in * f.w_in, Cc = f.c_in, M = B * L, d = c.cfg.head_dim;
@@ -117,18 +126,26 @@ struct Eval {
     for (int k = 0; k < f.depth; ++k, w += 20) {
       // ln1.g ln1.b a1.q a1.k a1.v a1.o.w a1.o.b ln2.g ln2.b a2.q a2.k a2.v a2.o.w a2.o.b ln3.g ln3.b ff1.w ff1.b ff2.w ff2.b
       AD_TRY(ln(h, M, Cc, w + 0, temp(0)));
-      AD_TRY(linear(temp(0), M, Cc, w + 2, -1, nullptr, temp(2)));
-      AD_TRY(linear(temp(0), M, Cc, w + 3, -1, nullptr, temp(3)));
-      if (vt) AD_TRY(linear(temp(0), M, Cc, w + 4, -1, nullptr, temp(4), OUT_TRANSPOSED, B, lp));
-      else AD_TRY(linear(temp(0), M, Cc, w + 4, -1, nullptr, temp(4)));
+      {   // q, k, v of the self-attention in one GEMM; v lands transposed when the MFMA attention kernel follows
+        WView wv{c};
+        ConvArgs a{dt, temp(0), nullptr, Cc, 0, B, L, 1, 0, 1, 1, wv.at(w + 2), 3 * Cc, nullptr, nullptr, 0, nullptr, temp(2), OUT_QKV,
+                   vt ? lp : 0, temp(9), ws.temp_bytes[9], temp(3), temp(4)};
+        AD_TRY(launch_conv(a, s));
+      }
       AD_TRY(launch_attention(dt, temp(2), temp(3), temp(4), vt, B, L, L, Cc, d, Cc, Cc, vt ? lp : Cc, Cc, temp(5), s));
       AD_TRY(linear(temp(5), M, Cc, w + 5, w + 6, h, h));
       AD_TRY(ln(h, M, Cc, w + 7, temp(0)));
       AD_TRY(linear(temp(0), M, Cc, w + 9, -1, nullptr, temp(2)));
-      AD_TRY(linear(text, B * Lk, c.cfg.ctx_dim, w + 10, -1, nullptr, temp(7)));
-      if (vt) AD_TRY(linear(text, B * Lk, c.cfg.ctx_dim, w + 11, -1, nullptr, temp(8), OUT_TRANSPOSED, B, lkp));
-      else AD_TRY(linear(text, B * Lk, c.cfg.ctx_dim, w + 11, -1, nullptr, temp(8)));
-      AD_TRY(launch_attention(dt, temp(2), temp(7), temp(8), vt, B, L, Lk, Cc, d, Cc, Cc, vt ? lkp : Cc, Cc, temp(5), s));
+      // keys / values of the text: taken from the per-run cache when it was built from this embedding
+      const void* tk = temp(7);
+      const void* tv = temp(8);
+      if (c.text_cached == text) {
+        tk = work(c.text_k_off[ui][k]);
+        tv = work(c.text_v_off[ui][k]);
+      } else {
+        AD_TRY(text_kv(w, temp(7), temp(8)));
+      }
+      AD_TRY(launch_attention(dt, temp(2), tk, tv, vt, B, L, Lk, Cc, d, Cc, Cc, vt ? lkp : Cc, Cc, temp(5), s));
       AD_TRY(linear(temp(5), M, Cc, w + 12, w + 13, h, h));
       AD_TRY(ln(h, M, Cc, w + 14, temp(0)));
       AD_TRY(linear(temp(0), M, Cc, w + 16, w + 17, nullptr, temp(6), OUT_GEGLU));
@@ -205,6 +222,23 @@ static ad_status run_component(Ctx& c, int comp, int lane, const void* const* in
         break;
     }
   }
+  return AD_OK;
+}
+
+// Cross-attention keys and values depend only on the text embedding: compute them once per run.
+static ad_status precompute_text(Ctx& c, const void* text, hipStream_t s) {
+  static const void* const no_in[1] = {nullptr};
+  static void* const no_out[1] = {nullptr};
+  c.text_cached = nullptr;
+  for (int ui = 0; ui < (int)c.units.size(); ++ui) {
+    const Unit& u = c.units[ui];
+    if (u.info.kind != AD_UNIT_TFM) continue;
+    const int comp = u.comp;
+    Eval e{c, c.comps[comp - 1], c.ws[comp - 1][0], no_in, no_out, text, s, c.cfg.dtype};
+    for (int k = 0; k < u.info.depth; ++k)
+      AD_TRY(e.text_kv(u.w_first + 4 + 20 * k, c.work_dev + c.text_k_off[ui][k], c.work_dev + c.text_v_off[ui][k]));
+  }
+  c.text_cached = text;
   return AD_OK;
 }
 
@@ -293,6 +327,16 @@ ad_status ad_load_weights(ad_ctx* ctx, const float* const* host_ptrs, int n) {
       pack_rows(dt, src, (size_t)sh[0] * sh[1], temb_w.data() + temb_row * c.temb_dim * esize(dt));
       continue;
     }
+    if (w.role == W_QKV_KV) continue;     // packed together with q
+    if (w.role == W_QKV_Q) {
+      const size_t each = (size_t)sh[0] * sh[1];
+      std::vector<float> cat(3 * each);
+      for (int j = 0; j < 3; ++j) std::memcpy(cat.data() + j * each, host_ptrs[i + j], each * 4);
+      stage.assign(w.dev_bytes, 0);
+      pack_conv(dt, cat.data(), 3 * sh[0], sh[1], 1, false, stage.data());
+      AD_HIP(hipMemcpy(c.weights_dev + w.dev_off, stage.data(), w.dev_bytes, hipMemcpyHostToDevice));
+      continue;
+    }
     if (w.role == W_TEMB_BIAS) {
       std::memcpy(temb_b.data() + temb_row, src, (size_t)sh[0] * 4);
       temb_row += sh[0];
@@ -354,6 +398,16 @@ ad_status ad_component_forward(ad_ctx* ctx, int comp, int lane, const void* cons
   if (needs_text && !text_emb) AD_FAIL(AD_ERR_INVALID, "text_emb is null");
   set_profiler(prof_of(c));
   ad_status st = run_component(c, comp, lane, hidden_in, c.taus[t_index], latent_scale, text_emb, pooled_emb, hidden_out, (hipStream_t)stream);
+  set_profiler(nullptr);
+  return st;
+}
+
+ad_status ad_precompute_text(ad_ctx* ctx, const void* text_emb, ad_stream stream) {
+  if (!ctx || !text_emb) AD_FAIL(AD_ERR_INVALID, "null argument");
+  Ctx& c = *C(ctx);
+  if (!c.weights_loaded) AD_FAIL(AD_ERR_STATE, "weights are not loaded");
+  set_profiler(prof_of(c));
+  ad_status st = precompute_text(c, text_emb, (hipStream_t)stream);
   set_profiler(nullptr);
   return st;
 }
@@ -426,7 +480,14 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
 
   // previous round closed with event 0 recorded on streams[0] (see the end of this function)
   hipStream_t s0 = (hipStream_t)streams[0];
-  if (c.rows[r0].round > 0)
+  bool fresh_text = false;
+  if (text_emb && c.text_cached != text_emb) {
+    // first round of a run (or a new embedding): build the text key / value cache ahead of everything else
+    AD_TRY(precompute_text(c, text_emb, s0));
+    AD_HIP(hipEventRecord(c.events[0], s0));
+    fresh_text = true;
+  }
+  if (c.rows[r0].round > 0 || fresh_text)
     for (int k = 1; k < ns; ++k) AD_HIP(hipStreamWaitEvent((hipStream_t)streams[k], c.events[0], 0));
 
   std::vector<int> eps_steps, eps_lane;
