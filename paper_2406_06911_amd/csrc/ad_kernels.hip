@@ -539,11 +539,12 @@ __device__ __forceinline__ float other_half(float x, bool low) {
   return __uint_as_float(low ? r[1] : r[0]);
 }
 
+constexpr int kAttnStage = 2 * 64 * kPitch;   // one K tile and one V^T tile (64 rows of 128 bytes + pad each)
+
 __global__ __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                    const bf16* __restrict__ Vt, bf16* __restrict__ O, int L, int Lk,
                                                    int C, int ldq, int ldk, int ldv, int ldo, float scale_log2) {
-  __shared__ __attribute__((aligned(16))) char Ks[64 * kPitch];
-  __shared__ __attribute__((aligned(16))) char Vs[64 * kPitch];
+  __shared__ __attribute__((aligned(16))) char lds[2 * kAttnStage];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
   const bool low = half == 0;
   const int b = blockIdx.z, h = blockIdx.y;
@@ -563,27 +564,50 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, c
   float m_run = -INFINITY, l_run = 0.f;
   const int srow = tid >> 3, scol = tid & 7;
   const int ntiles = (Lk + 63) / 64;
-  for (int t = 0; t < ntiles; ++t) {
+  const bf16* kbase = K + (size_t)b * Lk * ldk + h * 64 + scol * 8;
+  const bf16* vbase = Vt + ((size_t)b * C + h * 64) * ldv + scol * 8;
+
+  // the next tile travels through registers while the current one is multiplied
+  bf16x8 kr[2], vr[2];
+  auto load_tile = [&](int t) {
     const int key0 = t * 64;
-    __syncthreads();
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int row = srow + 32 * i;
-      bf16x8 kv, vv;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) kv[e] = (bf16)0.f;
-      if (key0 + row < Lk) kv = *(const bf16x8*)(K + ((size_t)b * Lk + key0 + row) * ldk + h * 64 + scol * 8);
-      *(bf16x8*)(Ks + row * kPitch + scol * 16) = kv;
-      const int kb = key0 + scol * 8;
-      vv = *(const bf16x8*)(Vt + ((size_t)b * C + h * 64 + row) * ldv + kb);
-      if (kb + 8 > Lk) {
+      for (int e = 0; e < 8; ++e) kr[i][e] = (bf16)0.f;
+      if (key0 + row < Lk) kr[i] = *(const bf16x8*)(kbase + (size_t)(key0 + row) * ldk);
+      vr[i] = *(const bf16x8*)(vbase + (size_t)row * ldv + key0);       // in bounds: ldv is padded to 64 keys
+    }
+  };
+  auto store_tile = [&](int t) {
+    char* st = lds + (t & 1) * kAttnStage;
+    const int kb = t * 64 + scol * 8;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = srow + 32 * i;
+      bf16x8 vv = vr[i];
+      if (kb + 8 > Lk) {        // keys past the end must not contribute, whatever the pad holds
 #pragma unroll
         for (int e = 0; e < 8; ++e)
           if (kb + e >= Lk) vv[e] = (bf16)0.f;
       }
-      *(bf16x8*)(Vs + row * kPitch + scol * 16) = vv;
+      *(bf16x8*)(st + row * kPitch + scol * 16) = kr[i];
+      *(bf16x8*)(st + 64 * kPitch + row * kPitch + scol * 16) = vv;
     }
-    __syncthreads();
+  };
+
+  load_tile(0);
+  store_tile(0);
+  if (ntiles > 1) load_tile(1);
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    if (t + 1 < ntiles) {
+      store_tile(t + 1);
+      if (t + 2 < ntiles) load_tile(t + 2);
+    }
+    const char* Ks = lds + (t & 1) * kAttnStage;
+    const char* Vs = Ks + 64 * kPitch;
     f32x16 sc[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -595,32 +619,40 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, c
         sc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sc[j], 0, 0, 0);
       }
     }
-    float mx = -INFINITY;
+    if (t == ntiles - 1 && (Lk & 63)) {     // only the last tile can hold keys past the end
+      const int key0 = t * 64;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = key0 + j * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (key >= Lk) sc[j][r] = -INFINITY;
-        mx = fmaxf(mx, sc[j][r]);
-      }
+        for (int r = 0; r < 16; ++r)
+          if (key0 + j * 32 + 8 * (r >> 2) + 4 * half + (r & 3) >= Lk) sc[j][r] = -INFINITY;
+    }
+    float mx = sc[0][0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[0][r]);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[1][r]);
     mx = fmaxf(mx, other_half(mx, low));
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = exp2f((m_run - m_new) * scale_log2);
-    m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {     // some row maximum moved: rescale what was accumulated
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
+      l_run *= alpha;
+#pragma unroll
+      for (int d = 0; d < 2; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+      m_run = m_new;
+    }
+    const float neg = -m_run * scale_log2;
     float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        sc[j][r] = exp2f((sc[j][r] - m_new) * scale_log2);
+        sc[j][r] = __builtin_amdgcn_exp2f(fmaf(sc[j][r], scale_log2, neg));
         psum += sc[j][r];
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int d = 0; d < 2; ++d)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+    l_run += psum;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -638,6 +670,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, c
           o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[d], 0, 0, 0);
         }
       }
+    __syncthreads();
   }
   const float l_tot = l_run + other_half(l_run, low);
   if (query < L) {
