@@ -225,16 +225,18 @@ ad_status ad_profile_get(const ad_ctx* ctx, int index, ad_profile_rec* out); /* 
  *   ksize 1|3, stride 1|2, padding ksize/2;  w_packed: weights as produced by ad_pack_conv_weight;
  *   bias fp32 [n] or NULL; rowvec fp32 [batch][n] or NULL; residual [m][n] or NULL;
  *   out_mode 0: [m][n] dtype; 1: GEGLU (weights packed with geglu=1) -> [m][n/2]; 2: transposed
- *   [batch][n][ld_t] in dtype; 3: transposed fp32 [batch][n][ld_t].
+ *   [batch][n][ld_t] in dtype; 3: transposed fp32 [batch][n][ld_t]; 4: fused q/k/v projection, n_out = 3c:
+ *   columns [0,c) -> out [m][c], [c,2c) -> out2 [m][c], [2c,3c) -> out3, [batch][c][ld_t] when ld_t > 0 else [m][c]
+ *   (out2, out3 are ignored by the other modes).
  *   splitk_ws: optional fp32 scratch of splitk_bytes (ad_conv_workspace_bytes); with it, GEMMs with few output
  *   tiles and a long K are split along K and reduced in a second kernel (fixed summation order). */
 size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n_out, int c_in_total, int ksize, int out_mode);
 ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hs, int ws,
                           int up, int ksize, int stride, const void* w_packed, int n_out, const float* bias,
-                          const float* rowvec, const void* residual, void* out, int out_mode, int ld_t,
-                          void* splitk_ws, size_t splitk_bytes, ad_stream stream);
+                          const float* rowvec, const void* residual, void* out, void* out2, void* out3, int out_mode,
+                          int ld_t, void* splitk_ws, size_t splitk_bytes, ad_stream stream);
 /* Tuning knob for measurements: forces the block tile of ad_conv_forward and of every convolution / linear
- * layer of the process (1: 128x128, 3: 64x64, -1: automatic choice, the default).
+ * layer of the process (1: 128x128 tiles, 3: 64x64 tiles, -1: automatic choice, the default).
  * Results are the same up to rounding order. */
 ad_status ad_tune_conv_tile(int tile);
 /* Packs HOST fp32 weights [n_out][c_in][k][k] into the kernel layout (HOST out, dtype elements).

@@ -9,7 +9,7 @@ AD_DDIM, AD_EULER = 0, 1
 AD_BETA_LINEAR, AD_BETA_SCALED_LINEAR = 0, 1
 AD_OK, AD_ERR_INVALID, AD_ERR_NOMEM, AD_ERR_HIP, AD_ERR_DONE, AD_ERR_STATE = range(6)
 UNIT_KINDS = ["conv_in", "res", "tfm", "down", "up", "out"]
-OUT_ROWMAJOR, OUT_GEGLU, OUT_TRANSPOSED, OUT_TRANSPOSED_F32 = 0, 1, 2, 3
+OUT_ROWMAJOR, OUT_GEGLU, OUT_TRANSPOSED, OUT_TRANSPOSED_F32, OUT_QKV = 0, 1, 2, 3, 4
 
 lib_path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libasyncdiff.so")
 
@@ -106,7 +106,7 @@ def _load():
     L.ad_sampler_update_raw.argtypes = [vp, vp, sz, ci, cf, cf, cf, vp]
     L.ad_get_slot_tensor.argtypes = [vp, ci, ci, P(vp), P(sz)]
     L.ad_get_eps_buffer.argtypes = [vp, ci, P(vp), P(sz)]
-    L.ad_conv_forward.argtypes = [ci, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp, ci, ci, vp, sz, vp]
+    L.ad_conv_forward.argtypes = [ci, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp, vp, vp, ci, ci, vp, sz, vp]
     L.ad_conv_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci]; L.ad_conv_workspace_bytes.restype = sz
     L.ad_pack_conv_weight.argtypes = [ci, vp, ci, ci, ci, ci, vp, P(sz)]
     L.ad_groupnorm_scratch_bytes.argtypes = [ci, ci, ci]; L.ad_groupnorm_scratch_bytes.restype = sz

@@ -123,6 +123,164 @@ __device__ __forceinline__ V buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned vo
 
 // MODE: epilogue selected at compile time (the OUT_* value, or OUT_PARTIAL for split-K partial sums)
 constexpr int OUT_PARTIAL = 5;
+// Epilogue shared by the GEMM kernels.  A lane holds column l32 of each 32x32 tile; accumulator register
+// r is row 8*(r/4) + 4*half + r%4 of the tile.  Row-major outputs go through LDS (one 32-column slab of
+// the wavefront's tile at a time, fp32, so the result is rounded once) and leave as 4-element vectors
+// with the residual read the same way; transposed outputs store the 4 consecutive rows a lane holds as
+// one vector.  `stage` is the wavefront's private LDS area of WTM rows x 144 bytes; the caller has
+// synchronised the workgroup after its last read of the k-loop tiles.
+template <typename T> struct Vec4;
+template <> struct Vec4<bf16> { typedef bf16x4 type; };
+template <> struct Vec4<float> { typedef f32x4 type; };
+
+template <typename T, int BM, int WTM, int WTN, int TM, int TN, int MODE>
+__device__ __forceinline__ void igemm_epilogue(const IgemmParams& p, f32x16 (&acc)[TM][TN], int m0, int n0, int wave_m,
+                                               int wave_n, int l32, int half, char* stage) {
+  typedef typename Vec4<T>::type V4;
+  const int row_base = m0 + wave_m * WTM + 4 * half;
+  const int col_base = n0 + wave_n * WTN + l32;
+  if constexpr (MODE == OUT_PARTIAL) {
+    float* dst = p.partial + (size_t)blockIdx.y * p.M * p.N;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = col_base + j * 32;
+      if (col >= p.N) continue;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < p.M) dst[(size_t)row * p.N + col] = acc[i][j][r];
+        }
+    }
+  } else if constexpr (MODE == OUT_GEGLU) {
+    static_assert(TN % 2 == 0, "GEGLU needs a value and a gate tile per wavefront");
+    const int half_n = p.N >> 1;
+    const int lane = l32 + 32 * half;
+#pragma unroll
+    for (int j = 0; j < TN; j += 2) {
+      const int oc0 = (n0 + wave_n * WTN + j * 32) >> 1;       // packed columns: 32 value, 32 gate
+      const int cv = col_base + j * 32;
+      const float bv = p.bias ? p.bias[cv] : 0.f, bg = p.bias ? p.bias[cv + 32] : 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          *(float*)(stage + (i * 32 + 4 * half + 8 * (r >> 2) + (r & 3)) * kPitch + l32 * 4) =
+              (acc[i][j][r] + bv) * gelu_f(acc[i][j + 1][r] + bg);
+      const int c4 = (lane & 7) * 4;
+      if (oc0 + c4 < half_n) {
+#pragma unroll
+        for (int it = 0; it < WTM / 8; ++it) {
+          const int rl = it * 8 + (lane >> 3), row = m0 + wave_m * WTM + rl;
+          if (row >= p.M) continue;
+          const f32x4 v = *(const f32x4*)(stage + rl * kPitch + c4 * 4);
+          V4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = from_f<T>(v[e]);
+          *(V4*)((T*)p.out + (size_t)row * half_n + oc0 + c4) = o;
+        }
+      }
+    }
+  } else {
+    // sample index of a row: a tile spans at most two samples when a sample has at least BM rows
+    const int b0 = m0 / p.hw_out;
+    const int bnd = (b0 + 1) * p.hw_out;
+    const bool one_step = p.hw_out >= BM;
+    auto sample_of = [&](int row) { return one_step ? b0 + (row >= bnd ? 1 : 0) : row / p.hw_out; };
+    const int lane = l32 + 32 * half;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int slab = n0 + wave_n * WTN + j * 32;      // first column of this 32-column slab
+      const int col = slab + l32;
+      const float bias = (p.bias && col < p.N) ? p.bias[col] : 0.f;
+      bool transposed = MODE == OUT_TRANSPOSED || MODE == OUT_TRANSPOSED_F32;
+      int c3 = 0, which = 0;
+      if constexpr (MODE == OUT_QKV) {
+        c3 = p.N / 3; which = slab / c3;               // a slab never straddles two thirds (c3 is a multiple of 32)
+        transposed = which == 2 && p.ld_t > 0;
+      }
+      if (transposed) {
+        if (col >= p.N) continue;
+        const int ncols = MODE == OUT_QKV ? c3 : p.N, cc = MODE == OUT_QKV ? col - which * c3 : col;
+        void* dstp = MODE == OUT_QKV ? p.out3 : p.out;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int row = row_base + i * 32 + 8 * g;                // 4 consecutive rows: registers 4g .. 4g+3
+            if (row >= p.M) continue;
+            const int b = sample_of(row);
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              v[e] = acc[i][j][4 * g + e] + bias;
+              if (MODE != OUT_QKV && p.rowvec) v[e] += p.rowvec[(size_t)sample_of(row + e) * p.rowvec_ld + col];
+            }
+            const size_t o = ((size_t)b * ncols + cc) * p.ld_t + (row - b * p.hw_out);
+            if ((p.hw_out & 3) == 0 && (p.ld_t & 3) == 0 && row + 3 < p.M) {
+              if constexpr (MODE == OUT_TRANSPOSED_F32) *(f32x4*)((float*)dstp + o) = f32x4{v[0], v[1], v[2], v[3]};
+              else *(V4*)((T*)dstp + o) = V4{from_f<T>(v[0]), from_f<T>(v[1]), from_f<T>(v[2]), from_f<T>(v[3])};
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                if (row + e >= p.M) break;
+                const int be = sample_of(row + e);
+                const size_t oe = ((size_t)be * ncols + cc) * p.ld_t + (row + e - be * p.hw_out);
+                if constexpr (MODE == OUT_TRANSPOSED_F32) ((float*)dstp)[oe] = v[e];
+                else ((T*)dstp)[oe] = from_f<T>(v[e]);
+              }
+            }
+          }
+        continue;
+      }
+      // row-major: out [M][ncols] (the whole N, or one third of it for the fused q/k/v projection)
+      const int ncols = MODE == OUT_QKV ? c3 : p.N;
+      const int cslab = MODE == OUT_QKV ? slab - which * c3 : slab;
+      T* dst = (T*)(MODE == OUT_QKV ? (which == 0 ? p.out : which == 1 ? p.out2 : p.out3) : p.out);
+      const bool use_rowvec = MODE != OUT_QKV && p.rowvec != nullptr && col < p.N;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = acc[i][j][r] + bias;
+          if (use_rowvec) {
+            const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+            v += p.rowvec[(size_t)sample_of(row < p.M ? row : p.M - 1) * p.rowvec_ld + col];
+          }
+          *(float*)(stage + (i * 32 + 4 * half + 8 * (r >> 2) + (r & 3)) * kPitch + l32 * 4) = v;
+        }
+      const int c4 = (lane & 7) * 4;
+      const bool vec_ok = (ncols & 3) == 0;
+      if (slab + c4 < p.N) {
+#pragma unroll
+        for (int it = 0; it < WTM / 8; ++it) {
+          const int rl = it * 8 + (lane >> 3), row = m0 + wave_m * WTM + rl;
+          if (row >= p.M) continue;
+          f32x4 v = *(const f32x4*)(stage + rl * kPitch + c4 * 4);
+          const size_t o = (size_t)row * ncols + cslab + c4;
+          if (vec_ok) {
+            if (MODE == OUT_ROWMAJOR && p.residual) {
+              const V4 rv = *(const V4*)((const T*)p.residual + o);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] += to_f(rv[e]);
+            }
+            *(V4*)(dst + o) = V4{from_f<T>(v[0]), from_f<T>(v[1]), from_f<T>(v[2]), from_f<T>(v[3])};
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if (slab + c4 + e >= p.N) break;
+              float x = v[e];
+              if (MODE == OUT_ROWMAJOR && p.residual) x += to_f(((const T*)p.residual)[o + e]);
+              dst[o + e] = from_f<T>(x);
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
 template <typename T, int BM, int BN, int WGM, int WGN, int NSET, int MODE>
 __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
   typedef typename Vec<T>::type V;
@@ -256,99 +414,173 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
     }
   }
 
-  // epilogue: lane holds column l32 of each 32x32 tile; register r is row 8*(r/4) + 4*half + r%4
-  const int row_base = m0 + wave_m * WTM + 4 * half;
-  const int col_base = n0 + wave_n * WTN + l32;
-  if constexpr (MODE == OUT_PARTIAL) {
-    float* dst = p.partial + (size_t)blockIdx.y * p.M * p.N;
+  // the k-loop ended with a barrier: every wavefront is done with the tiles, LDS can be reused
+  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch));
+}
+
+// =================================================================================================
+// The same GEMM with the tiles brought into LDS by the load unit itself (buffer_load ... lds): no
+// VGPR staging, no ds_write (which shares the LDS pipe with the fragment reads and is the slower of
+// the two), and NSTAGE - 1 k-tiles in flight.  LDS rows are dense (128 bytes); the 16-byte column
+// of a row is XOR-swizzled with the row number so that fragment reads stay conflict-free.  A
+// wavefront's load covers 8 rows x 128 bytes = 1 KiB, written at m0 + lane * 16.  The loads are
+// issued from inline assembly so that the k-loop can wait for exactly the tile it is about to use.
+// =================================================================================================
+__device__ __forceinline__ void dma_load16(u32x4 rsrc, unsigned voffset, unsigned soffset, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+}
+__device__ __forceinline__ u32x4 make_rsrc_words(const void* base, unsigned bytes) {
+  const unsigned long long a = (unsigned long long)base;
+  return u32x4{(unsigned)a, (unsigned)(a >> 32) & 0xffffu, bytes, 0x00020000u};
+}
+// waits until at most n of this wavefront's vector-memory operations are outstanding (n < 64)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <typename T, int MODE, int NSTAGE>
+__global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
+  typedef typename Vec<T>::type V;
+  constexpr int BM = 128, BN = 128, WTM = 64, WTN = 64, TM = 2, TN = 2, AV = 4, BV = 4;
+  constexpr int BK = kRowBytes / (int)sizeof(T), ES = (int)sizeof(T), VN = Vec<T>::N;
+  constexpr int STAGE = (BM + BN) * kRowBytes;
+  constexpr int OPS = AV + BV;                   // loads per wavefront per k-tile
+  static_assert(NSTAGE >= 2 && NSTAGE <= 4 && OPS * (NSTAGE - 1) < 64, "pipeline depth");
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wave_m = wave >> 1, wave_n = wave & 1;
+  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+  const u32x4 rs0 = make_rsrc_words(p.src0, p.bytes0), rs1 = make_rsrc_words(p.src1, p.bytes1);
+  const u32x4 rsw = make_rsrc_words(p.w, p.bytes_w);
+
+  // lane -> (row of the wavefront's 8-row group, swizzled 16-byte column it fetches)
+  const int drow = wave * 8 + (lane >> 3);
+  const int scol = (lane & 7) ^ (lane >> 3);
+  int a_iy0[AV], a_ix0[AV], a_b[AV];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = col_base + j * 32;
-      if (col >= p.N) continue;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-          if (row < p.M) dst[(size_t)row * p.N + col] = acc[i][j][r];
-        }
-    }
-  } else if constexpr (MODE == OUT_GEGLU) {
-    static_assert(TN % 2 == 0, "GEGLU needs a value and a gate tile per wavefront");
-    const int half_n = p.N >> 1;
-#pragma unroll
-    for (int j = 0; j < TN; j += 2) {
-      const int oc = ((n0 + wave_n * WTN + j * 32) >> 1) + l32;      // packed columns: 32 value, 32 gate
-      if (oc >= half_n) continue;
-      const int cv = col_base + j * 32;
-      const float bv = p.bias ? p.bias[cv] : 0.f, bg = p.bias ? p.bias[cv + 32] : 0.f;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-          if (row < p.M)
-            ((T*)p.out)[(size_t)row * half_n + oc] = from_f<T>((acc[i][j][r] + bv) * gelu_f(acc[i][j + 1][r] + bg));
-        }
-    }
-  } else {
-    // sample index of a row: a tile spans at most two samples when a sample has at least BM rows
-    const int b0 = m0 / p.hw_out;
-    const int bnd = (b0 + 1) * p.hw_out;
-    const bool one_step = p.hw_out >= BM;
-    auto sample_of = [&](int row) { return one_step ? b0 + (row >= bnd ? 1 : 0) : row / p.hw_out; };
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = col_base + j * 32;
-      if (col >= p.N) continue;
-      const float bias = p.bias ? p.bias[col] : 0.f;
-      if constexpr (MODE == OUT_ROWMAJOR) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-            if (row >= p.M) continue;
-            float v = acc[i][j][r] + bias;
-            if (p.rowvec) v += p.rowvec[(size_t)sample_of(row) * p.rowvec_ld + col];
-            if (p.residual) v += to_f(((const T*)p.residual)[(size_t)row * p.N + col]);
-            ((T*)p.out)[(size_t)row * p.N + col] = from_f<T>(v);
-          }
-      } else if constexpr (MODE == OUT_QKV) {
-        const int c3 = p.N / 3, which = col / c3, cc = col - which * c3;
-        T* dst = (T*)(which == 0 ? p.out : which == 1 ? p.out2 : p.out3);
-        const bool transposed = which == 2 && p.ld_t > 0;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-            if (row >= p.M) continue;
-            const float v = acc[i][j][r] + bias;
-            if (transposed) {
-              const int b = sample_of(row);
-              dst[((size_t)b * c3 + cc) * p.ld_t + (row - b * p.hw_out)] = from_f<T>(v);
-            } else {
-              dst[(size_t)row * c3 + cc] = from_f<T>(v);
-            }
-          }
-      } else {   // OUT_TRANSPOSED, OUT_TRANSPOSED_F32
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-            if (row >= p.M) continue;
-            const int b = sample_of(row);
-            float v = acc[i][j][r] + bias;
-            if (p.rowvec) v += p.rowvec[(size_t)b * p.rowvec_ld + col];
-            const size_t o = ((size_t)b * p.N + col) * p.ld_t + (row - b * p.hw_out);
-            if constexpr (MODE == OUT_TRANSPOSED) ((T*)p.out)[o] = from_f<T>(v);
-            else ((float*)p.out)[o] = v;
-          }
-      }
+  for (int i = 0; i < AV; ++i) {
+    const int m = m0 + drow + 32 * i;
+    if (m < p.M) {
+      const int b = m / p.hw_out, r = m - b * p.hw_out;
+      const int oy = r / p.wout, ox = r - oy * p.wout;
+      a_b[i] = b * p.hs; a_iy0[i] = oy * p.stride - p.pad; a_ix0[i] = ox * p.stride - p.pad;
+    } else {
+      a_b[i] = -1; a_iy0[i] = 0; a_ix0[i] = 0;
     }
   }
+  unsigned b_off[BV];
+#pragma unroll
+  for (int i = 0; i < BV; ++i) b_off[i] = (unsigned)((n0 + drow + 32 * i) * p.Kp + scol * VN) * ES;
+  unsigned a_off0[AV], a_off1[AV];
+  auto set_tap = [&](int tap) {
+    const int u = tap / p.ksize, v = tap - u * p.ksize;
+#pragma unroll
+    for (int i = 0; i < AV; ++i) {
+      const int iy = a_iy0[i] + u, ix = a_ix0[i] + v;
+      const bool ok = a_b[i] >= 0 && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
+      const unsigned pix = (unsigned)((a_b[i] + (iy >> p.up)) * p.ws + (ix >> p.up));
+      a_off0[i] = ok ? (pix * (unsigned)p.c0 + scol * VN) * ES : kOob;
+      a_off1[i] = ok ? (pix * (unsigned)p.c1 + scol * VN) * ES : kOob;
+    }
+  };
+  const int kt_begin = blockIdx.y * p.kt_per_split;
+  const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
+  int f_k0 = kt_begin * BK;
+  int f_tap = f_k0 / p.ctot, f_cc = f_k0 - f_tap * p.ctot;
+  set_tap(f_tap);
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
+  const unsigned grp = (unsigned)wave * 8 * kRowBytes;      // this wavefront's 8-row group inside a 32-row slab
+  auto issue = [&](int stage) {
+    const unsigned st = lds_base + stage * STAGE + grp;
+    if (f_cc < p.c0) {
+#pragma unroll
+      for (int i = 0; i < AV; ++i) dma_load16(rs0, a_off0[i], (unsigned)(f_cc * ES), st + i * 32 * kRowBytes);
+    } else {
+#pragma unroll
+      for (int i = 0; i < AV; ++i) dma_load16(rs1, a_off1[i], (unsigned)((f_cc - p.c0) * ES), st + i * 32 * kRowBytes);
+    }
+#pragma unroll
+    for (int i = 0; i < BV; ++i) dma_load16(rsw, b_off[i], (unsigned)(f_k0 * ES), st + (BM + i * 32) * kRowBytes);
+    f_k0 += BK;
+    f_cc += BK;
+    if (f_cc >= p.ctot) {
+      f_cc = 0;
+      ++f_tap;
+      if (f_tap < p.ksize * p.ksize) set_tap(f_tap);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t)
+    if (t < nkt) issue(t);
+  // fragment reads: row * 128 + ((chunk ^ (row & 7)) * 16), chunk = 2 ks + half
+  const int a_row = (wave_m * WTM + l32) * kRowBytes, b_row = (BM + wave_n * WTN + l32) * kRowBytes;
+  const int x7 = l32 & 7;
+  int stage = 0;
+  for (int kt = 0; kt < nkt; ++kt) {
+    // tiles issued after kt that may still be in flight: min(NSTAGE - 2, nkt - 1 - kt)
+    const int later = min(NSTAGE - 2, nkt - 1 - kt);
+    if (later >= 2) wait_vmcnt<2 * OPS>();
+    else if (later == 1) wait_vmcnt<OPS>();
+    else wait_vmcnt<0>();
+    __syncthreads();     // tile kt is complete for every wavefront; the stage read in iteration kt-1 is free again
+    if (kt + NSTAGE - 1 < nkt) {
+      int target = stage + NSTAGE - 1;
+      if (target >= NSTAGE) target -= NSTAGE;
+      issue(target);
+    }
+    const char* st = lds + stage * STAGE;
+#pragma unroll
+    for (int ks = 0; ks < kRowBytes / 32; ++ks) {
+      const int sw = ((ks * 2 + half) ^ x7) << 4;
+      V af[TM], bf[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i] = *(const V*)(st + a_row + i * 32 * kRowBytes + sw);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bf[j] = *(const V*)(st + b_row + j * 32 * kRowBytes + sw);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) Mma<T>::run(af[i], bf[j], acc[i][j]);
+    }
+    if (++stage == NSTAGE) stage = 0;
+  }
+  wait_vmcnt<0>();
+  __syncthreads();     // every wavefront is done reading the last tile: LDS can be reused by the epilogue
+  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch));
+}
+
+template <typename T, int MODE, int NSTAGE>
+static ad_status run_igemm_dma(const IgemmParams& p0, const char* name, hipStream_t s) {
+  IgemmParams p = p0;
+  p.tiles_n = (p.N + 127) / 128;
+  const int tiles_m = (p.M + 127) / 128;
+  constexpr int lds_bytes = NSTAGE * 256 * kRowBytes;
+  static bool attr_set = false;
+  if (!attr_set) {
+    AD_HIP(hipFuncSetAttribute((const void*)k_igemm_dma<T, MODE, NSTAGE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    attr_set = true;
+  }
+  const double in_bytes = (double)p.M * p.ctot * sizeof(T) * (p.stride == 2 ? 4 : 1) / (p.up ? 4 : 1);
+  const double out_cols = p.out_mode == OUT_GEGLU ? p.N / 2 : p.N;
+  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
+  const int splits = (p.ktiles + p.kt_per_split - 1) / p.kt_per_split;
+  hipLaunchKernelGGL((k_igemm_dma<T, MODE, NSTAGE>), dim3(p.tiles_n * tiles_m, splits), dim3(256), lds_bytes, s, p);
+  AD_HIP(hipGetLastError());
+  return AD_OK;
 }
 
 template <typename T, int BM, int BN, int WGM, int WGN, int NSET, int MODE>
@@ -411,14 +643,15 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
 enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_AUTO = -1 };
 static int g_tile_override = TILE_AUTO;
 
+
 static int choose_tile(long long m, int n, int out_mode) {
   const bool geglu = out_mode == OUT_GEGLU;   // needs a value and a gate tile in the same wavefront
   if (g_tile_override != TILE_AUTO && !geglu) return g_tile_override;
-  // Measured on the GEMM shapes of the SD-sized models (M <= 18432): the machine is far from full with
-  // large tiles, and the 64x64 tile (most workgroups, shortest dependent chain per k-tile) is fastest
-  // except for GEMMs wide enough to give 128x128 tiles at least two workgroups per CU.
+  // Measured on the GEMM shapes of the SD-sized models (M <= 18432): 128x128 tiles pay off once there is
+  // more than one of them per CU; below that the 64x64 tile (most workgroups, shortest dependent chain per
+  // k-tile) is faster.
   const long long tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
-  int best = (geglu || tiles128 >= 1024) ? TILE_128x128 : TILE_64x64;
+  int best = (geglu || tiles128 >= 288) ? TILE_128x128 : TILE_64x64;
   return best;
 }
 
@@ -428,7 +661,7 @@ static int choose_splits(long long m, int n, int ktiles, int out_mode, int tile)
   if (out_mode == OUT_GEGLU || n % 4) return 1;
   const int bm = tile == TILE_64x64 ? 64 : 128, bn = bm;
   const long long tiles = ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
-  if (tiles >= 512 || ktiles < 16) return 1;
+  if (tiles >= 400 || ktiles < 16) return 1;
   int splits = (int)((1024 + tiles - 1) / tiles);
   if (splits > ktiles / 8) splits = ktiles / 8;
   if (splits > 16) splits = 16;
@@ -502,7 +735,16 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
     case OUT_PARTIAL: AD_RUN(TT, BM_, OUT_PARTIAL); break;             \
     default: break;                                                    \
   }
-  if (mode == OUT_GEGLU) {
+  // bf16 GEMMs with enough 128x128 tiles to occupy the machine take the LDS-DMA kernel (measured 1.2-1.4x
+  // over the register-staged kernels there); everything else the 64x64 register-staged kernel.
+  const bool dma_mode = mode == OUT_ROWMAJOR || mode == OUT_GEGLU || mode == OUT_QKV || mode == OUT_PARTIAL;
+  if (h16 && dma_mode && (big || mode == OUT_GEGLU)) {
+    name = "igemm_bf16_128x128_dma";
+    if (mode == OUT_ROWMAJOR) return run_igemm_dma<bf16, OUT_ROWMAJOR, 2>(p, name, s);
+    if (mode == OUT_GEGLU) return run_igemm_dma<bf16, OUT_GEGLU, 2>(p, name, s);
+    if (mode == OUT_QKV) return run_igemm_dma<bf16, OUT_QKV, 2>(p, name, s);
+    st = run_igemm_dma<bf16, OUT_PARTIAL, 2>(p, "igemm_bf16_128x128_dma_splitk", s);
+  } else if (mode == OUT_GEGLU) {
     if (h16) AD_RUN(bf16, 128, OUT_GEGLU); else AD_RUN(float, 128, OUT_GEGLU);
   } else if (h16) {
     if (big) { AD_MODES(bf16, 128) } else { AD_MODES(bf16, 64) }
@@ -1146,9 +1388,9 @@ extern "C" {
 
 ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hs, int ws,
                           int up, int ksize, int stride, const void* w_packed, int n_out, const float* bias,
-                          const float* rowvec, const void* residual, void* out, int out_mode, int ld_t, void* splitk_ws,
-                          size_t splitk_bytes, ad_stream stream) {
-  ConvArgs a{dtype, src0, src1, c0, c1, batch, hs, ws, up, ksize, stride, w_packed, n_out, bias, rowvec, n_out, residual, out, out_mode, ld_t, splitk_ws, splitk_bytes};
+                          const float* rowvec, const void* residual, void* out, void* out2, void* out3, int out_mode, int ld_t,
+                          void* splitk_ws, size_t splitk_bytes, ad_stream stream) {
+  ConvArgs a{dtype, src0, src1, c0, c1, batch, hs, ws, up, ksize, stride, w_packed, n_out, bias, rowvec, n_out, residual, out, out_mode, ld_t, splitk_ws, splitk_bytes, out2, out3};
   return launch_conv(a, (hipStream_t)stream);
 }
 

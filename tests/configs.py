@@ -21,6 +21,10 @@ CONFIGS = {
     "sd21_narrow": dict(latent_channels=4, height=24, width=24, batch=2, channels=[64, 128, 256, 256],
                         layers_per_block=2, transformer_depth=[1, 1, 1, 0], mid_depth=1, head_dim=64, gn_groups=32,
                         ctx_len=77, ctx_dim=1024, pooled_dim=0),
+    # reduced-width clone of the SDXL-shaped model: no attention at level 0, deeper transformers below, pooled branch
+    "sdxl_narrow": dict(latent_channels=4, height=32, width=32, batch=2, channels=[64, 128, 256],
+                        layers_per_block=2, transformer_depth=[0, 1, 2], mid_depth=2, head_dim=64, gn_groups=32,
+                        ctx_len=77, ctx_dim=256, pooled_dim=128),
 }
 
 RUNS = {
@@ -29,4 +33,5 @@ RUNS = {
     "sd21_768": dict(N=4, T=50, w=3, S=1, sampler="ddim", cfg_scale=7.5, dtype="bf16"),
     "sdxl_1024": dict(N=4, T=50, w=3, S=2, sampler="euler", cfg_scale=7.5, dtype="bf16"),
     "sd21_narrow": dict(N=4, T=50, w=3, S=1, sampler="ddim", cfg_scale=7.5, dtype="bf16"),
+    "sdxl_narrow": dict(N=4, T=50, w=3, S=2, sampler="euler", cfg_scale=7.5, dtype="bf16"),
 }

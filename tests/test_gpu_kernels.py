@@ -58,7 +58,7 @@ def run_conv(dtype, x0, x1, w, bias, stride=1, up=0, rowvec=None, residual=None,
     ws_bytes = lib.ad_conv_workspace_bytes(dtype, n, ho, wo, n_out, c0 + c1, k, mode) if splitk else 0
     wsb = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=DEV)
     B.check(lib.ad_conv_forward(dtype, p(d0), p(d1), c0, c1, n, hs, ws, up, k, stride, p(wp), n_out, p(db), p(drow), p(dres),
-                                p(out), mode, ld_t, p(wsb) if ws_bytes else None, ws_bytes, stream_ptr()))
+                                p(out), None, None, mode, ld_t, p(wsb) if ws_bytes else None, ws_bytes, stream_ptr()))
     run_conv.last_ws_bytes = ws_bytes
     sync()
     return host(out), (ho, wo)
@@ -120,6 +120,53 @@ def test_conv_epilogues(dtype):
         got, (ho, wo) = run_conv(dtype, x, None, w, bias, mode=mode)
         ref = P.conv2d(x, w, bias).reshape(n, n_out, ho * wo)
         assert rel_l2(got[:, :, :ho * wo], ref) < TOL[dtype]
+
+
+@pytest.fixture
+def force_big_tiles():
+    """Forces the 128x128-tile kernels (for bf16 the LDS-DMA kernel) on shapes that would take the small tile."""
+    B.check(lib.ad_tune_conv_tile(1))
+    yield
+    B.check(lib.ad_tune_conv_tile(-1))
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("case", CONV_CASES[:5], ids=[c[0] for c in CONV_CASES[:5]])
+def test_conv_big_tile_kernels(dtype, case, force_big_tiles):
+    test_conv_matches_direct_summation(dtype, case)
+    test_conv_epilogues(dtype)
+    test_linear_and_geglu(dtype)
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("big", [False, True])
+@pytest.mark.parametrize("vt", [False, True])
+def test_fused_qkv_projection(dtype, big, vt):
+    """One GEMM for q, k, v: thirds of the output columns go to three tensors, the last optionally transposed."""
+    bsz, l, c = 2, 72, 64
+    if big:
+        B.check(lib.ad_tune_conv_tile(1))
+    try:
+        x = quantize(SI.make_array((bsz * l, c), 35), dtype)
+        w = quantize(SI.make_array((3 * c, c), 36, 0.2), dtype)
+        dx = dev(x, dtype)
+        wp = dev_bytes(B.pack_conv_weight(dtype, w))
+        ld_t = 128 if vt else 0
+        q = torch.full((bsz * l, c), float("nan"), device=DEV, dtype=tdtype(dtype))
+        k = torch.full((bsz * l, c), float("nan"), device=DEV, dtype=tdtype(dtype))
+        v = torch.full((bsz, c, ld_t) if vt else (bsz * l, c), float("nan"), device=DEV, dtype=tdtype(dtype))
+        B.check(lib.ad_conv_forward(dtype, p(dx), None, c, 0, bsz, l, 1, 0, 1, 1, p(wp), 3 * c, None, None, None, p(q), p(k), p(v),
+                                    B.OUT_QKV, ld_t, None, 0, stream_ptr()))
+        sync()
+    finally:
+        B.check(lib.ad_tune_conv_tile(-1))
+    ref = P.linear(x, w)
+    assert rel_l2(host(q), ref[:, :c]) < TOL[dtype] and rel_l2(host(k), ref[:, c:2 * c]) < TOL[dtype]
+    if vt:
+        got = host(v)[:, :, :l]
+        assert rel_l2(got, ref[:, 2 * c:].reshape(bsz, l, c).transpose(0, 2, 1)) < TOL[dtype]
+    else:
+        assert rel_l2(host(v), ref[:, 2 * c:]) < TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype", DT)

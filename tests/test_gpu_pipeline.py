@@ -249,6 +249,32 @@ def test_narrow_sd_bf16_full_trajectory():
     assert err < 5e-2
 
 
+def test_narrow_sdxl_bf16_stride2_euler_pooled():
+    """Reduced-width clone of the SDXL-shaped configuration: pooled-embedding branch, transformer depth 1/2, Euler
+    sampler, stride 2, N=4, w=3: per-component parity over warm-up and the first rounds, then a short trajectory."""
+    r = RUNS["sdxl_narrow"]
+    case = Case("sdxl_narrow", B.AD_BF16, r["N"], r["w"], r["S"], 9, sampler=r["sampler"], cfg_scale=r["cfg_scale"])
+    log = []
+    worst = run_components_isolated(case, log)
+    xs = case.oracle.run(case.noise, case.text, case.pooled)
+    latent, rounds = run_steps(case, 5)
+    err = rel_l2(latent, xs[-1])
+    print(f"sdxl narrow bf16: worst per-component rel L2 {worst:.2e}, latent after 9 steps ({rounds} rounds) {err:.2e}")
+    assert rounds == len({row[0] for row in case.m.schedule()})
+    assert err < 5e-2
+
+
+def test_time_shift_fp32():
+    """Appendix A "Time Shifting": the time embedding lags one step after warm-up; table and arithmetic match the oracle."""
+    T = 8
+    case = Case("tiny", B.AD_F32, 3, 2, 1, T, std=0.1, time_shift=True)
+    xs = case.oracle.run(case.noise, case.text)
+    latent, _ = run_steps(case, 3)
+    assert rel_l2(latent, xs[-1]) < 1e-4
+    plain = Case("tiny", B.AD_F32, 3, 2, 1, T, std=0.1, time_shift=False)
+    assert rel_l2(run_steps(plain, 3)[0], xs[-1]) > 1e-3        # the shift really changes the result
+
+
 def test_state_errors():
     m = ad.AsyncDiff(CONFIGS["tiny"], 2, 1, 1, B.AD_F32)
     m.reset(4)
