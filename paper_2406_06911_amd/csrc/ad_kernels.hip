@@ -644,14 +644,16 @@ enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_AUTO = -1 };
 static int g_tile_override = TILE_AUTO;
 
 
-static int choose_tile(long long m, int n, int out_mode) {
+static int choose_tile(long long m, int n, int ktiles, int out_mode) {
   const bool geglu = out_mode == OUT_GEGLU;   // needs a value and a gate tile in the same wavefront
   if (g_tile_override != TILE_AUTO && !geglu) return g_tile_override;
   // Measured on the GEMM shapes of the SD-sized models (M <= 18432): 128x128 tiles pay off once there is
   // more than one of them per CU; below that the 64x64 tile (most workgroups, shortest dependent chain per
   // k-tile) is faster.
   const long long tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
-  int best = (geglu || tiles128 >= 288) ? TILE_128x128 : TILE_64x64;
+  // very few rows and a long K (deepest level): taller tiles re-read the weights less often, split-K supplies the workgroups
+  const bool deep = m <= 512 && ktiles >= 64;
+  int best = (geglu || tiles128 >= 288 || deep) ? TILE_128x128 : TILE_64x64;
   return best;
 }
 
@@ -672,7 +674,7 @@ static int choose_splits(long long m, int n, int ktiles, int out_mode, int tile)
 
 size_t conv_workspace_bytes(int dtype, long long m, int n, int k, int out_mode) {
   const int ktiles = k / bk_elems(dtype);
-  const int splits = choose_splits(m, n, ktiles, out_mode, choose_tile(m, n, out_mode));
+  const int splits = choose_splits(m, n, ktiles, out_mode, choose_tile(m, n, ktiles, out_mode));
   return splits > 1 ? (size_t)splits * m * n * 4 : 0;
 }
 
@@ -714,7 +716,7 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   p.bytes0 = (unsigned)(in_elems * a.c0 * esize(a.dtype));
   p.bytes1 = a.c1 ? (unsigned)(in_elems * a.c1 * esize(a.dtype)) : p.bytes0;
   p.bytes_w = (unsigned)w_bytes;
-  const int tile = choose_tile(m, a.n_out, a.out_mode);
+  const int tile = choose_tile(m, a.n_out, p.ktiles, a.out_mode);
   int splits = choose_splits(m, a.n_out, p.ktiles, a.out_mode, tile);
   if (splits > 1 && (!a.splitk_ws || a.splitk_bytes < (size_t)splits * m * a.n_out * 4)) splits = 1;   // no scratch: plain launch
   p.kt_per_split = splits > 1 ? (p.ktiles + splits - 1) / splits : p.ktiles;
@@ -1132,6 +1134,62 @@ __global__ __launch_bounds__(256) void k_gn_apply(const T* __restrict__ src0, co
   }
 }
 
+// GroupNorm for small feature maps in one launch: a workgroup owns one (sample, group), keeps its
+// (C/G) x HW elements in registers, reduces them and writes the normalised result.
+constexpr int kGnSmallVecs = 8;    // 16-byte vectors a thread can hold (larger maps take the three-pass path)
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_gn_small(const T* __restrict__ src0, const T* __restrict__ src1, int c0, int c1, int hw,
+                                                  int groups, const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                  float eps, int silu, T* __restrict__ out) {
+  typedef typename Vec<T>::type V;
+  constexpr int VN = Vec<T>::N;
+  __shared__ float red[8];
+  const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ctot = c0 + c1, cpg = ctot / groups, vpp = cpg / VN;
+  const int ch0 = g * cpg;                               // first channel of the group in the concatenation
+  const bool second = ch0 >= c0;                         // the launcher guarantees a group does not straddle the sources
+  const T* src = second ? src1 : src0;
+  const int cs = second ? c1 : c0, coff = second ? ch0 - c0 : ch0;
+  const int nvec = hw * vpp;
+  V x[kGnSmallVecs];
+  float s = 0.f, q = 0.f;
+#pragma unroll
+  for (int k = 0; k < kGnSmallVecs; ++k) {
+    const int v = tid + 256 * k;
+    if (v < nvec) {
+      const int p = v / vpp, vi = v - p * vpp;
+      x[k] = *(const V*)(src + ((size_t)b * hw + p) * cs + coff + vi * VN);
+#pragma unroll
+      for (int e = 0; e < VN; ++e) { const float f = to_f(x[k][e]); s += f; q += f * f; }
+    }
+  }
+  s = wave_sum(s); q = wave_sum(q);
+  if (lane == 0) { red[wave * 2] = s; red[wave * 2 + 1] = q; }
+  __syncthreads();
+  const float n = (float)hw * cpg;
+  const float mean = (red[0] + red[2] + red[4] + red[6]) / n;
+  float var = (red[1] + red[3] + red[5] + red[7]) / n - mean * mean;
+  var = var < 0.f ? 0.f : var;
+  const float rstd = rsqrtf(var + eps);
+#pragma unroll
+  for (int k = 0; k < kGnSmallVecs; ++k) {
+    const int v = tid + 256 * k;
+    if (v < nvec) {
+      const int p = v / vpp, vi = v - p * vpp;
+      V o;
+#pragma unroll
+      for (int e = 0; e < VN; ++e) {
+        const int c = ch0 + vi * VN + e;
+        float y = (to_f(x[k][e]) - mean) * rstd * gamma[c] + beta[c];
+        if (silu) y = silu_f(y);
+        o[e] = from_f<T>(y);
+      }
+      *(V*)(out + ((size_t)b * hw + p) * ctot + ch0 + vi * VN) = o;
+    }
+  }
+}
+
 }  // namespace ad
 
 extern "C" size_t ad_groupnorm_scratch_bytes(int batch, int hw, int c) {
@@ -1146,6 +1204,14 @@ static ad_status run_groupnorm(const void* src0, const void* src1, int c0, int c
                                const float* gamma, const float* beta, float eps, int silu, void* out, void* scratch,
                                hipStream_t s) {
   const int ctot = c0 + c1, nchunk = gn_chunks(hw);
+  const int cpg = ctot / groups;
+  if (cpg % Vec<T>::N == 0 && c0 % cpg == 0 && (long long)hw * (cpg / Vec<T>::N) <= 256LL * kGnSmallVecs) {
+    ProfLaunch pl("gn_small", 0, 2.0 * batch * hw * ctot * sizeof(T), s, batch * hw, ctot, 0);
+    hipLaunchKernelGGL(k_gn_small<T>, dim3(groups, batch), dim3(256), 0, s, (const T*)src0, (const T*)src1, c0, c1, hw, groups, gamma, beta, eps,
+                       silu, (T*)out);
+    AD_HIP(hipGetLastError());
+    return AD_OK;
+  }
   float* partial = (float*)scratch;
   float* ss = partial + (size_t)batch * kGnMaxChunks * ctot * 2;
   const long long rows = (long long)batch * hw;
