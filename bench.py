@@ -142,7 +142,8 @@ def main():
         roofline = dict(kernel=dname, bound="mfma", achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                         frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, launches=da["calls"],
                         avg_launch_us=round(da["ms"] / da["calls"] * 1e3, 2),
-                        flops_per_launch=round(da["flops"] / da["calls"]))
+                        flops_per_launch=round(da["flops"] / da["calls"]),
+                        algorithmic_bytes_per_launch=round(da["bytes"] / da["calls"]))
     else:
         ach = da["bytes"] / (da["ms"] * 1e-3) / 1e9
         roofline = dict(kernel=dname, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",

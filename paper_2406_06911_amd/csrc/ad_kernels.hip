@@ -787,12 +787,16 @@ constexpr int kAttnStage = 2 * 64 * kPitch;   // one K tile and one V^T tile (64
 
 __global__ __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                    const bf16* __restrict__ Vt, bf16* __restrict__ O, int L, int Lk,
-                                                   int C, int ldq, int ldk, int ldv, int ldo, float scale_log2) {
+                                                   int C, int ldq, int ldk, int ldv, int ldo, float scale_log2, int qblocks) {
   __shared__ __attribute__((aligned(16))) char lds[2 * kAttnStage];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
   const bool low = half == 0;
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int query = blockIdx.x * 128 + wave * 32 + l32;
+  // one-dimensional grid, renumbered so that the query blocks of a (sample, head) run on one XCD and
+  // its keys and values are fetched into a single L2
+  const int vid = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = vid / qblocks, heads = C / 64;
+  const int b = bh / heads, h = bh - b * heads;
+  const int query = (vid - bh * qblocks) * 128 + wave * 32 + l32;
   bf16x8 qf[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
@@ -993,8 +997,9 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
   if (dtype == AD_BF16 && head_dim == 64 && v_t) {
     if (ldv < round_up(lk, 64) || (ldq | ldk | ldv | ldo) % 8) AD_FAIL(AD_ERR_INVALID, "attention: MFMA path needs padded, 8-aligned strides");
     ProfLaunch pl("attn_mfma_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s, batch * l, lk, c);
-    hipLaunchKernelGGL(k_attn_mfma, dim3((l + 127) / 128, heads, batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
-                       (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, scale * 1.44269504088896341f);
+    const int qblocks = (l + 127) / 128;
+    hipLaunchKernelGGL(k_attn_mfma, dim3(qblocks * heads * batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, scale * 1.44269504088896341f, qblocks);
   } else if (dtype == AD_BF16) {
     ProfLaunch pl("attn_simple_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s);
     hipLaunchKernelGGL(k_attn_simple<bf16>, dim3((l + 3) / 4, heads, batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
