@@ -37,6 +37,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", default="sd21_768")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams for the timed region (0 = one per concurrent evaluation)")
+    ap.add_argument("--graphs", type=int, default=0, help="1: replay full asynchronous rounds from HIP graphs; 0 (default): launch every kernel directly")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--shapes", action="store_true", help="print the per-shape GEMM/attention timings of the instrumented round to stderr")
     args = ap.parse_args()
@@ -85,11 +86,13 @@ def main():
     n_par = N + S - 1
     n_streams = args.streams if args.streams > 0 else n_par
     # ---- timed region: concurrent components -----------------------------------------------------
+    m.set_graph_mode(bool(args.graphs))
     lat, ss = fresh(n_streams)
     run_rounds(m, lat, text, ss, w + W)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     run_rounds(m, lat, text, ss, K)
+    t_host = time.perf_counter() - t1          # time the host needed to enqueue the K rounds
     torch.cuda.synchronize()
     t2 = time.perf_counter()
     sec = t2 - t1
@@ -99,6 +102,7 @@ def main():
     log(f"concurrent ({n_streams} streams): {steps_per_s:.2f} steps/s, {ms_per_step:.3f} ms/step")
     # ---- the same rounds on one stream (sequential UNet with the same kernels) ---------------------
     K2 = min(K, 10)
+    m.set_graph_mode(False)
     lat, ss = fresh(1)
     run_rounds(m, lat, text, ss, w + 1)
     torch.cuda.synchronize()
@@ -202,10 +206,11 @@ def main():
         "dtype": "bf16" if dtype == ad.AD_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: latent {d['latent_channels']}x{d['height']}x{d['width']}, batch {d['batch']} (guidance), "
                                f"N={N} components on {n_streams} HIP streams, warm-up {w}, stride {S}, {r['sampler']}",
-                   "n_components": N, "stride": S, "streams": n_streams, "flops_per_step": flops_step},
+                   "n_components": N, "stride": S, "streams": n_streams, "hip_graphs": bool(args.graphs), "flops_per_step": flops_step},
         "component_evals_per_s": round(steps_per_s / S * n_par, 2),
         "sequential_steps_per_s": round(seq_steps_per_s, 3),
         "concurrent_over_sequential": round(steps_per_s / seq_steps_per_s, 4),
+        "host_enqueue_ms_per_step": round(t_host / (K * S) * 1e3, 3),
         "mfma_frac_whole_step": round(flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline,
         "kernels": kernels,

@@ -186,6 +186,14 @@ ad_status ad_precompute_text(ad_ctx* ctx, const void* text_emb, ad_stream stream
 ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* pooled_emb,
                   const ad_stream* streams, int n_streams, int* steps_done);
 
+/* Graph mode (off by default): full asynchronous rounds are captured into a HIP graph the first time each
+ * slot parity is met (per-step scalars are read from a device table through a device-side step counter, so
+ * the captured launch arguments do not change from round to round) and replayed afterwards with one
+ * hipGraphLaunch on streams[0]; the host then enqueues one call per round instead of ~500 launches.  Warm-up
+ * rounds, trailing partial rounds and rounds under ad_profile_enable are launched directly.  The graphs are
+ * tied to the latent / text / pooled pointers, the streams and the run; a change re-captures. */
+ad_status ad_set_graph_mode(ad_ctx* ctx, int on);
+
 /* Sampler update of step `step_index` (Section 3.1, Eq. 3, read as deterministic DDIM; or Euler),
  * fused with the guidance combination eps = eps_u + g (eps_c - eps_u) (batch row 0 = conditional):
  *   x  DEVICE fp32 [C][H][W] in place;  eps  DEVICE fp32 [batch][C][H][W]. */

@@ -71,7 +71,7 @@ EXPORTS = [
     "ad_reset", "ad_get_timesteps", "ad_num_sched_rows", "ad_get_schedule", "ad_get_sampler_coeffs",
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
     "ad_conv_forward", "ad_conv_workspace_bytes", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
-    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text",
+    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode",
 ]
 
 
@@ -115,6 +115,7 @@ def _load():
     L.ad_attention_forward.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
     L.ad_tune_conv_tile.argtypes = [ci]
     L.ad_precompute_text.argtypes = [vp, vp, vp]
+    L.ad_set_graph_mode.argtypes = [vp, ci]
     L.ad_profile_enable.argtypes = [vp, ci]
     L.ad_profile_clear.argtypes = [vp]
     L.ad_profile_count.argtypes = [vp]
@@ -250,6 +251,9 @@ class AsyncDiff:
             return None
         check(st)
         return done.value
+
+    def set_graph_mode(self, on):
+        check(lib.ad_set_graph_mode(self._h, int(on)))
 
     def precompute_text(self, text_emb, stream):
         check(lib.ad_precompute_text(self._h, _ptr(text_emb), C.c_void_p(stream.cuda_stream)))

@@ -367,6 +367,8 @@ static void plan_work(Ctx& c) {
         for (int s = 0; s < 2; ++s) c.slot_off[s][u] = take(tensor_bytes(c, u));
   c.eps_off.clear();
   for (int j = 0; j < c.stride; ++j) c.eps_off.push_back(take(tensor_bytes(c, nu - 1)));
+  c.step_table_off = take((size_t)(kTrainSteps + 8) * sizeof(StepRec));
+  c.step_counter_off = take(256);
   c.text_k_off.assign(nu, {});
   c.text_v_off.assign(nu, {});
   for (int ui = 0; ui < nu; ++ui) {
@@ -621,6 +623,7 @@ ad_status ad_reset(ad_ctx* ctx, int T, int sampler_kind, int beta_kind, float cf
   c.next_row = 0;
   c.steps_done = 0;
   c.text_cached = nullptr;
+  c.step_table_ready = false;
   return AD_OK;
 }
 

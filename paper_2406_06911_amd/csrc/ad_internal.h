@@ -118,6 +118,21 @@ struct Ctx {
   std::vector<hipEvent_t> events;      // one per stream used + helpers
   hipEvent_t ev_pack = nullptr;
   void* profiler = nullptr;            // ad::Profiler*, owned
+
+  // per-step scalars on the device (timestep, input scale, sampler coefficients) and the step counter the
+  // kernels index them with; uploaded at the first round of a run
+  size_t step_table_off = 0, step_counter_off = 0;
+  bool step_table_ready = false;
+
+  // captured asynchronous rounds, one per slot parity (graph mode)
+  bool use_graphs = false;
+  struct RoundGraph {
+    hipGraphExec_t exec = nullptr;
+    hipGraph_t graph = nullptr;
+    const void* latent = nullptr; const void* text = nullptr; const void* pooled = nullptr;
+    std::vector<hipStream_t> streams;
+    float cfg_scale = 0.f;
+  } round_graph[2];
 };
 
 // host logic

@@ -62,10 +62,19 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
 // in_ld = 0 feeds every row the same input
 ad_status launch_linear_rows(int dtype, const float* in, int in_ld, int rows, int k, const void* w, const float* bias, int n,
                              int silu_in, int silu_out, int accumulate, float* out, hipStream_t s);
-ad_status launch_sinusoid(float tau, int dim, float* out, hipStream_t s);
+// Per-step scalars can be passed as immediates or looked up on the device: table[*counter + offset].  The
+// second form keeps the launch arguments identical from round to round, which a captured graph needs.
+struct StepRec { float tau, in_scale, cx, ce; };
+struct StepRef {
+  const StepRec* table = nullptr;   // nullptr: use the immediate value
+  const int* counter = nullptr;
+  int offset = 0;
+};
+ad_status launch_sinusoid(float tau, StepRef ref, int dim, float* out, hipStream_t s);
+ad_status launch_advance(int* counter, int by, hipStream_t s);
 // im2col of the fp32 latent [cl][h][w] (times scale) for the first 3x3 convolution: out [batch*h*w][kConvInK]
-ad_status launch_pack_latent(int dtype, const float* latent, float scale, int cl, int h, int w, int batch, void* out,
-                             hipStream_t s);
-ad_status launch_sampler(float* x, const float* eps, size_t n, int batch, float cx, float ce, float g, hipStream_t s);
+ad_status launch_pack_latent(int dtype, const float* latent, float scale, StepRef ref, int cl, int h, int w, int batch,
+                             void* out, hipStream_t s);
+ad_status launch_sampler(float* x, const float* eps, size_t n, int batch, float cx, float ce, StepRef ref, float g, hipStream_t s);
 
 }  // namespace ad

@@ -1362,7 +1362,8 @@ ad_status launch_linear_rows(int dtype, const float* in, int in_ld, int rows, in
 }
 
 // Sinusoidal timestep embedding [cos | sin], evaluated in double because tau * f reaches ~1e3 rad.
-__global__ void k_sinusoid(float tau, int dim, float* __restrict__ out) {
+__global__ void k_sinusoid(float tau, StepRef ref, int dim, float* __restrict__ out) {
+  if (ref.table) tau = ref.table[*ref.counter + ref.offset].tau;
   const int half = dim / 2;
   const int k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k >= half) return;
@@ -1371,18 +1372,30 @@ __global__ void k_sinusoid(float tau, int dim, float* __restrict__ out) {
   out[half + k] = (float)sin(a);
 }
 
-ad_status launch_sinusoid(float tau, int dim, float* out, hipStream_t s) {
+__global__ void k_advance(int* counter, int by) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *counter += by;
+}
+
+ad_status launch_advance(int* counter, int by, hipStream_t s) {
+  if (!counter) AD_FAIL(AD_ERR_INVALID, "advance: null counter");
+  hipLaunchKernelGGL(k_advance, dim3(1), dim3(64), 0, s, counter, by);
+  AD_HIP(hipGetLastError());
+  return AD_OK;
+}
+
+ad_status launch_sinusoid(float tau, StepRef ref, int dim, float* out, hipStream_t s) {
   if (!out || dim < 2 || dim % 2) AD_FAIL(AD_ERR_INVALID, "sinusoid: bad argument");
   ProfLaunch pl("sinusoid", 0, 0, s);
-  hipLaunchKernelGGL(k_sinusoid, dim3((dim / 2 + 63) / 64), dim3(64), 0, s, tau, dim, out);
+  hipLaunchKernelGGL(k_sinusoid, dim3((dim / 2 + 63) / 64), dim3(64), 0, s, tau, ref, dim, out);
   AD_HIP(hipGetLastError());
   return AD_OK;
 }
 
 // im2col of the latent for the first convolution: row (b, y, x), column tap * cl + c, zero padded to kConvInK.
 template <typename T>
-__global__ __launch_bounds__(256) void k_pack_latent(const float* __restrict__ latent, float scale, int cl, int h, int w,
-                                                     int batch, T* __restrict__ out) {
+__global__ __launch_bounds__(256) void k_pack_latent(const float* __restrict__ latent, float scale, StepRef ref, int cl, int h,
+                                                     int w, int batch, T* __restrict__ out) {
+  if (ref.table) scale = ref.table[*ref.counter + ref.offset].in_scale;
   const long long total = (long long)batch * h * w * kConvInK;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
     const int kk = (int)(i % kConvInK);
@@ -1399,21 +1412,25 @@ __global__ __launch_bounds__(256) void k_pack_latent(const float* __restrict__ l
   }
 }
 
-ad_status launch_pack_latent(int dtype, const float* latent, float scale, int cl, int h, int w, int batch, void* out,
-                             hipStream_t s) {
+ad_status launch_pack_latent(int dtype, const float* latent, float scale, StepRef ref, int cl, int h, int w, int batch,
+                             void* out, hipStream_t s) {
   if (!latent || !out || cl < 1 || 9 * cl > kConvInK || h < 1 || w < 1 || batch < 1) AD_FAIL(AD_ERR_INVALID, "pack_latent: bad argument");
   const long long total = (long long)batch * h * w * kConvInK;
   const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
   ProfLaunch pl("pack_latent", 0, (double)total * (dtype == AD_BF16 ? 2 : 4), s);
-  if (dtype == AD_BF16) hipLaunchKernelGGL(k_pack_latent<bf16>, dim3(blocks), dim3(256), 0, s, latent, scale, cl, h, w, batch, (bf16*)out);
-  else hipLaunchKernelGGL(k_pack_latent<float>, dim3(blocks), dim3(256), 0, s, latent, scale, cl, h, w, batch, (float*)out);
+  if (dtype == AD_BF16) hipLaunchKernelGGL(k_pack_latent<bf16>, dim3(blocks), dim3(256), 0, s, latent, scale, ref, cl, h, w, batch, (bf16*)out);
+  else hipLaunchKernelGGL(k_pack_latent<float>, dim3(blocks), dim3(256), 0, s, latent, scale, ref, cl, h, w, batch, (float*)out);
   AD_HIP(hipGetLastError());
   return AD_OK;
 }
 
 // Sampler: x <- cx * x + ce * eps, eps = eps_u + g (eps_c - eps_u) when batch == 2 (row 0 conditional).
 __global__ __launch_bounds__(256) void k_sampler(float* __restrict__ x, const float* __restrict__ eps, size_t n, int batch,
-                                                 float cx, float ce, float g) {
+                                                 float cx, float ce, StepRef ref, float g) {
+  if (ref.table) {
+    const StepRec r = ref.table[*ref.counter + ref.offset];
+    cx = r.cx; ce = r.ce;
+  }
   const size_t n4 = n / 4;
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
@@ -1432,7 +1449,7 @@ __global__ __launch_bounds__(256) void k_sampler(float* __restrict__ x, const fl
   }
 }
 
-ad_status launch_sampler(float* x, const float* eps, size_t n, int batch, float cx, float ce, float g, hipStream_t s) {
+ad_status launch_sampler(float* x, const float* eps, size_t n, int batch, float cx, float ce, StepRef ref, float g, hipStream_t s) {
   if (!x || !eps || n == 0) AD_FAIL(AD_ERR_INVALID, "sampler: bad argument");
   if (batch != 1 && batch != 2) AD_FAIL(AD_ERR_INVALID, "sampler: batch must be 1 (no guidance) or 2 (guidance)");
   if (((uintptr_t)x | (uintptr_t)eps) & 15 || (batch == 2 && (n % 4))) {
@@ -1443,7 +1460,7 @@ ad_status launch_sampler(float* x, const float* eps, size_t n, int batch, float 
   if (blocks < 1) blocks = 1;
   if (blocks > 2048) blocks = 2048;
   ProfLaunch pl("sampler", 0, (double)n * 4 * (2 + batch), s);
-  hipLaunchKernelGGL(k_sampler, dim3((unsigned)blocks), dim3(256), 0, s, x, eps, n, batch, cx, ce, g);
+  hipLaunchKernelGGL(k_sampler, dim3((unsigned)blocks), dim3(256), 0, s, x, eps, n, batch, cx, ce, ref, g);
   AD_HIP(hipGetLastError());
   return AD_OK;
 }
@@ -1495,7 +1512,7 @@ ad_status ad_tune_conv_tile(int tile) {
 
 ad_status ad_sampler_update_raw(void* x, const void* eps, size_t n, int batch, float c_x, float c_eps, float cfg_scale,
                                 ad_stream stream) {
-  return launch_sampler((float*)x, (const float*)eps, n, batch, c_x, c_eps, cfg_scale, (hipStream_t)stream);
+  return launch_sampler((float*)x, (const float*)eps, n, batch, c_x, c_eps, StepRef{}, cfg_scale, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -157,7 +157,7 @@ struct Eval {
 
 // temb = Lin2(SiLU(Lin1(sinusoid(tau)))) (+ pooled branch), then every ResBlock projection of the
 // component in one launch: proj[b][row] = temb_b[row] + sum_k SiLU(temb[b][k]) W[row][k].
-static ad_status time_projection(Eval& e, int tau, const void* pooled) {
+static ad_status time_projection(Eval& e, int tau, StepRef tau_ref, const void* pooled) {
   Ctx& c = e.c;
   const int B = c.cfg.batch, td = c.temb_dim, c0 = c.cfg.channels[0], dt = e.dt;
   float* sinus = e.f32area();
@@ -166,7 +166,7 @@ static ad_status time_projection(Eval& e, int tau, const void* pooled) {
   float* pool1 = temb + (size_t)B * td;
   float* proj = pool1 + 2 * (size_t)B * td;
   WView wv{c};
-  AD_TRY(launch_sinusoid((float)tau, c0, sinus, e.s));
+  AD_TRY(launch_sinusoid((float)tau, tau_ref, c0, sinus, e.s));
   // the sinusoid is the same for every batch row: evaluate the MLP on one row, broadcast below
   AD_TRY(launch_linear_rows(dt, sinus, 0, 1, c0, wv.at(0), wv.f32(1), td, 0, 1, 0, t1, e.s));
   AD_TRY(launch_linear_rows(dt, t1, 0, B, td, wv.at(2), wv.f32(3), td, 0, 0, 0, temb, e.s));
@@ -187,11 +187,11 @@ static ad_status time_projection(Eval& e, int tau, const void* pooled) {
 
 static ad_status run_component(Ctx& c, int comp, int lane, const void* const* in, int tau, float latent_scale,
                                const void* text, const void* pooled, void* const* out, hipStream_t s,
-                               hipEvent_t latent_consumed = nullptr) {
+                               hipEvent_t latent_consumed = nullptr, StepRef tau_ref = StepRef{}, StepRef scale_ref = StepRef{}) {
   const Component& cp = c.comps[comp - 1];
   Eval e{c, cp, c.ws[comp - 1][lane], in, out, text, s, c.cfg.dtype};
   const ad_unet_cfg& g = c.cfg;
-  AD_TRY(time_projection(e, tau, pooled));
+  AD_TRY(time_projection(e, tau, tau_ref, pooled));
   for (int ui = cp.first; ui <= cp.last; ++ui) {
     const Unit& u = c.units[ui];
     const ad_unit_info& f = u.info;
@@ -199,7 +199,7 @@ static ad_status run_component(Ctx& c, int comp, int lane, const void* const* in
       case AD_UNIT_CONV_IN: {
         const void* latent = e.tensor_in(-1);
         if (!latent) AD_FAIL(AD_ERR_STATE, "conv_in: missing latent");
-        AD_TRY(launch_pack_latent(e.dt, (const float*)latent, latent_scale, g.latent_channels, g.height, g.width, g.batch, e.temp(0), s));
+        AD_TRY(launch_pack_latent(e.dt, (const float*)latent, latent_scale, scale_ref, g.latent_channels, g.height, g.width, g.batch, e.temp(0), s));
         if (latent_consumed) AD_HIP(hipEventRecord(latent_consumed, s));
         AD_TRY(e.conv(e.temp(0), nullptr, kConvInK, 0, g.height, g.width, 0, 1, 1, u.w_first, u.w_first + 1, nullptr, nullptr, e.tensor_out(ui)));
         break;
@@ -291,6 +291,11 @@ void ad_destroy(ad_ctx* ctx) {
   if (c->profiler) { prof_clear(prof_of(*c)); delete prof_of(*c); }
   for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
   if (c->ev_pack) (void)hipEventDestroy(c->ev_pack);
+  if (c->round_graph[0].exec || c->round_graph[1].exec) (void)hipDeviceSynchronize();
+  for (auto& g : c->round_graph) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (g.graph) (void)hipGraphDestroy(g.graph);
+  }
   delete c;
 }
 
@@ -421,7 +426,7 @@ ad_status ad_ddim_update(ad_ctx* ctx, void* x, const void* eps, int step_index, 
   sampler_coeffs(c, step_index, &cx, &ce, &s0, &s1);
   const size_t n = (size_t)c.cfg.latent_channels * c.cfg.height * c.cfg.width;
   set_profiler(prof_of(c));
-  ad_status st = launch_sampler((float*)x, (const float*)eps, n, c.cfg.batch, (float)cx, (float)ce, cfg_scale, (hipStream_t)stream);
+  ad_status st = launch_sampler((float*)x, (const float*)eps, n, c.cfg.batch, (float)cx, (float)ce, StepRef{}, cfg_scale, (hipStream_t)stream);
   set_profiler(nullptr);
   return st;
 }
@@ -448,47 +453,24 @@ ad_status ad_get_eps_buffer(const ad_ctx* ctx, int j, void** ptr, size_t* bytes)
 }
 
 // One round of the table.  Streams: evaluation e of the round runs on streams[e % n]; every stream
-// first waits for the events that closed the previous round (the round reads the slot that round
-// wrote and overwrites the slot that round read), the sampler runs behind the last-component
-// evaluations and behind the latent read of component 1.
-ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* pooled_emb, const ad_stream* streams,
-                  int n_streams, int* steps_done) {
-  if (!ctx || !latent || !streams || n_streams < 1) AD_FAIL(AD_ERR_INVALID, "bad argument");
-  Ctx& c = *C(ctx);
-  if (!c.weights_loaded) AD_FAIL(AD_ERR_STATE, "weights are not loaded");
-  if (c.T == 0) AD_FAIL(AD_ERR_STATE, "ad_reset has not been called");
-  if (c.next_row >= c.rows.size()) {
-    if (steps_done) *steps_done = c.steps_done;
-    return AD_ERR_DONE;
-  }
-  struct ProfGuard { ProfGuard(Profiler* p) { set_profiler(p); } ~ProfGuard() { set_profiler(nullptr); } } guard(prof_of(c));
-  const int max_par = c.N + c.stride - 1;
-  const int ns = n_streams < max_par ? n_streams : max_par;
-  // events: [0..ns) end-of-round per stream, [ns..2ns) scratch for this round
-  while ((int)c.events.size() < 2 * max_par + 2) {
-    hipEvent_t ev;
-    AD_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
-    c.events.push_back(ev);
-  }
-  if (!c.ev_pack) AD_HIP(hipEventCreateWithFlags(&c.ev_pack, hipEventDisableTiming));
-
-  const size_t r0 = c.next_row;
-  size_t r1 = r0;
-  while (r1 < c.rows.size() && c.rows[r1].round == c.rows[r0].round) ++r1;
+// first waits for the event that opened the round (recorded on streams[0] behind the previous round, which
+// this round reads from and whose read slot it overwrites), the sampler runs behind the last-component
+// evaluations and behind the latent read of component 1, and streams[0] joins the other streams at the end.
+// Every per-step scalar is looked up on the device (table[counter + offset]) so that the launch arguments of
+// an asynchronous round depend only on its slot parity: such a round can be captured once and replayed.
+static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const void* text_emb, const void* pooled_emb,
+                               const ad_stream* streams, int ns, bool capturing, std::vector<int>* steps_out) {
   const bool warm = c.rows[r0].read_slot == c.rows[r0].write_slot;
   const int nu = (int)c.units.size();
-
-  // previous round closed with event 0 recorded on streams[0] (see the end of this function)
+  const int max_par = c.N + c.stride - 1;
   hipStream_t s0 = (hipStream_t)streams[0];
-  bool fresh_text = false;
-  if (text_emb && c.text_cached != text_emb) {
-    // first round of a run (or a new embedding): build the text key / value cache ahead of everything else
-    AD_TRY(precompute_text(c, text_emb, s0));
-    AD_HIP(hipEventRecord(c.events[0], s0));
-    fresh_text = true;
-  }
-  if (c.rows[r0].round > 0 || fresh_text)
-    for (int k = 1; k < ns; ++k) AD_HIP(hipStreamWaitEvent((hipStream_t)streams[k], c.events[0], 0));
+  const StepRec* table = (const StepRec*)(c.work_dev + c.step_table_off);
+  int* counter = (int*)(c.work_dev + c.step_counter_off);
+  const int base = c.steps_done;             // the device counter holds this value when the round runs
+
+  // open the round: the other streams start behind everything streams[0] has been given so far
+  AD_HIP(hipEventRecord(c.events[0], s0));
+  for (int k = 1; k < ns; ++k) AD_HIP(hipStreamWaitEvent((hipStream_t)streams[k], c.events[0], 0));
 
   std::vector<int> eps_steps, eps_lane;
   std::vector<hipStream_t> eps_stream;
@@ -512,11 +494,11 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
       else if (row.write_slot >= 0) out[i] = c.work_dev + c.slot_off[row.write_slot][u];
       else AD_FAIL(AD_ERR_STATE, "schedule row drops a stored tensor");
     }
-    double cx, ce, in_scale = 1.0, init_scale;
-    if (row.latent_step >= 0) sampler_coeffs(c, row.latent_step, &cx, &ce, &in_scale, &init_scale);
+    const StepRef tau_ref{table, counter, row.tau_step - base};
+    const StepRef scale_ref{table, counter, row.latent_step >= 0 ? row.latent_step - base : 0};
     // the sampler may overwrite the latent only after component 1 has consumed it
-    AD_TRY(run_component(c, row.comp, lane, in, c.taus[row.tau_step], (float)in_scale, text_emb, pooled_emb, out, s,
-                         row.latent_step >= 0 ? c.ev_pack : nullptr));
+    AD_TRY(run_component(c, row.comp, lane, in, c.taus[row.tau_step], 1.f, text_emb, pooled_emb, out, s,
+                         row.latent_step >= 0 ? c.ev_pack : nullptr, tau_ref, scale_ref));
     if (row.latent_step >= 0) { pack_recorded = true; pack_stream = s; }
     if (row.eps_step >= 0) { eps_steps.push_back(row.eps_step); eps_lane.push_back(lane); eps_stream.push_back(s); }
   }
@@ -528,21 +510,123 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
       AD_HIP(hipStreamWaitEvent(ss, c.events[1 + j], 0));
     }
   if (pack_recorded && pack_stream != ss) AD_HIP(hipStreamWaitEvent(ss, c.ev_pack, 0));
-  for (size_t j = 0; j < eps_steps.size(); ++j) {
-    double cx, ce, a, b;
-    sampler_coeffs(c, eps_steps[j], &cx, &ce, &a, &b);
-    const size_t n = (size_t)c.cfg.latent_channels * c.cfg.height * c.cfg.width;
-    AD_TRY(launch_sampler((float*)latent, (const float*)(c.work_dev + c.eps_off[eps_lane[j]]), n, c.cfg.batch, (float)cx,
-                          (float)ce, c.cfg_scale, ss));
-    c.steps_done = eps_steps[j] + 1;
+  const size_t n = (size_t)c.cfg.latent_channels * c.cfg.height * c.cfg.width;
+  for (size_t j = 0; j < eps_steps.size(); ++j)
+    AD_TRY(launch_sampler((float*)latent, (const float*)(c.work_dev + c.eps_off[eps_lane[j]]), n, c.cfg.batch, 0.f, 0.f,
+                          StepRef{table, counter, eps_steps[j] - base}, c.cfg_scale, ss));
+  // close the round: streams[0] joins every other stream, then moves the step counter on
+  for (int k = 1; k < ns; ++k) {
+    AD_HIP(hipEventRecord(c.events[max_par + k], (hipStream_t)streams[k]));
+    AD_HIP(hipStreamWaitEvent(s0, c.events[max_par + k], 0));
   }
-  // close the round: streams[0] waits for every other stream, then records the round event
-  if (!warm)
-    for (int k = 1; k < ns; ++k) {
-      AD_HIP(hipEventRecord(c.events[max_par + k], (hipStream_t)streams[k]));
-      AD_HIP(hipStreamWaitEvent(s0, c.events[max_par + k], 0));
+  AD_TRY(launch_advance(counter, (int)eps_steps.size(), s0));
+  (void)capturing;
+  if (steps_out) *steps_out = eps_steps;
+  return AD_OK;
+}
+
+static void drop_graph(Ctx::RoundGraph& g) {
+  if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  if (g.graph) (void)hipGraphDestroy(g.graph);
+  g.exec = nullptr; g.graph = nullptr;
+}
+
+ad_status ad_set_graph_mode(ad_ctx* ctx, int on) {
+  if (!ctx) AD_FAIL(AD_ERR_INVALID, "null argument");
+  Ctx& c = *C(ctx);
+  c.use_graphs = on != 0;
+  if (!c.use_graphs && (c.round_graph[0].exec || c.round_graph[1].exec)) {
+    AD_HIP(hipDeviceSynchronize());
+    for (auto& g : c.round_graph) drop_graph(g);
+  }
+  return AD_OK;
+}
+
+ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* pooled_emb, const ad_stream* streams,
+                  int n_streams, int* steps_done) {
+  if (!ctx || !latent || !streams || n_streams < 1) AD_FAIL(AD_ERR_INVALID, "bad argument");
+  Ctx& c = *C(ctx);
+  if (!c.weights_loaded) AD_FAIL(AD_ERR_STATE, "weights are not loaded");
+  if (c.T == 0) AD_FAIL(AD_ERR_STATE, "ad_reset has not been called");
+  if (c.next_row >= c.rows.size()) {
+    if (steps_done) *steps_done = c.steps_done;
+    return AD_ERR_DONE;
+  }
+  const int max_par = c.N + c.stride - 1;
+  const int ns = n_streams < max_par ? n_streams : max_par;
+  while ((int)c.events.size() < 2 * max_par + 2) {
+    hipEvent_t ev;
+    AD_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    c.events.push_back(ev);
+  }
+  if (!c.ev_pack) AD_HIP(hipEventCreateWithFlags(&c.ev_pack, hipEventDisableTiming));
+  hipStream_t s0 = (hipStream_t)streams[0];
+
+  if (!c.step_table_ready) {
+    // first round of a run: per-step scalars and the step counter go to the device (once, synchronously)
+    std::vector<StepRec> tab(c.T);
+    for (int i = 0; i < c.T; ++i) {
+      double cx, ce, in_scale, init_scale;
+      sampler_coeffs(c, i, &cx, &ce, &in_scale, &init_scale);
+      tab[i] = StepRec{(float)c.taus[i], (float)in_scale, (float)cx, (float)ce};
     }
-  AD_HIP(hipEventRecord(c.events[0], s0));
+    const int zero = c.steps_done;
+    AD_HIP(hipDeviceSynchronize());
+    AD_HIP(hipMemcpy(c.work_dev + c.step_table_off, tab.data(), tab.size() * sizeof(StepRec), hipMemcpyHostToDevice));
+    AD_HIP(hipMemcpy(c.work_dev + c.step_counter_off, &zero, sizeof(int), hipMemcpyHostToDevice));
+    AD_HIP(hipDeviceSynchronize());
+    c.step_table_ready = true;
+    for (auto& g : c.round_graph) drop_graph(g);      // the table belongs to the run; so do its graphs
+  }
+  if (text_emb && c.text_cached != text_emb) {
+    // first round of a run (or a new embedding): build the text key / value cache ahead of everything else
+    set_profiler(prof_of(c));
+    ad_status st = precompute_text(c, text_emb, s0);
+    set_profiler(nullptr);
+    if (st != AD_OK) return st;
+  }
+
+  const size_t r0 = c.next_row;
+  size_t r1 = r0;
+  while (r1 < c.rows.size() && c.rows[r1].round == c.rows[r0].round) ++r1;
+  const bool warm = c.rows[r0].read_slot == c.rows[r0].write_slot;
+  const bool full = !warm && (int)(r1 - r0) == max_par;
+  Profiler* prof = prof_of(c);
+  const bool profiling = prof && prof->on;
+  std::vector<int> done;
+  ad_status st = AD_OK;
+  if (c.use_graphs && full && !profiling) {
+    // an asynchronous full round depends on the step only through the device-side counter: capture it once
+    // per slot parity (and per set of caller pointers), then replay
+    Ctx::RoundGraph& g = c.round_graph[c.rows[r0].write_slot & 1];
+    bool same = g.exec && g.latent == latent && g.text == text_emb && g.pooled == pooled_emb && g.cfg_scale == c.cfg_scale &&
+                (int)g.streams.size() == ns;
+    for (int k = 0; same && k < ns; ++k) same = g.streams[k] == (hipStream_t)streams[k];
+    if (!same) {
+      if (g.exec) AD_HIP(hipStreamSynchronize(s0));   // a replay of the old graph may still be running
+      drop_graph(g);
+      AD_HIP(hipStreamBeginCapture(s0, hipStreamCaptureModeRelaxed));
+      st = enqueue_round(c, r0, r1, latent, text_emb, pooled_emb, streams, ns, true, &done);
+      hipGraph_t graph = nullptr;
+      const hipError_t e = hipStreamEndCapture(s0, &graph);
+      if (st != AD_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
+      if (e != hipSuccess) AD_FAIL(AD_ERR_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+      g.graph = graph;
+      AD_HIP(hipGraphInstantiate(&g.exec, g.graph, nullptr, nullptr, 0));
+      g.latent = latent; g.text = text_emb; g.pooled = pooled_emb; g.cfg_scale = c.cfg_scale;
+      g.streams.assign((const hipStream_t*)streams, (const hipStream_t*)streams + ns);
+    } else {
+      for (size_t r = r0; r < r1; ++r)
+        if (c.rows[r].eps_step >= 0) done.push_back(c.rows[r].eps_step);
+    }
+    AD_HIP(hipGraphLaunch(g.exec, s0));
+  } else {
+    set_profiler(prof);
+    st = enqueue_round(c, r0, r1, latent, text_emb, pooled_emb, streams, ns, false, &done);
+    set_profiler(nullptr);
+    if (st != AD_OK) return st;
+  }
+  for (int i : done) c.steps_done = i + 1 > c.steps_done ? i + 1 : c.steps_done;
   c.next_row = r1;
   if (steps_done) *steps_done = c.steps_done;
   return AD_OK;
