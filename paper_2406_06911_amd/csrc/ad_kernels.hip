@@ -11,6 +11,7 @@
 #include "ad_kernels.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace ad {
 
@@ -563,6 +564,191 @@ __global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
   igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch));
 }
 
+// =================================================================================================
+// Three-stage LDS-DMA GEMM.  Same tile layout in LDS as above; what differs is the order of work
+// inside a k-tile.  The loads of tile kt+2 are spread between the MFMAs of the first three k-steps of
+// tile kt (one every STEP MFMAs, so the load unit's queue never backs up into the issuing wavefront),
+// every fragment read is issued one k-step ahead of its use, and the workgroup barrier sits before
+// the last k-step: once it is passed, tile kt+1 has landed for everyone and everyone holds its last
+// fragments of tile kt in registers, so the first fragments of tile kt+1 are read during that last
+// k-step and the stage of tile kt can be refilled in the next iteration.  One workgroup per CU
+// (96 KiB for 128x128, 144 KiB for 256x128), 4 wavefronts in a 2 x 2 grid.
+// =================================================================================================
+template <typename T, int BM, int BN, int MODE>
+__global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
+  typedef typename Vec<T>::type V;
+  constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
+  constexpr int ES = (int)sizeof(T), VN = Vec<T>::N, BK = kRowBytes / ES;
+  constexpr int STAGE = (BM + BN) * kRowBytes, NSTAGE = 3;
+  constexpr int AG = BM / 32, BG = BN / 32, OPS = AG + BG;     // 8-row groups (= loads) per wavefront and k-tile
+  constexpr int NG = TM * TN, STEP = (3 * NG) / OPS;
+  static_assert(STEP >= 1 && OPS * STEP <= 3 * NG && TM + TN <= NG && OPS < 32, "schedule");
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wave_m = wave >> 1, wave_n = wave & 1;
+  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+  const u32x4 rs0 = make_rsrc_words(p.src0, p.bytes0), rs1 = make_rsrc_words(p.src1, p.bytes1);
+  const u32x4 rsw = make_rsrc_words(p.w, p.bytes_w);
+
+  // load i of a k-tile covers rows (4 i + wave) * 8 .. + 7 of the A tile (i < AG) or of the B tile
+  const int r8 = lane >> 3, scol = (lane & 7) ^ r8;
+  int a_iy0[AG], a_ix0[AG], a_b[AG];
+#pragma unroll
+  for (int i = 0; i < AG; ++i) {
+    const int m = m0 + (4 * i + wave) * 8 + r8;
+    if (m < p.M) {
+      const int b = m / p.hw_out, r = m - b * p.hw_out;
+      const int oy = r / p.wout, ox = r - oy * p.wout;
+      a_b[i] = b * p.hs; a_iy0[i] = oy * p.stride - p.pad; a_ix0[i] = ox * p.stride - p.pad;
+    } else {
+      a_b[i] = -1; a_iy0[i] = 0; a_ix0[i] = 0;
+    }
+  }
+  unsigned b_off[BG];
+#pragma unroll
+  for (int i = 0; i < BG; ++i) b_off[i] = (unsigned)((n0 + (4 * i + wave) * 8 + r8) * p.Kp + scol * VN) * ES;
+  unsigned a_off0[AG], a_off1[AG];
+  auto set_tap = [&](int tap) {
+    const int u = tap / p.ksize, v = tap - u * p.ksize;
+#pragma unroll
+    for (int i = 0; i < AG; ++i) {
+      const int iy = a_iy0[i] + u, ix = a_ix0[i] + v;
+      const bool ok = a_b[i] >= 0 && iy >= 0 && iy < p.hin && ix >= 0 && ix < p.win;
+      const unsigned pix = (unsigned)((a_b[i] + (iy >> p.up)) * p.ws + (ix >> p.up));
+      a_off0[i] = ok ? (pix * (unsigned)p.c0 + scol * VN) * ES : kOob;
+      a_off1[i] = ok ? (pix * (unsigned)p.c1 + scol * VN) * ES : kOob;
+    }
+  };
+  const int kt_begin = blockIdx.y * p.kt_per_split;
+  const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
+  int f_k0 = kt_begin * BK;
+  int f_tap = f_k0 / p.ctot, f_cc = f_k0 - f_tap * p.ctot;
+  set_tap(f_tap);
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
+  const unsigned grp = (unsigned)wave * 8 * kRowBytes;
+  // per-tile state of the loads being issued: which source holds the channels, and the scalar offsets
+  bool second = false;
+  u32x4 rsa = rs0;
+  unsigned soff_a = 0, soff_b = 0;
+  auto begin_tile = [&]() {
+    second = f_cc >= p.c0;
+    rsa = second ? rs1 : rs0;
+    soff_a = (unsigned)((second ? f_cc - p.c0 : f_cc) * ES);
+    soff_b = (unsigned)(f_k0 * ES);
+  };
+  auto issue_one = [&](int stage, int i) {
+    const unsigned st = lds_base + stage * STAGE + grp;
+    if (i < AG) dma_load16(rsa, second ? a_off1[i] : a_off0[i], soff_a, st + i * 32 * kRowBytes);
+    else dma_load16(rsw, b_off[i - AG], soff_b, st + (BM + (i - AG) * 32) * kRowBytes);
+  };
+  auto end_tile = [&]() {
+    f_k0 += BK;
+    f_cc += BK;
+    if (f_cc >= p.ctot) {
+      f_cc = 0;
+      ++f_tap;
+      if (f_tap < p.ksize * p.ksize) set_tap(f_tap);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t)
+    if (t < nkt) {
+      begin_tile();
+#pragma unroll
+      for (int i = 0; i < OPS; ++i) issue_one(t, i);
+      end_tile();
+    }
+  // fragment reads: row * 128 + ((chunk ^ (row & 7)) * 16), chunk = 2 ks + half
+  const int a_row = (wave_m * WTM + l32) * kRowBytes, b_row = (BM + wave_n * WTN + l32) * kRowBytes;
+  const int x7 = l32 & 7;
+  int sw[kRowBytes / 32];
+#pragma unroll
+  for (int ks = 0; ks < kRowBytes / 32; ++ks) sw[ks] = ((ks * 2 + half) ^ x7) << 4;
+  V fr[2][TM + TN];
+  auto read_frag = [&](const char* st, int ks, int r) {
+    fr[ks & 1][r] = r < TM ? *(const V*)(st + a_row + r * 32 * kRowBytes + sw[ks & 3])
+                           : *(const V*)(st + b_row + (r - TM) * 32 * kRowBytes + sw[ks & 3]);
+  };
+  int stage = 0;
+  // PHASE 2: a next tile follows and the tile after it is fetched; 1: a next tile follows; 0: last tile
+  auto k_tile = [&](auto phase) {
+    constexpr int PHASE = decltype(phase)::value;
+    int target = stage + NSTAGE - 1;
+    if (target >= NSTAGE) target -= NSTAGE;
+    int next = stage + 1;
+    if (next >= NSTAGE) next -= NSTAGE;
+    const char* st = lds + stage * STAGE;
+    const char* sn = lds + next * STAGE;
+    if (PHASE == 2) begin_tile();
+    int q = 0;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if (ks == 3 && PHASE >= 1) {
+        if (PHASE == 2) wait_vmcnt<OPS>(); else wait_vmcnt<0>();
+        __syncthreads();
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int g = i * TN + j;
+          Mma<T>::run(fr[ks & 1][i], fr[ks & 1][TM + j], acc[i][j]);
+          if (ks < 3 && g < TM + TN) read_frag(st, ks + 1, g);
+          if (ks == 3 && PHASE >= 1 && g < TM + TN) read_frag(sn, 4, g);
+          if (PHASE == 2 && q % STEP == 0 && q / STEP < OPS) issue_one(target, q / STEP);
+          __builtin_amdgcn_sched_barrier(0);
+          ++q;
+        }
+    }
+    if (PHASE == 2) end_tile();
+    stage = next;
+  };
+  if (nkt > 1) wait_vmcnt<OPS>(); else wait_vmcnt<0>();
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < TM + TN; ++r) read_frag(lds, 0, r);
+  int kt = 0;
+  for (; kt + 2 < nkt; ++kt) k_tile(std::integral_constant<int, 2>{});
+  for (; kt + 1 < nkt; ++kt) k_tile(std::integral_constant<int, 1>{});
+  k_tile(std::integral_constant<int, 0>{});
+  __syncthreads();     // every wavefront holds its last fragments: LDS can be reused by the epilogue
+  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch));
+}
+
+template <typename T, int BM, int BN, int MODE>
+static ad_status run_igemm_p3(const IgemmParams& p0, const char* name, hipStream_t s) {
+  IgemmParams p = p0;
+  p.tiles_n = (p.N + BN - 1) / BN;
+  const int tiles_m = (p.M + BM - 1) / BM;
+  constexpr int lds_bytes = 3 * (BM + BN) * kRowBytes;
+  static_assert(lds_bytes >= 4 * (BM / 2) * kPitch, "epilogue staging fits");
+  static bool attr_set = false;
+  if (!attr_set) {
+    AD_HIP(hipFuncSetAttribute((const void*)k_igemm_p3<T, BM, BN, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    attr_set = true;
+  }
+  const double in_bytes = (double)p.M * p.ctot * sizeof(T) * (p.stride == 2 ? 4 : 1) / (p.up ? 4 : 1);
+  const double out_cols = p.out_mode == OUT_GEGLU ? p.N / 2 : p.N;
+  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
+  const int splits = (p.ktiles + p.kt_per_split - 1) / p.kt_per_split;
+  hipLaunchKernelGGL((k_igemm_p3<T, BM, BN, MODE>), dim3(p.tiles_n * tiles_m, splits), dim3(256), lds_bytes, s, p);
+  AD_HIP(hipGetLastError());
+  return AD_OK;
+}
+
 template <typename T, int MODE, int NSTAGE>
 static ad_status run_igemm_dma(const IgemmParams& p0, const char* name, hipStream_t s) {
   IgemmParams p = p0;
@@ -639,30 +825,23 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
   }
 }
 
-// Tile shapes: block tile BM x BN, wavefront grid WGM x WGN (4 wavefronts).
-enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_AUTO = -1 };
+// Tile shapes.  The register-staged kernels (64x64, 128x128) serve fp32 and the transposed epilogues; bf16
+// GEMMs with a row-major, GEGLU, fused q/k/v or split-K epilogue take the three-stage LDS-DMA kernel with a
+// 128x128 or a 256x128 tile.
+enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_DMA2_128 = 4, TILE_P3_128 = 5, TILE_P3_256 = 6, TILE_AUTO = -1 };
 static int g_tile_override = TILE_AUTO;
 
+struct ConvPlan { int tile; int splits; };
 
-static int choose_tile(long long m, int n, int ktiles, int out_mode) {
-  const bool geglu = out_mode == OUT_GEGLU;   // needs a value and a gate tile in the same wavefront
-  if (g_tile_override != TILE_AUTO && !geglu) return g_tile_override;
-  // Measured on the GEMM shapes of the SD-sized models (M <= 18432): 128x128 tiles pay off once there is
-  // more than one of them per CU; below that the 64x64 tile (most workgroups, shortest dependent chain per
-  // k-tile) is faster.
-  const long long tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
-  // very few rows and a long K (deepest level): taller tiles re-read the weights less often, split-K supplies the workgroups
-  const bool deep = m <= 512 && ktiles >= 64;
-  int best = (geglu || tiles128 >= 288 || deep) ? TILE_128x128 : TILE_64x64;
-  return best;
+static bool dma_capable(int dtype, int out_mode) {
+  return dtype == AD_BF16 && (out_mode == OUT_ROWMAJOR || out_mode == OUT_GEGLU || out_mode == OUT_QKV);
 }
 
-// Split-K: GEMMs with few output tiles and a long K (the deep levels of the UNet: M = 288 .. 1152,
-// K up to 23040) are cut along K so that a few hundred workgroups exist.
-static int choose_splits(long long m, int n, int ktiles, int out_mode, int tile) {
+// Split-K for the register-staged kernels: GEMMs with few output tiles and a long K are cut along K so that a
+// few hundred workgroups exist.
+static int splits_by_tiles(long long m, int n, int ktiles, int out_mode, int bm) {
   if (out_mode == OUT_GEGLU || n % 4) return 1;
-  const int bm = tile == TILE_64x64 ? 64 : 128, bn = bm;
-  const long long tiles = ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
+  const long long tiles = ((m + bm - 1) / bm) * ((n + bm - 1) / bm);
   if (tiles >= 400 || ktiles < 16) return 1;
   int splits = (int)((1024 + tiles - 1) / tiles);
   if (splits > ktiles / 8) splits = ktiles / 8;
@@ -672,9 +851,56 @@ static int choose_splits(long long m, int n, int ktiles, int out_mode, int tile)
   return (ktiles + per - 1) / per;
 }
 
+// Cost of a (tile, splits) choice for the one-workgroup-per-CU kernels, in units of one 128x128 k-tile of one
+// workgroup (about 0.4 us): rounds of 256 workgroups x (k-tiles per workgroup + a fixed prologue / epilogue
+// share), a 256x128 tile costing 1.8 tiles of 128x128, plus the second pass of split-K (a launch and
+// (splits + 1/2) x M x N x 4 bytes through memory).
+static double plan_cost(long long m, int n, int ktiles, int bm, int splits) {
+  const long long wgs = ((m + bm - 1) / bm) * ((n + 127) / 128) * splits;
+  const long long rounds = (wgs + 255) / 256;
+  const int per = (ktiles + splits - 1) / splits;
+  double cost = (double)rounds * (per + 8) * (bm == 256 ? 1.8 : 1.0);
+  if (splits > 1) cost += 15.0 + (splits + 0.5) * (double)m * n * 4.0 / 2.5e12 / 0.4e-6;
+  return cost;
+}
+
+static ConvPlan choose_plan(int dtype, long long m, int n, int ktiles, int out_mode) {
+  const bool geglu = out_mode == OUT_GEGLU;   // needs a value and a gate tile in the same wavefront
+  const bool dma = dma_capable(dtype, out_mode);
+  int forced = g_tile_override;
+  if (forced == TILE_P3_128 || forced == TILE_P3_256 || forced == TILE_DMA2_128) { if (!dma) forced = TILE_AUTO; }
+  else if (forced != TILE_AUTO && geglu) forced = TILE_AUTO;
+  if (forced == TILE_128x128 || forced == TILE_64x64) return ConvPlan{forced, splits_by_tiles(m, n, ktiles, out_mode, forced == TILE_64x64 ? 64 : 128)};
+  if (forced == TILE_DMA2_128) return ConvPlan{forced, splits_by_tiles(m, n, ktiles, out_mode, 128)};
+  if (!dma) {
+    // measured on the GEMM shapes of the SD-sized models: 128x128 register-staged tiles pay off once there is
+    // more than one of them per CU, or with very few rows and a long K (the weights are re-read less often)
+    const long long tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
+    const int tile = (geglu || tiles128 >= 288 || (m <= 512 && ktiles >= 64)) ? TILE_128x128 : TILE_64x64;
+    return ConvPlan{tile, splits_by_tiles(m, n, ktiles, out_mode, tile == TILE_64x64 ? 64 : 128)};
+  }
+  // short K with more than a tile per CU: prologue and epilogue dominate, and two co-resident workgroups of the
+  // two-stage kernel (64 KiB each) overlap them; measured faster below about a dozen k-tiles
+  if (forced == TILE_AUTO && ktiles < 12 && ((m + 127) / 128) * ((n + 127) / 128) >= 256) return ConvPlan{TILE_DMA2_128, 1};
+  ConvPlan best{TILE_P3_128, 1};
+  double best_cost = 1e300;
+  const int max_splits = (geglu || n % 4) ? 1 : 16;
+  for (int tile : {TILE_P3_128, TILE_P3_256}) {
+    if (forced != TILE_AUTO && tile != forced) continue;
+    for (int sp = 1; sp <= max_splits; ++sp) {
+      if (sp > 1 && ktiles / sp < 4) break;
+      const int per = (ktiles + sp - 1) / sp;
+      if ((ktiles + per - 1) / per != sp) continue;          // every split must own at least one k-tile
+      const double c = plan_cost(m, n, ktiles, tile == TILE_P3_256 ? 256 : 128, sp);
+      if (c < best_cost) { best_cost = c; best = ConvPlan{tile, sp}; }
+    }
+  }
+  return best;
+}
+
 size_t conv_workspace_bytes(int dtype, long long m, int n, int k, int out_mode) {
   const int ktiles = k / bk_elems(dtype);
-  const int splits = choose_splits(m, n, ktiles, out_mode, choose_tile(m, n, ktiles, out_mode));
+  const int splits = choose_plan(dtype, m, n, ktiles, out_mode).splits;
   return splits > 1 ? (size_t)splits * m * n * 4 : 0;
 }
 
@@ -716,8 +942,9 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   p.bytes0 = (unsigned)(in_elems * a.c0 * esize(a.dtype));
   p.bytes1 = a.c1 ? (unsigned)(in_elems * a.c1 * esize(a.dtype)) : p.bytes0;
   p.bytes_w = (unsigned)w_bytes;
-  const int tile = choose_tile(m, a.n_out, p.ktiles, a.out_mode);
-  int splits = choose_splits(m, a.n_out, p.ktiles, a.out_mode, tile);
+  const ConvPlan plan = choose_plan(a.dtype, m, a.n_out, p.ktiles, a.out_mode);
+  const int tile = plan.tile;
+  int splits = plan.splits;
   if (splits > 1 && (!a.splitk_ws || a.splitk_bytes < (size_t)splits * m * a.n_out * 4)) splits = 1;   // no scratch: plain launch
   p.kt_per_split = splits > 1 ? (p.ktiles + splits - 1) / splits : p.ktiles;
   p.partial = splits > 1 ? (float*)a.splitk_ws : nullptr;
@@ -737,15 +964,24 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
     case OUT_PARTIAL: AD_RUN(TT, BM_, OUT_PARTIAL); break;             \
     default: break;                                                    \
   }
-  // bf16 GEMMs with enough 128x128 tiles to occupy the machine take the LDS-DMA kernel (measured 1.2-1.4x
-  // over the register-staged kernels there); everything else the 64x64 register-staged kernel.
-  const bool dma_mode = mode == OUT_ROWMAJOR || mode == OUT_GEGLU || mode == OUT_QKV || mode == OUT_PARTIAL;
-  if (h16 && dma_mode && (big || mode == OUT_GEGLU)) {
+#define AD_P3(BM_)                                                                                                    \
+  switch (mode) {                                                                                                     \
+    case OUT_ROWMAJOR: st = run_igemm_p3<bf16, BM_, 128, OUT_ROWMAJOR>(p, "igemm_bf16_" #BM_ "x128_p3", s); break;    \
+    case OUT_GEGLU: st = run_igemm_p3<bf16, BM_, 128, OUT_GEGLU>(p, "igemm_bf16_" #BM_ "x128_p3", s); break;          \
+    case OUT_QKV: st = run_igemm_p3<bf16, BM_, 128, OUT_QKV>(p, "igemm_bf16_" #BM_ "x128_p3", s); break;              \
+    case OUT_PARTIAL: st = run_igemm_p3<bf16, BM_, 128, OUT_PARTIAL>(p, "igemm_bf16_" #BM_ "x128_p3_splitk", s); break; \
+    default: break;                                                                                                   \
+  }
+  if (tile == TILE_P3_128) {
+    AD_P3(128)
+  } else if (tile == TILE_P3_256) {
+    AD_P3(256)
+  } else if (tile == TILE_DMA2_128) {
     name = "igemm_bf16_128x128_dma";
-    if (mode == OUT_ROWMAJOR) return run_igemm_dma<bf16, OUT_ROWMAJOR, 2>(p, name, s);
-    if (mode == OUT_GEGLU) return run_igemm_dma<bf16, OUT_GEGLU, 2>(p, name, s);
-    if (mode == OUT_QKV) return run_igemm_dma<bf16, OUT_QKV, 2>(p, name, s);
-    st = run_igemm_dma<bf16, OUT_PARTIAL, 2>(p, "igemm_bf16_128x128_dma_splitk", s);
+    if (mode == OUT_ROWMAJOR) st = run_igemm_dma<bf16, OUT_ROWMAJOR, 2>(p, name, s);
+    else if (mode == OUT_GEGLU) st = run_igemm_dma<bf16, OUT_GEGLU, 2>(p, name, s);
+    else if (mode == OUT_QKV) st = run_igemm_dma<bf16, OUT_QKV, 2>(p, name, s);
+    else st = run_igemm_dma<bf16, OUT_PARTIAL, 2>(p, "igemm_bf16_128x128_dma_splitk", s);
   } else if (mode == OUT_GEGLU) {
     if (h16) AD_RUN(bf16, 128, OUT_GEGLU); else AD_RUN(float, 128, OUT_GEGLU);
   } else if (h16) {
@@ -753,6 +989,7 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   } else {
     if (big) { AD_MODES(float, 128) } else { AD_MODES(float, 64) }
   }
+#undef AD_P3
 #undef AD_MODES
 #undef AD_RUN
   if (st != AD_OK || splits <= 1) return st;
@@ -785,7 +1022,10 @@ __device__ __forceinline__ float other_half(float x, bool low) {
 
 constexpr int kAttnStage = 2 * 64 * kPitch;   // one K tile and one V^T tile (64 rows of 128 bytes + pad each)
 
-__global__ __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+// three wavefronts per SIMD: the register budget of that occupancy (170) holds the score and output tiles in
+// ordinary VGPRs; left alone the compiler aims for four, spills the MFMA results to accumulation registers
+// and copies them back and forth around every softmax (about a third of the vector instructions of the loop)
+__global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                    const bf16* __restrict__ Vt, bf16* __restrict__ O, int L, int Lk,
                                                    int C, int ldq, int ldk, int ldv, int ldo, float scale_log2, int qblocks) {
   __shared__ __attribute__((aligned(16))) char lds[2 * kAttnStage];
@@ -1505,7 +1745,7 @@ size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n
 }
 
 ad_status ad_tune_conv_tile(int tile) {
-  if (tile != -1 && tile != 1 && tile != 3) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1 or 3");
+  if (tile != -1 && tile != 1 && tile != 3 && tile != 4 && tile != 5 && tile != 6) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1, 3, 4, 5 or 6");
   set_tile_override(tile);
   return AD_OK;
 }

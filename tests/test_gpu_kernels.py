@@ -122,10 +122,10 @@ def test_conv_epilogues(dtype):
         assert rel_l2(got[:, :, :ho * wo], ref) < TOL[dtype]
 
 
-@pytest.fixture
-def force_big_tiles():
-    """Forces the 128x128-tile kernels (for bf16 the LDS-DMA kernel) on shapes that would take the small tile."""
-    B.check(lib.ad_tune_conv_tile(1))
+@pytest.fixture(params=[1, 3, 4, 5, 6], ids=["reg128", "reg64", "dma2_128", "dma3_128", "dma3_256"])
+def force_big_tiles(request):
+    """Forces one GEMM kernel family on every shape (the LDS-DMA ones apply to bf16 only; fp32 keeps the automatic choice)."""
+    B.check(lib.ad_tune_conv_tile(request.param))
     yield
     B.check(lib.ad_tune_conv_tile(-1))
 
@@ -136,16 +136,17 @@ def test_conv_big_tile_kernels(dtype, case, force_big_tiles):
     test_conv_matches_direct_summation(dtype, case)
     test_conv_epilogues(dtype)
     test_linear_and_geglu(dtype)
+    test_conv_split_k(dtype)
 
 
 @pytest.mark.parametrize("dtype", DT)
-@pytest.mark.parametrize("big", [False, True])
+@pytest.mark.parametrize("big", [0, 1, 4, 5, 6])
 @pytest.mark.parametrize("vt", [False, True])
 def test_fused_qkv_projection(dtype, big, vt):
     """One GEMM for q, k, v: thirds of the output columns go to three tensors, the last optionally transposed."""
     bsz, l, c = 2, 72, 64
     if big:
-        B.check(lib.ad_tune_conv_tile(1))
+        B.check(lib.ad_tune_conv_tile(big))
     try:
         x = quantize(SI.make_array((bsz * l, c), 35), dtype)
         w = quantize(SI.make_array((3 * c, c), 36, 0.2), dtype)
