@@ -37,7 +37,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", default="sd21_768")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams for the timed region (0 = one per concurrent evaluation)")
-    ap.add_argument("--graphs", type=int, default=0, help="1: replay full asynchronous rounds from HIP graphs; 0 (default): launch every kernel directly")
+    ap.add_argument("--graphs", type=int, default=1, help="1 (default): replay full asynchronous rounds from HIP graphs; 0: launch every kernel directly")
+    ap.add_argument("--cuts", default="auto", help="partition of the units into components: 'auto' (default: balanced by unit times measured on this GPU "
+                    "before the timed region), 'flops' (FLOP-balanced, the library default) or N-1 comma-separated first units of components 2..N")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--shapes", action="store_true", help="print the per-shape GEMM/attention timings of the instrumented round to stderr")
     args = ap.parse_args()
@@ -58,9 +60,19 @@ def main():
     K, W = args.steps, args.warmup
     dev = "cuda:0"
     t0 = time.time()
-    m = ad.AsyncDiff(d, N, w, S, dtype)
+    probe = ad.AsyncDiff(d, 1, 0, 1, dtype)
+    wts = SI.make_weights(probe.weight_manifest(), bf16_exact=(dtype == ad.AD_BF16))
+    probe.close()
+    unit_us = None
+    if args.cuts == "auto":
+        # components of comparable measured time: every unit is timed alone on this GPU, then split by the library's rule
+        from paper_2406_06911_amd.tuning import time_balanced_cuts
+        cuts, unit_us = time_balanced_cuts(d, N, dtype, wts, dev) if N > 1 else (None, None)
+        log(f"unit times measured in {time.time() - t0:.1f}s; time-balanced cuts {cuts}")
+    else:
+        cuts = None if args.cuts == "flops" else [int(x) for x in args.cuts.split(",")]
+    m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts)
     m.allocate(dev)
-    wts = SI.make_weights(m.weight_manifest(), bf16_exact=(dtype == ad.AD_BF16))
     m.load_weights(wts)
     del wts
     log(f"model ready in {time.time() - t0:.1f}s; arenas {[round(b / 2**20) for b in m.device_bytes()]} MiB")
@@ -206,7 +218,8 @@ def main():
         "dtype": "bf16" if dtype == ad.AD_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: latent {d['latent_channels']}x{d['height']}x{d['width']}, batch {d['batch']} (guidance), "
                                f"N={N} components on {n_streams} HIP streams, warm-up {w}, stride {S}, {r['sampler']}",
-                   "n_components": N, "stride": S, "streams": n_streams, "hip_graphs": bool(args.graphs), "flops_per_step": flops_step},
+                   "n_components": N, "stride": S, "streams": n_streams, "hip_graphs": bool(args.graphs), "partition": args.cuts if args.cuts in ("auto", "flops") else "given",
+                   "component_first_units": [a for a, _ in m.partition()], "flops_per_step": flops_step},
         "component_evals_per_s": round(steps_per_s / S * n_par, 2),
         "sequential_steps_per_s": round(seq_steps_per_s, 3),
         "concurrent_over_sequential": round(steps_per_s / seq_steps_per_s, 4),

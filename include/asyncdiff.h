@@ -111,6 +111,16 @@ typedef void* ad_stream; /* a hipStream_t */
  * warmup >= 1 is required when n_components > 1 (the stored states must exist before the first
  * asynchronous round); stride >= 1.  cfg: HOST.  *out receives a context owned by the library. */
 ad_status ad_create(const ad_unet_cfg* cfg, int n_components, int warmup, int stride, ad_ctx** out);
+/* The same with the partition given by the caller (Section 3.2 asks for components of comparable load and leaves
+ * the measure open; a caller that has timed the units can balance by time instead of FLOPs).  cuts: HOST,
+ * n_components - 1 unit indices, cuts[k] = first unit of component k + 2, strictly increasing, inside
+ * (0, number of units); ignored (may be NULL) when n_components is 1.  Everything else as ad_create. */
+ad_status ad_create_with_cuts(const ad_unet_cfg* cfg, int n_components, const int* cuts, int warmup, int stride, ad_ctx** out);
+/* The partition rule of ad_create applied to arbitrary per-unit costs (FLOPs, measured microseconds, ...): the
+ * contiguous split of n_units costs into n_components parts that minimises the largest part; among optimal
+ * splits the lexicographically smallest cut vector.  costs: HOST, non-negative; cuts: HOST, receives
+ * n_components - 1 first-unit indices (the format ad_create_with_cuts takes). */
+ad_status ad_balance_cuts(const int64_t* costs, int n_units, int n_components, int* cuts);
 void ad_destroy(ad_ctx* ctx); /* NULL is allowed */
 const char* ad_last_error(void);
 

@@ -14,11 +14,17 @@ F = np.float64
 
 class Pipeline:
     def __init__(self, cfg: UNetConfig, wts, N, w, S, T, sampler="ddim", cfg_scale=7.5,
-                 beta_kind="linear", time_shift=False):
+                 beta_kind="linear", time_shift=False, cuts=None):
+        """cuts: optional explicit partition (first unit of components 2..N); default: the FLOP-balanced one."""
         self.cfg, self.N, self.w, self.S, self.T = cfg, N, w, S, T
         self.wts = {k: np.asarray(v, F) for k, v in wts.items()}
         self.units = build_units(cfg)
-        self.ranges = component_ranges(cfg, N)
+        if cuts is None:
+            self.ranges = component_ranges(cfg, N)
+        else:
+            edges = [0] + list(cuts) + [len(self.units)]
+            assert len(cuts) == N - 1 and all(a < b for a, b in zip(edges, edges[1:])), "bad cuts"
+            self.ranges = [(edges[k], edges[k + 1] - 1) for k in range(N)]
         self.sampler, self.cfg_scale, self.time_shift = sampler, cfg_scale, time_shift
         self.taus = SM.timesteps(T)
         self.acp = SM.alphas_cumprod(kind=beta_kind)

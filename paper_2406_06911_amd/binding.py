@@ -71,7 +71,7 @@ EXPORTS = [
     "ad_reset", "ad_get_timesteps", "ad_num_sched_rows", "ad_get_schedule", "ad_get_sampler_coeffs",
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
     "ad_conv_forward", "ad_conv_workspace_bytes", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
-    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode",
+    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode", "ad_create_with_cuts", "ad_balance_cuts",
 ]
 
 
@@ -84,6 +84,8 @@ def _load():
     P = C.POINTER
     L.ad_last_error.restype = C.c_char_p
     L.ad_create.argtypes = [P(UNetCfg), ci, ci, ci, P(vp)]
+    L.ad_create_with_cuts.argtypes = [P(UNetCfg), ci, P(ci), ci, ci, P(vp)]
+    L.ad_balance_cuts.argtypes = [P(C.c_int64), ci, ci, P(ci)]
     L.ad_destroy.argtypes = [vp]; L.ad_destroy.restype = None
     L.ad_num_units.argtypes = [vp]
     L.ad_get_unit.argtypes = [vp, ci, P(UnitInfo)]
@@ -135,14 +137,29 @@ def _ptr(t):
     return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
 
 
+def balance_cuts(costs, n_components):
+    """Minimax contiguous split of integer per-unit costs (ad_balance_cuts); returns the n_components - 1 cuts."""
+    costs = [int(c) for c in costs]
+    arr = (C.c_int64 * len(costs))(*costs)
+    out = (C.c_int * max(n_components - 1, 1))()
+    check(lib.ad_balance_cuts(arr, len(costs), n_components, out))
+    return [out[k] for k in range(n_components - 1)]
+
+
 class AsyncDiff:
     """Owns an ad_ctx plus the torch tensors that back its two device arenas."""
 
-    def __init__(self, cfg_dict, n_components, warmup, stride, dtype=AD_F32):
+    def __init__(self, cfg_dict, n_components, warmup, stride, dtype=AD_F32, cuts=None):
         self.cfg = UNetCfg.from_dict(cfg_dict, dtype)
         self.N, self.warmup, self.stride, self.dtype = n_components, warmup, stride, dtype
         self._h = C.c_void_p()
-        check(lib.ad_create(C.byref(self.cfg), n_components, warmup, stride, C.byref(self._h)))
+        if cuts is None:
+            check(lib.ad_create(C.byref(self.cfg), n_components, warmup, stride, C.byref(self._h)))
+        else:
+            if len(cuts) != n_components - 1:
+                raise ValueError("cuts must hold n_components - 1 unit indices")
+            arr = (C.c_int * max(len(cuts), 1))(*cuts)
+            check(lib.ad_create_with_cuts(C.byref(self.cfg), n_components, arr, warmup, stride, C.byref(self._h)))
         self._weights_t = self._work_t = None
 
     def close(self):

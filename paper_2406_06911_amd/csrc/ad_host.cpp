@@ -505,7 +505,7 @@ extern "C" {
 
 const char* ad_last_error(void) { return g_err; }
 
-ad_status ad_create(const ad_unet_cfg* cfg, int n_components, int warmup, int stride, ad_ctx** out) {
+static ad_status create_ctx(const ad_unet_cfg* cfg, int n_components, const int* user_cuts, int warmup, int stride, ad_ctx** out) {
   if (!cfg || !out) AD_FAIL(AD_ERR_INVALID, "null argument");
   *out = nullptr;
   ad_status st = validate(*cfg, n_components, warmup, stride);
@@ -525,7 +525,19 @@ ad_status ad_create(const ad_unet_cfg* cfg, int n_components, int warmup, int st
     }
   std::vector<int64_t> costs;
   for (Unit& u : c->units) { u.info.flops = unit_flops(c->cfg, u.info); costs.push_back(u.info.flops); }
-  std::vector<int> cuts = partition_cuts(costs, n_components);
+  std::vector<int> cuts;
+  if (user_cuts) {
+    for (int k = 0; k + 1 < n_components; ++k) {
+      const int lo = k == 0 ? 0 : user_cuts[k - 1];
+      if (user_cuts[k] <= lo || user_cuts[k] >= nu) {
+        delete c;
+        AD_FAIL(AD_ERR_INVALID, "cuts must be strictly increasing and inside (0, %d)", nu);
+      }
+      cuts.push_back(user_cuts[k]);
+    }
+  } else {
+    cuts = partition_cuts(costs, n_components);
+  }
   std::vector<int> edges{0};
   edges.insert(edges.end(), cuts.begin(), cuts.end());
   edges.push_back(nu);
@@ -550,6 +562,26 @@ ad_status ad_create(const ad_unet_cfg* cfg, int n_components, int warmup, int st
   plan_work(*c);
   *out = reinterpret_cast<ad_ctx*>(c);
   return AD_OK;
+}
+
+ad_status ad_create(const ad_unet_cfg* cfg, int n_components, int warmup, int stride, ad_ctx** out) {
+  return create_ctx(cfg, n_components, nullptr, warmup, stride, out);
+}
+
+ad_status ad_balance_cuts(const int64_t* costs, int n_units, int n_components, int* cuts) {
+  if (!costs || n_units < 1 || n_components < 1 || n_components > n_units || (n_components > 1 && !cuts))
+    AD_FAIL(AD_ERR_INVALID, "bad argument");
+  std::vector<int64_t> c(costs, costs + n_units);
+  for (int64_t v : c)
+    if (v < 0) AD_FAIL(AD_ERR_INVALID, "costs must not be negative");
+  const std::vector<int> r = partition_cuts(c, n_components);
+  for (size_t k = 0; k < r.size(); ++k) cuts[k] = r[k];
+  return AD_OK;
+}
+
+ad_status ad_create_with_cuts(const ad_unet_cfg* cfg, int n_components, const int* cuts, int warmup, int stride, ad_ctx** out) {
+  if (n_components > 1 && !cuts) AD_FAIL(AD_ERR_INVALID, "null argument");
+  return create_ctx(cfg, n_components, n_components > 1 ? cuts : nullptr, warmup, stride, out);
 }
 
 static inline const Ctx* C(const ad_ctx* p) { return reinterpret_cast<const Ctx*>(p); }

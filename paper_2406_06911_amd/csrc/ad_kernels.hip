@@ -1052,49 +1052,63 @@ __global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) voi
   float m_run = -INFINITY, l_run = 0.f;
   const int srow = tid >> 3, scol = tid & 7;
   const int ntiles = (Lk + 63) / 64;
-  const bf16* kbase = K + (size_t)b * Lk * ldk + h * 64 + scol * 8;
-  const bf16* vbase = Vt + ((size_t)b * C + h * 64) * ldv + scol * 8;
+  const bool ragged = (Lk & 63) != 0;
+  // running pointers of this thread's two rows of the K tile (keys) and of the V^T tile (channels)
+  const bf16* kp[2];
+  const bf16* vp[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    kp[i] = K + ((size_t)b * Lk + srow + 32 * i) * ldk + h * 64 + scol * 8;
+    vp[i] = Vt + ((size_t)b * C + h * 64 + srow + 32 * i) * ldv + scol * 8;
+  }
+  const size_t kstep = (size_t)64 * ldk;
 
-  // the next tile travels through registers while the current one is multiplied
+  // the next tile travels through registers while the current one is multiplied; tiles are loaded in order.
+  // Only the last tile can be ragged: every test on key indices sits behind a workgroup-uniform branch.
   bf16x8 kr[2], vr[2];
   auto load_tile = [&](int t) {
-    const int key0 = t * 64;
+    if (!ragged || t + 1 < ntiles) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) kr[i] = *(const bf16x8*)kp[i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kr[i][e] = (bf16)0.f;
+        if (t * 64 + srow + 32 * i < Lk) kr[i] = *(const bf16x8*)kp[i];
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int row = srow + 32 * i;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) kr[i][e] = (bf16)0.f;
-      if (key0 + row < Lk) kr[i] = *(const bf16x8*)(kbase + (size_t)(key0 + row) * ldk);
-      vr[i] = *(const bf16x8*)(vbase + (size_t)row * ldv + key0);       // in bounds: ldv is padded to 64 keys
+      vr[i] = *(const bf16x8*)vp[i];          // in bounds: ldv is padded to 64 keys
+      kp[i] += kstep;
+      vp[i] += 64;
     }
   };
-  auto store_tile = [&](int t) {
-    char* st = lds + (t & 1) * kAttnStage;
-    const int kb = t * 64 + scol * 8;
+  auto store_tile = [&](int t, int parity) {
+    char* st = lds + parity * kAttnStage;
+    if (ragged && t + 1 == ntiles) {          // keys past the end must not contribute, whatever the pad holds
+      const int kb = t * 64 + scol * 8;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int row = srow + 32 * i;
-      bf16x8 vv = vr[i];
-      if (kb + 8 > Lk) {        // keys past the end must not contribute, whatever the pad holds
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (kb + e >= Lk) vv[e] = (bf16)0.f;
-      }
-      *(bf16x8*)(st + row * kPitch + scol * 16) = kr[i];
-      *(bf16x8*)(st + 64 * kPitch + row * kPitch + scol * 16) = vv;
+          if (kb + e >= Lk) vr[i][e] = (bf16)0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      *(bf16x8*)(st + (srow + 32 * i) * kPitch + scol * 16) = kr[i];
+      *(bf16x8*)(st + 64 * kPitch + (srow + 32 * i) * kPitch + scol * 16) = vr[i];
     }
   };
-
-  load_tile(0);
-  store_tile(0);
-  if (ntiles > 1) load_tile(1);
-  __syncthreads();
-  for (int t = 0; t < ntiles; ++t) {
+  // one key tile; PAR (the LDS stage) is a compile-time constant so that every LDS address is base + immediate
+  auto step = [&](int t, auto par) {
+    constexpr int PAR = decltype(par)::value;
     if (t + 1 < ntiles) {
-      store_tile(t + 1);
+      store_tile(t + 1, PAR ^ 1);
       if (t + 2 < ntiles) load_tile(t + 2);
     }
-    const char* Ks = lds + (t & 1) * kAttnStage;
+    const char* Ks = lds + PAR * kAttnStage;
     const char* Vs = Ks + 64 * kPitch;
     f32x16 sc[2];
 #pragma unroll
@@ -1107,7 +1121,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) voi
         sc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sc[j], 0, 0, 0);
       }
     }
-    if (t == ntiles - 1 && (Lk & 63)) {     // only the last tile can hold keys past the end
+    if (ragged && t == ntiles - 1) {     // only the last tile can hold keys past the end
       const int key0 = t * 64;
 #pragma unroll
       for (int j = 0; j < 2; ++j)
@@ -1159,6 +1173,15 @@ __global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) voi
         }
       }
     __syncthreads();
+  };
+
+  load_tile(0);
+  store_tile(0, 0);
+  if (ntiles > 1) load_tile(1);
+  __syncthreads();
+  for (int t = 0; t < ntiles; t += 2) {
+    step(t, std::integral_constant<int, 0>{});
+    if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
   }
   const float l_tot = l_run + other_half(l_run, low);
   if (query < L) {

@@ -12,7 +12,7 @@ from paper_2406_06911_amd import binding as B
 from configs import CONFIGS
 from oracle import sampler as SM
 from oracle import schedule as SC
-from oracle.partition import component_ranges, unit_flops
+from oracle.partition import component_ranges, partition, unit_flops
 from oracle.unet import UNetConfig, build_units, component_io, weight_manifest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -82,6 +82,38 @@ def test_sampler_coefficients(sampler, beta):
             assert abs(init_scale - SM.euler_init_scale(taus, acp)) < 1e-12
         assert abs(cx * x + ce * e - float(ref)) < 1e-12
     m.close()
+
+
+def test_balance_cuts_matches_oracle_partition_rule():
+    """ad_balance_cuts on arbitrary costs (the use: measured unit times) is the oracle's minimax / lexicographic rule."""
+    rng = np.random.default_rng(7)
+    for trial in range(60):
+        nu = int(rng.integers(1, 40))
+        n = int(rng.integers(1, min(nu, 6) + 1))
+        costs = [int(c) for c in rng.integers(0 if trial % 3 else 1, 1000 if trial % 2 else 5, size=nu)]
+        assert ad.balance_cuts(costs, n) == partition(costs, n), (costs, n)
+    with pytest.raises(ad.AsyncDiffError):
+        ad.balance_cuts([1, 2, 3], 4)
+    with pytest.raises(ad.AsyncDiffError):
+        ad.balance_cuts([1, -2, 3], 2)
+
+
+def test_explicit_cuts():
+    d = CONFIGS["tiny"]
+    ocfg = UNetConfig(**d)
+    ounits = build_units(ocfg)
+    nu = len(ounits)
+    for cuts in ([1], [nu - 1], [2, 5], [1, 2, 3], list(range(1, nu))):
+        m = ad.AsyncDiff(d, len(cuts) + 1, 1, 1, B.AD_F32, cuts=cuts)
+        edges = [0] + cuts + [nu]
+        assert m.partition() == [(edges[k], edges[k + 1] - 1) for k in range(len(cuts) + 1)]
+        for k, (a, b) in enumerate(m.partition(), start=1):
+            assert m.component_io(k) == tuple(component_io(ounits, a, b))
+        m.close()
+    for cuts in ([0], [nu], [3, 3], [5, 2]):
+        with pytest.raises(ad.AsyncDiffError) as e:
+            ad.AsyncDiff(d, len(cuts) + 1, 1, 1, B.AD_F32, cuts=cuts)
+        assert e.value.status == B.AD_ERR_INVALID
 
 
 def test_invalid_arguments_are_reported():

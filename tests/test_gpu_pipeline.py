@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 class Case:
     """A model instance on the GPU plus the oracle pipeline over the same seeded inputs."""
 
-    def __init__(self, name, dtype, N, w, S, T, sampler="ddim", cfg_scale=1.0, std=0.02, time_shift=False):
+    def __init__(self, name, dtype, N, w, S, T, sampler="ddim", cfg_scale=1.0, std=0.02, time_shift=False, cuts=None):
         d = CONFIGS[name]
         self.d, self.dtype, self.N, self.S, self.T = d, dtype, N, S, T
         ocfg = UNetConfig(**d)
@@ -25,8 +25,8 @@ class Case:
         self.noise = SI.make_latent(d["latent_channels"], d["height"], d["width"])
         self.text = quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), dtype)
         self.pooled = SI.make_pooled(d["batch"], d["pooled_dim"]) if d["pooled_dim"] else None
-        self.oracle = Pipeline(ocfg, self.wts, N=N, w=w, S=S, T=T, sampler=sampler, cfg_scale=cfg_scale, time_shift=time_shift)
-        self.m = ad.AsyncDiff(d, N, w, S, dtype)
+        self.oracle = Pipeline(ocfg, self.wts, N=N, w=w, S=S, T=T, sampler=sampler, cfg_scale=cfg_scale, time_shift=time_shift, cuts=cuts)
+        self.m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts)
         self.m.allocate(DEV)
         self.m.load_weights(self.wts)
         self.m.reset(T, sampler=B.AD_DDIM if sampler == "ddim" else B.AD_EULER, cfg_scale=cfg_scale, time_shift=time_shift)
@@ -240,6 +240,22 @@ def test_graph_replay_equals_direct_launch_bitwise(name, dtype, N, w, S, T, samp
             assert np.array_equal(a, b), f"run {attempt}, round {r}"
     assert np.isfinite(direct[-1]).all()
     case.m.set_graph_mode(False)
+
+
+@pytest.mark.parametrize("cuts,graphs", [([1, 2], False), ([3, 9], True), ([2], True)])
+def test_caller_given_partition_matches_oracle(cuts, graphs):
+    """A partition supplied by the caller (for instance one balanced by measured time) changes which tensors are
+    stale, so the trajectory differs from the default one; the oracle run with the same cuts must agree."""
+    T, N = 9, len(cuts) + 1
+    case = Case("tiny", B.AD_F32, N, 1, 1, T, cfg_scale=2.0, std=0.1, cuts=cuts)
+    case.m.set_graph_mode(graphs)
+    assert [a for a, _ in case.m.partition()][1:] == cuts
+    xs = case.oracle.run(case.noise, case.text, mode="table")
+    got, rounds = run_steps(case, N)
+    assert rel_l2(got, xs[-1]) < 1e-4
+    default = Case("tiny", B.AD_F32, N, 1, 1, T, cfg_scale=2.0, std=0.1)
+    if [a for a, _ in default.m.partition()][1:] != cuts:
+        assert rel_l2(default.oracle.run(default.noise, default.text, mode="table")[-1], xs[-1]) > 1e-6
 
 
 def test_full_warmup_equals_single_component_bitwise():
