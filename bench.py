@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--graphs", type=int, default=1, help="1 (default): replay full asynchronous rounds from HIP graphs; 0: launch every kernel directly")
     ap.add_argument("--cuts", default="auto", help="partition of the units into components: 'auto' (default: balanced by unit times measured on this GPU "
                     "before the timed region), 'flops' (FLOP-balanced, the library default) or N-1 comma-separated first units of components 2..N")
+    ap.add_argument("--tile", type=int, default=-1, help="GEMM kernel family override for measurements (ad_tune_conv_tile); -1 = automatic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--shapes", action="store_true", help="print the per-shape GEMM/attention timings of the instrumented round to stderr")
     args = ap.parse_args()
@@ -60,6 +61,8 @@ def main():
     K, W = args.steps, args.warmup
     dev = "cuda:0"
     t0 = time.time()
+    if args.tile != -1:
+        ad.binding.check(ad.lib.ad_tune_conv_tile(args.tile))
     probe = ad.AsyncDiff(d, 1, 0, 1, dtype)
     wts = SI.make_weights(probe.weight_manifest(), bf16_exact=(dtype == ad.AD_BF16))
     probe.close()

@@ -394,7 +394,12 @@ static void plan_work(Ctx& c) {
       const ad_unit_info& u = c.units[ui].info;
       const size_t B = g.batch;
       const size_t m_in = B * u.h_in * u.w_in, m_out = B * u.h_out * u.w_out;
-      auto gemm = [&](size_t m, int n, int k, int mode = OUT_ROWMAJOR) { want(9, conv_workspace_bytes(g.dtype, (long long)m, n, k, mode)); };
+      // split-K scratch: the largest need over the epilogues a GEMM of this shape can be launched with, so that
+      // the split chosen for a layer (and with it the rounding order) never depends on what else shares its component
+      auto gemm = [&](size_t m, int n, int k, int mode = OUT_ROWMAJOR) {
+        for (int md : {mode, (int)OUT_ROWMAJOR, (int)OUT_TRANSPOSED, (int)OUT_TRANSPOSED_F32})
+          want(9, conv_workspace_bytes(g.dtype, (long long)m, n, k, md));
+      };
       switch (u.kind) {
         case AD_UNIT_CONV_IN: want(0, m_out * kConvInK * es); break;
         case AD_UNIT_DOWN: case AD_UNIT_UP: gemm(m_out, u.c_out, 9 * u.c_in); break;

@@ -333,3 +333,90 @@ def test_state_errors():
         m.step(x, x, [torch.cuda.current_stream()])
     assert e.value.status == B.AD_ERR_STATE
     m.close()
+
+
+# ---------------------------------------------------------------------------------------------------
+# The metric configuration at full size (768px SD2.1 shape, 866M parameters, N = 4, bf16)
+# ---------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def full_size_weights():
+    d = CONFIGS["sd21_768"]
+    return SI.make_weights(weight_manifest(UNetConfig(**d)), bf16_exact=True)
+
+
+def test_full_size_first_units_match_oracle(full_size_weights):
+    """One evaluation of the first three units at the real shape (first convolution, ResBlock, transformer block
+    with the 9216-token self-attention): the layers that hold the largest GEMMs and the dominant attention
+    launch, in the tile / split-K configuration the full-size shapes select.  The oracle computes the same
+    units from the same seeded inputs (about 360 GFLOP in fp64)."""
+    from oracle.unet import build_units, run_units
+    d = CONFIGS["sd21_768"]
+    ocfg = UNetConfig(**d)
+    units = build_units(ocfg)
+    last = 2
+    prefixes = tuple(units[i].name + "." for i in range(last + 1)) + ("time.",)
+    sub = {k: np.asarray(v, np.float64) for k, v in full_size_weights.items() if k.startswith(prefixes)}
+    noise = SI.make_latent(d["latent_channels"], d["height"], d["width"])
+    text = quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), B.AD_BF16)
+    taus = __import__("oracle.sampler", fromlist=["timesteps"]).timesteps(50)
+    x = np.broadcast_to(noise.astype(np.float64), (d["batch"],) + noise.shape).copy()
+    ref = run_units(ocfg, units, 0, last, sub, {-1: x}, taus[0], text.astype(np.float64), None)
+
+    m = ad.AsyncDiff(d, 4, 3, 1, B.AD_BF16, cuts=[last + 1, 28, 39])
+    m.allocate(DEV)
+    m.load_weights(full_size_weights)
+    m.reset(50)
+    ins, outs = m.component_io(1)
+    assert ins == [-1] and sorted(ref.keys()) == sorted(outs)
+    d_text = dev(text, B.AD_BF16)
+    hout = []
+    for u in outs:
+        (b, h, w, c), _ = m.tensor_shape(u)
+        hout.append(torch.full((b, h, w, c), float("nan"), device=DEV, dtype=torch.bfloat16))
+    m.component_forward(1, [dev_f32(noise.astype(np.float32))], 0, d_text, hout, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for u, t in zip(outs, hout):
+        err = rel_l2(nhwc_to_nchw(host(t)), ref[u])
+        assert err < 2e-2, f"unit {u}: rel L2 {err:.3e}"
+    m.close()
+
+
+def test_full_size_bench_configuration_properties(full_size_weights):
+    """The launch configuration bench.py times (time-balanced partition, four streams, graph replay) at full
+    size: every round gives bit for bit what direct launches on one stream give, the warm-up steps equal plain
+    sequential denoising by a single component, and the latent stays finite."""
+    d = CONFIGS["sd21_768"]
+    T, w = 8, 3
+    noise = dev_f32(SI.make_latent(d["latent_channels"], d["height"], d["width"]).astype(np.float32))
+    d_text = dev(quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), B.AD_BF16), B.AD_BF16)
+
+    def trajectory(n, cuts, warm, streams, graphs, rounds=None):
+        m = ad.AsyncDiff(d, n, warm, 1, B.AD_BF16, cuts=cuts)
+        m.allocate(DEV)
+        m.load_weights(full_size_weights)
+        m.set_graph_mode(graphs)
+        m.reset(T, cfg_scale=7.5)
+        latent = noise.clone()
+        ss = [torch.cuda.Stream(device=DEV) for _ in range(streams)]
+        torch.cuda.synchronize()
+        snaps = []
+        while (rounds is None or len(snaps) < rounds) and m.step(latent, d_text, ss) is not None:
+            torch.cuda.synchronize()
+            snaps.append(latent.cpu().numpy().copy())
+        m.close()
+        return snaps
+
+    cuts = [11, 28, 39]
+    direct = trajectory(4, cuts, w, 1, False)
+    replay = trajectory(4, cuts, w, 4, True)
+    assert len(direct) == len(replay) == T
+    for r, (a, b) in enumerate(zip(direct, replay)):
+        assert np.array_equal(a, b), f"round {r}"
+    assert np.isfinite(replay[-1]).all()
+    single = trajectory(1, None, 0, 1, False, rounds=w)
+    for r in range(w):
+        assert np.array_equal(single[r], direct[r]), f"warm-up step {r}"
+    # the asynchronous steps differ from sequential denoising (stale inputs), but only slightly (Section 3.2)
+    full = trajectory(1, None, 0, 1, False)
+    dev_async = rel_l2(direct[-1], full[-1])
+    assert 0 < dev_async < 0.2, dev_async
