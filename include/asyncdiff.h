@@ -255,8 +255,8 @@ ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0,
                           int ld_t, void* splitk_ws, size_t splitk_bytes, ad_stream stream);
 /* Tuning knob for measurements: forces the block tile of ad_conv_forward and of every convolution / linear
  * layer of the process (1: 128x128 register-staged tiles, 3: 64x64 register-staged tiles, 4: 128x128 two-stage
- * LDS-DMA, 5: 128x128 three-stage LDS-DMA, 6: 256x128 three-stage LDS-DMA, -1: automatic choice, the default).
- * 4, 5 and 6 apply to bf16 GEMMs with a row-major, GEGLU or fused q/k/v output; other calls keep the automatic
+ * LDS-DMA, 5: 128x128 three-stage LDS-DMA, 6: 256x128 three-stage LDS-DMA, 7: 64x64 three-stage LDS-DMA,
+ * -1: automatic choice, the default).  4 to 7 apply to bf16 GEMMs with a row-major, GEGLU or fused q/k/v output; other calls keep the automatic
  * choice.  Results are the same up to rounding order. */
 ad_status ad_tune_conv_tile(int tile);
 /* Packs HOST fp32 weights [n_out][c_in][k][k] into the kernel layout (HOST out, dtype elements).

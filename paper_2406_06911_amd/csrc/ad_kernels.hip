@@ -581,8 +581,8 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
   constexpr int ES = (int)sizeof(T), VN = Vec<T>::N, BK = kRowBytes / ES;
   constexpr int STAGE = (BM + BN) * kRowBytes, NSTAGE = 3;
   constexpr int AG = BM / 32, BG = BN / 32, OPS = AG + BG;     // 8-row groups (= loads) per wavefront and k-tile
-  constexpr int NG = TM * TN, STEP = (3 * NG) / OPS;
-  static_assert(STEP >= 1 && OPS * STEP <= 3 * NG && TM + TN <= NG && OPS < 32, "schedule");
+  constexpr int NG = TM * TN;                                  // MFMA groups per k-step; loads go out during the first three k-steps
+  static_assert(OPS < 32, "vmcnt range");
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -706,9 +706,18 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
         for (int j = 0; j < TN; ++j) {
           const int g = i * TN + j;
           Mma<T>::run(fr[ks & 1][i], fr[ks & 1][TM + j], acc[i][j]);
-          if (ks < 3 && g < TM + TN) read_frag(st, ks + 1, g);
-          if (ks == 3 && PHASE >= 1 && g < TM + TN) read_frag(sn, 4, g);
-          if (PHASE == 2 && q % STEP == 0 && q / STEP < OPS) issue_one(target, q / STEP);
+          // fragment r of the next k-step follows MFMA group floor(r NG / (TM+TN)); load l follows slot floor(l 3NG / OPS)
+#pragma unroll
+          for (int r = 0; r < TM + TN; ++r)
+            if (r * NG / (TM + TN) == g) {
+              if (ks < 3) read_frag(st, ks + 1, r);
+              else if (PHASE >= 1) read_frag(sn, 4, r);
+            }
+          if (PHASE == 2 && ks < 3) {
+#pragma unroll
+            for (int l = 0; l < OPS; ++l)
+              if (l * 3 * NG / OPS == q) issue_one(target, l);
+          }
           __builtin_amdgcn_sched_barrier(0);
           ++q;
         }
@@ -828,7 +837,7 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
 // Tile shapes.  The register-staged kernels (64x64, 128x128) serve fp32 and the transposed epilogues; bf16
 // GEMMs with a row-major, GEGLU, fused q/k/v or split-K epilogue take the three-stage LDS-DMA kernel with a
 // 128x128 or a 256x128 tile.
-enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_DMA2_128 = 4, TILE_P3_128 = 5, TILE_P3_256 = 6, TILE_AUTO = -1 };
+enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_DMA2_128 = 4, TILE_P3_128 = 5, TILE_P3_256 = 6, TILE_P3_64 = 7, TILE_AUTO = -1 };
 static int g_tile_override = TILE_AUTO;
 
 struct ConvPlan { int tile; int splits; };
@@ -855,11 +864,12 @@ static int splits_by_tiles(long long m, int n, int ktiles, int out_mode, int bm)
 // workgroup (about 0.4 us): rounds of 256 workgroups x (k-tiles per workgroup + a fixed prologue / epilogue
 // share), a 256x128 tile costing 1.8 tiles of 128x128, plus the second pass of split-K (a launch and
 // (splits + 1/2) x M x N x 4 bytes through memory).
-static double plan_cost(long long m, int n, int ktiles, int bm, int splits) {
+static double plan_cost(long long m, int n, int ktiles, int tile, int splits) {
+  const int bm = tile == TILE_P3_256 ? 256 : 128;
   const long long wgs = ((m + bm - 1) / bm) * ((n + 127) / 128) * splits;
   const long long rounds = (wgs + 255) / 256;
   const int per = (ktiles + splits - 1) / splits;
-  double cost = (double)rounds * (per + 8) * (bm == 256 ? 1.8 : 1.0);
+  double cost = (double)rounds * (per + 8) * (tile == TILE_P3_256 ? 1.8 : 1.0);
   if (splits > 1) cost += 15.0 + (splits + 0.5) * (double)m * n * 4.0 / 2.5e12 / 0.4e-6;
   return cost;
 }
@@ -868,7 +878,9 @@ static ConvPlan choose_plan(int dtype, long long m, int n, int ktiles, int out_m
   const bool geglu = out_mode == OUT_GEGLU;   // needs a value and a gate tile in the same wavefront
   const bool dma = dma_capable(dtype, out_mode);
   int forced = g_tile_override;
-  if (forced == TILE_P3_128 || forced == TILE_P3_256 || forced == TILE_DMA2_128) { if (!dma) forced = TILE_AUTO; }
+  if (forced == TILE_P3_128 || forced == TILE_P3_256 || forced == TILE_DMA2_128 || forced == TILE_P3_64) {
+    if (!dma || (forced == TILE_P3_64 && geglu)) forced = TILE_AUTO;
+  }
   else if (forced != TILE_AUTO && geglu) forced = TILE_AUTO;
   if (forced == TILE_128x128 || forced == TILE_64x64) return ConvPlan{forced, splits_by_tiles(m, n, ktiles, out_mode, forced == TILE_64x64 ? 64 : 128)};
   if (forced == TILE_DMA2_128) return ConvPlan{forced, splits_by_tiles(m, n, ktiles, out_mode, 128)};
@@ -885,13 +897,19 @@ static ConvPlan choose_plan(int dtype, long long m, int n, int ktiles, int out_m
   ConvPlan best{TILE_P3_128, 1};
   double best_cost = 1e300;
   const int max_splits = (geglu || n % 4) ? 1 : 16;
+  // few output tiles and a short K (the linear layers of the deeper transformer blocks): nothing amortises the
+  // prologue and epilogue of a 128x128 workgroup, and 64x64 tiles (three workgroups per CU) overlap them;
+  // measured 1.1-1.3x there, slower everywhere else
+  const long long tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
+  if (forced == TILE_P3_64) return ConvPlan{TILE_P3_64, splits_by_tiles(m, n, ktiles, out_mode, 64)};
+  if (forced == TILE_AUTO && !geglu && tiles128 <= 192 && ktiles <= 32) return ConvPlan{TILE_P3_64, 1};
   for (int tile : {TILE_P3_128, TILE_P3_256}) {
     if (forced != TILE_AUTO && tile != forced) continue;
     for (int sp = 1; sp <= max_splits; ++sp) {
       if (sp > 1 && ktiles / sp < 4) break;
       const int per = (ktiles + sp - 1) / sp;
       if ((ktiles + per - 1) / per != sp) continue;          // every split must own at least one k-tile
-      const double c = plan_cost(m, n, ktiles, tile == TILE_P3_256 ? 256 : 128, sp);
+      const double c = plan_cost(m, n, ktiles, tile, sp);
       if (c < best_cost) { best_cost = c; best = ConvPlan{tile, sp}; }
     }
   }
@@ -976,6 +994,13 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
     AD_P3(128)
   } else if (tile == TILE_P3_256) {
     AD_P3(256)
+  } else if (tile == TILE_P3_64) {
+    switch (mode) {
+      case OUT_ROWMAJOR: st = run_igemm_p3<bf16, 64, 64, OUT_ROWMAJOR>(p, "igemm_bf16_64x64_p3", s); break;
+      case OUT_QKV: st = run_igemm_p3<bf16, 64, 64, OUT_QKV>(p, "igemm_bf16_64x64_p3", s); break;
+      case OUT_PARTIAL: st = run_igemm_p3<bf16, 64, 64, OUT_PARTIAL>(p, "igemm_bf16_64x64_p3_splitk", s); break;
+      default: break;
+    }
   } else if (tile == TILE_DMA2_128) {
     name = "igemm_bf16_128x128_dma";
     if (mode == OUT_ROWMAJOR) st = run_igemm_dma<bf16, OUT_ROWMAJOR, 2>(p, name, s);
@@ -1768,7 +1793,7 @@ size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n
 }
 
 ad_status ad_tune_conv_tile(int tile) {
-  if (tile != -1 && tile != 1 && tile != 3 && tile != 4 && tile != 5 && tile != 6) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1, 3, 4, 5 or 6");
+  if (tile != -1 && tile != 1 && tile != 3 && (tile < 4 || tile > 7)) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1, 3, 4, 5, 6 or 7");
   set_tile_override(tile);
   return AD_OK;
 }
