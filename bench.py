@@ -41,6 +41,7 @@ def main():
     ap.add_argument("--cuts", default="auto", help="partition of the units into components: 'auto' (default: balanced by unit times measured on this GPU "
                     "before the timed region), 'flops' (FLOP-balanced, the library default) or N-1 comma-separated first units of components 2..N")
     ap.add_argument("--tile", type=int, default=-1, help="GEMM kernel family override for measurements (ad_tune_conv_tile); -1 = automatic")
+    ap.add_argument("--order", type=int, default=-1, help="GEMM workgroup order override for measurements (ad_tune_conv_order); -1 = automatic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--shapes", action="store_true", help="print the per-shape GEMM/attention timings of the instrumented round to stderr")
     args = ap.parse_args()
@@ -63,6 +64,8 @@ def main():
     t0 = time.time()
     if args.tile != -1:
         ad.binding.check(ad.lib.ad_tune_conv_tile(args.tile))
+    if args.order != -1:
+        ad.binding.check(ad.lib.ad_tune_conv_order(args.order))
     probe = ad.AsyncDiff(d, 1, 0, 1, dtype)
     wts = SI.make_weights(probe.weight_manifest(), bf16_exact=(dtype == ad.AD_BF16))
     probe.close()

@@ -259,6 +259,11 @@ ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0,
  * -1: automatic choice, the default).  4 to 7 apply to bf16 GEMMs with a row-major, GEGLU or fused q/k/v output; other calls keep the automatic
  * choice.  Results are the same up to rounding order. */
 ad_status ad_tune_conv_tile(int tile);
+/* Tuning knob for measurements: order in which the workgroups of a GEMM walk its output tiles.  0: an XCD owns a
+ * run of row tiles and every column tile of them (the weights are fetched into every L2); 1: an XCD owns a run of
+ * column tiles (the activations are fetched into every L2); -1: automatic, the default (the smaller operand is
+ * the one fetched everywhere).  Results are bit-identical. */
+ad_status ad_tune_conv_order(int order);
 /* Packs HOST fp32 weights [n_out][c_in][k][k] into the kernel layout (HOST out, dtype elements).
  * Returns the packed size in bytes through *bytes when out == NULL. */
 ad_status ad_pack_conv_weight(int dtype, const float* w, int n_out, int c_in, int ksize, int geglu, void* out, size_t* bytes);

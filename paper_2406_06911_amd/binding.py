@@ -71,7 +71,7 @@ EXPORTS = [
     "ad_reset", "ad_get_timesteps", "ad_num_sched_rows", "ad_get_schedule", "ad_get_sampler_coeffs",
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
     "ad_conv_forward", "ad_conv_workspace_bytes", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
-    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode", "ad_create_with_cuts", "ad_balance_cuts",
+    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode", "ad_create_with_cuts", "ad_balance_cuts", "ad_tune_conv_order",
 ]
 
 
@@ -85,6 +85,7 @@ def _load():
     L.ad_last_error.restype = C.c_char_p
     L.ad_create.argtypes = [P(UNetCfg), ci, ci, ci, P(vp)]
     L.ad_create_with_cuts.argtypes = [P(UNetCfg), ci, P(ci), ci, ci, P(vp)]
+    L.ad_tune_conv_order.argtypes = [ci]
     L.ad_balance_cuts.argtypes = [P(C.c_int64), ci, ci, P(ci)]
     L.ad_destroy.argtypes = [vp]; L.ad_destroy.restype = None
     L.ad_num_units.argtypes = [vp]

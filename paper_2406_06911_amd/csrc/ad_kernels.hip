@@ -91,7 +91,26 @@ struct IgemmParams {
   int kt_per_split;                   // k-tiles handled by one workgroup along grid.y (split-K), else ktiles
   float* partial;                     // split-K: fp32 partial sums [splits][M][N]; nullptr otherwise
   void* out2; void* out3;             // OUT_QKV
+  int tiles_m;                        // row tiles
+  int n_major;                        // workgroup order: 0 = an XCD owns a run of row tiles (all column tiles of each),
+                                      // 1 = an XCD owns a run of column tiles (all row tiles of each); see tile_of()
 };
+
+// Which (row tile, column tile, split) a workgroup computes.  Workgroups go to the 8 XCDs round-robin in
+// launch order (x fastest, then y); xcd_remap turns that into 8 contiguous runs of a virtual index, and the
+// virtual index is laid out [split][row tile][column tile] or [split][column tile][row tile].  With the first
+// order an XCD's L2 sees a slice of the activations and every weight it needs once per slice; with the second it
+// sees a slice of the weights and all activations.  The launcher picks the order that re-fetches the smaller
+// operand (deep levels: few rows, tens of MB of weights -> column-major).
+struct TileId { int m_tile, n_tile, split; };
+__device__ __forceinline__ TileId tile_of(const IgemmParams& p) {
+  const int tiles = p.tiles_m * p.tiles_n;
+  const int lid = blockIdx.y * gridDim.x + blockIdx.x;
+  const int vid = xcd_remap(lid, gridDim.x * gridDim.y);
+  const int split = vid / tiles, t = vid - split * tiles;
+  if (p.n_major) return TileId{t % p.tiles_m, t / p.tiles_m, split};
+  return TileId{t / p.tiles_n, t % p.tiles_n, split};
+}
 
 constexpr int kPitch = kRowBytes + 16;   // LDS row pitch in bytes
 
@@ -136,12 +155,12 @@ template <> struct Vec4<float> { typedef f32x4 type; };
 
 template <typename T, int BM, int WTM, int WTN, int TM, int TN, int MODE>
 __device__ __forceinline__ void igemm_epilogue(const IgemmParams& p, f32x16 (&acc)[TM][TN], int m0, int n0, int wave_m,
-                                               int wave_n, int l32, int half, char* stage) {
+                                               int wave_n, int l32, int half, char* stage, int split) {
   typedef typename Vec4<T>::type V4;
   const int row_base = m0 + wave_m * WTM + 4 * half;
   const int col_base = n0 + wave_n * WTN + l32;
   if constexpr (MODE == OUT_PARTIAL) {
-    float* dst = p.partial + (size_t)blockIdx.y * p.M * p.N;
+    float* dst = p.partial + (size_t)split * p.M * p.N;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = col_base + j * 32;
@@ -296,8 +315,8 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   const int wave_m = wave / WGN, wave_n = wave % WGN;
-  const int tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+  const TileId tid3 = tile_of(p);
+  const int m0 = tid3.m_tile * BM, n0 = tid3.n_tile * BN;
 
   const __amdgpu_buffer_rsrc_t rs0 = make_rsrc(p.src0, p.bytes0);
   const __amdgpu_buffer_rsrc_t rs1 = make_rsrc(p.src1, p.bytes1);
@@ -340,7 +359,7 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
   // problem sizes allow.
   V areg[NSET][AV], breg[NSET][BV];
   // this workgroup's range of k-tiles (all of them unless the launch splits K along grid.y)
-  const int kt_begin = blockIdx.y * p.kt_per_split;
+  const int kt_begin = tid3.split * p.kt_per_split;
   const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
   int f_k0 = kt_begin * BK;              // position of the next k-tile to fetch
   int f_tap = f_k0 / p.ctot, f_cc = f_k0 - f_tap * p.ctot;
@@ -416,7 +435,7 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
   }
 
   // the k-loop ended with a barrier: every wavefront is done with the tiles, LDS can be reused
-  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch));
+  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch), tid3.split);
 }
 
 // =================================================================================================
@@ -454,8 +473,8 @@ __global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
   const int wave_m = wave >> 1, wave_n = wave & 1;
-  const int tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+  const TileId tid3 = tile_of(p);
+  const int m0 = tid3.m_tile * BM, n0 = tid3.n_tile * BN;
   const u32x4 rs0 = make_rsrc_words(p.src0, p.bytes0), rs1 = make_rsrc_words(p.src1, p.bytes1);
   const u32x4 rsw = make_rsrc_words(p.w, p.bytes_w);
 
@@ -489,7 +508,7 @@ __global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
       a_off1[i] = ok ? (pix * (unsigned)p.c1 + scol * VN) * ES : kOob;
     }
   };
-  const int kt_begin = blockIdx.y * p.kt_per_split;
+  const int kt_begin = tid3.split * p.kt_per_split;
   const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
   int f_k0 = kt_begin * BK;
   int f_tap = f_k0 / p.ctot, f_cc = f_k0 - f_tap * p.ctot;
@@ -561,7 +580,7 @@ __global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
   }
   wait_vmcnt<0>();
   __syncthreads();     // every wavefront is done reading the last tile: LDS can be reused by the epilogue
-  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch));
+  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch), tid3.split);
 }
 
 // =================================================================================================
@@ -589,8 +608,8 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
   const int wave_m = wave >> 1, wave_n = wave & 1;
-  const int tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+  const TileId tid3 = tile_of(p);
+  const int m0 = tid3.m_tile * BM, n0 = tid3.n_tile * BN;
   const u32x4 rs0 = make_rsrc_words(p.src0, p.bytes0), rs1 = make_rsrc_words(p.src1, p.bytes1);
   const u32x4 rsw = make_rsrc_words(p.w, p.bytes_w);
 
@@ -623,7 +642,7 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
       a_off1[i] = ok ? (pix * (unsigned)p.c1 + scol * VN) * ES : kOob;
     }
   };
-  const int kt_begin = blockIdx.y * p.kt_per_split;
+  const int kt_begin = tid3.split * p.kt_per_split;
   const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
   int f_k0 = kt_begin * BK;
   int f_tap = f_k0 / p.ctot, f_cc = f_k0 - f_tap * p.ctot;
@@ -734,7 +753,7 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
   for (; kt + 1 < nkt; ++kt) k_tile(std::integral_constant<int, 1>{});
   k_tile(std::integral_constant<int, 0>{});
   __syncthreads();     // every wavefront holds its last fragments: LDS can be reused by the epilogue
-  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch));
+  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch), tid3.split);
 }
 
 template <typename T, int BM, int BN, int MODE>
@@ -742,6 +761,7 @@ static ad_status run_igemm_p3(const IgemmParams& p0, const char* name, hipStream
   IgemmParams p = p0;
   p.tiles_n = (p.N + BN - 1) / BN;
   const int tiles_m = (p.M + BM - 1) / BM;
+  p.tiles_m = tiles_m;
   constexpr int lds_bytes = 3 * (BM + BN) * kRowBytes;
   static_assert(lds_bytes >= 4 * (BM / 2) * kPitch, "epilogue staging fits");
   static bool attr_set = false;
@@ -763,6 +783,7 @@ static ad_status run_igemm_dma(const IgemmParams& p0, const char* name, hipStrea
   IgemmParams p = p0;
   p.tiles_n = (p.N + 127) / 128;
   const int tiles_m = (p.M + 127) / 128;
+  p.tiles_m = tiles_m;
   constexpr int lds_bytes = NSTAGE * 256 * kRowBytes;
   static bool attr_set = false;
   if (!attr_set) {
@@ -783,6 +804,7 @@ static ad_status run_igemm(const IgemmParams& p0, const char* name, hipStream_t 
   IgemmParams p = p0;
   p.tiles_n = (p.N + BN - 1) / BN;
   const int tiles_m = (p.M + BM - 1) / BM;
+  p.tiles_m = tiles_m;
   constexpr int lds_bytes = 2 * (BM + BN) * kPitch;
   static bool attr_set = false;     // LDS above 64 KiB has to be requested once per kernel
   if (!attr_set) {
@@ -839,6 +861,7 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
 // 128x128 or a 256x128 tile.
 enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_DMA2_128 = 4, TILE_P3_128 = 5, TILE_P3_256 = 6, TILE_P3_64 = 7, TILE_AUTO = -1 };
 static int g_tile_override = TILE_AUTO;
+static int g_order_override = -1;
 
 struct ConvPlan { int tile; int splits; };
 
@@ -960,6 +983,9 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   p.bytes0 = (unsigned)(in_elems * a.c0 * esize(a.dtype));
   p.bytes1 = a.c1 ? (unsigned)(in_elems * a.c1 * esize(a.dtype)) : p.bytes0;
   p.bytes_w = (unsigned)w_bytes;
+  // workgroup order: the operand that is re-fetched by every XCD should be the smaller one
+  p.n_major = w_bytes > in_elems * (long long)(a.c0 + a.c1) * (long long)esize(a.dtype) ? 1 : 0;
+  if (g_order_override >= 0) p.n_major = g_order_override;
   const ConvPlan plan = choose_plan(a.dtype, m, a.n_out, p.ktiles, a.out_mode);
   const int tile = plan.tile;
   int splits = plan.splits;
@@ -1033,6 +1059,7 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
 }
 
 void set_tile_override(int tile) { g_tile_override = tile; }
+void set_order_override(int order) { g_order_override = order; }
 
 // =================================================================================================
 // Fused attention for bf16, head_dim 64.  A workgroup handles 128 queries of one (batch, head); each
@@ -1795,6 +1822,12 @@ size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n
 ad_status ad_tune_conv_tile(int tile) {
   if (tile != -1 && tile != 1 && tile != 3 && (tile < 4 || tile > 7)) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1, 3, 4, 5, 6 or 7");
   set_tile_override(tile);
+  return AD_OK;
+}
+
+ad_status ad_tune_conv_order(int order) {
+  if (order < -1 || order > 1) AD_FAIL(AD_ERR_INVALID, "order must be -1, 0 or 1");
+  set_order_override(order);
   return AD_OK;
 }
 
