@@ -20,6 +20,16 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+# HBM-side traffic per launch (bytes: fetched + written) of the kernel classes of the sd21_768 workload, from two
+# `rocprofv3 --pmc` runs of this file (FETCH_SIZE, WRITE_SIZE; KiB per dispatch scaled by the factors 2.00 and 1.00 that the
+# same counters show for the 2^26-element sampler launch).  Commands and tables: profiles/bench_sd21_768_all_kernels.md.
+MEASURED_TRAFFIC = {"sd21_768": {
+    "attn_mfma_bf16": 22606529, "igemm_bf16_128x128_p3": 135523489, "igemm_bf16_128x128_dma": 56125384,
+    "igemm_bf16_256x128_p3": 76287400, "igemm_bf16_64x64_p3": 25208776, "igemm_bf16_128x128_p3_splitk": 53056367,
+    "igemm_bf16_256x128_p3_splitk": 119105773, "splitk_reduce": 17837781, "gn_apply": 17453181, "gn_partial": 8349800,
+    "layernorm": 13111232, "gn_finalize": 2068316, "linear_rows": 5907990, "gn_small": 3065651}}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -147,6 +157,8 @@ def main():
     kernels = {}
     for name, a in sorted(agg.items(), key=lambda kv: -kv[1]["ms"]):
         e = dict(calls=a["calls"], total_ms=round(a["ms"], 4), avg_us=round(a["ms"] / a["calls"] * 1e3, 2))
+        if a["bytes"] > 0:
+            e["algorithmic_mb_per_launch"] = round(a["bytes"] / a["calls"] / 1e6, 2)
         if a["flops"] > 0 and name.startswith(("igemm", "attn")):
             e["tflops"] = round(a["flops"] / (a["ms"] * 1e-3) / 1e12, 2)
             e["frac_mfma_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
@@ -162,14 +174,14 @@ def main():
     if da["flops"] > 0:
         ach = da["flops"] / (da["ms"] * 1e-3) / 1e12
         roofline = dict(kernel=dname, bound="mfma", achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, launches=da["calls"],
+                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=MEASURED_TRAFFIC.get(args.config, {}).get(dname), launches=da["calls"],
                         avg_launch_us=round(da["ms"] / da["calls"] * 1e3, 2),
                         flops_per_launch=round(da["flops"] / da["calls"]),
                         algorithmic_bytes_per_launch=round(da["bytes"] / da["calls"]))
     else:
         ach = da["bytes"] / (da["ms"] * 1e-3) / 1e9
         roofline = dict(kernel=dname, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, launches=da["calls"],
+                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=MEASURED_TRAFFIC.get(args.config, {}).get(dname), launches=da["calls"],
                         avg_launch_us=round(da["ms"] / da["calls"] * 1e3, 2),
                         bytes_per_launch=round(da["bytes"] / da["calls"]))
     # ---- the sampler kernel at a bandwidth-bound size (same kernel, synthetic size) ---------------------
