@@ -3,6 +3,9 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- before the library: PyTorch ships its own HIP runtime, and the process must hold one copy.
+# Loaded in this order the library binds to the runtime PyTorch brought; loaded first, it would pull in the system's
+# runtime, PyTorch would then mix the two, and the first HIP call fails with "no ROCm-capable device is detected".
 
 AD_F32, AD_BF16 = 0, 1
 AD_DDIM, AD_EULER = 0, 1
