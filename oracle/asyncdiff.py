@@ -6,7 +6,7 @@ import numpy as np
 
 from . import sampler as SM
 from . import schedule as SC
-from .partition import component_ranges
+from .partition import component_ranges, segment_ranges_wrapped
 from .unet import UNetConfig, build_units, component_io, run_units
 
 F = np.float64
@@ -14,12 +14,17 @@ F = np.float64
 
 class Pipeline:
     def __init__(self, cfg: UNetConfig, wts, N, w, S, T, sampler="ddim", cfg_scale=7.5,
-                 beta_kind="linear", time_shift=False, cuts=None):
-        """cuts: optional explicit partition (first unit of components 2..N); default: the FLOP-balanced one."""
+                 beta_kind="linear", time_shift=False, cuts=None, wrap=False):
+        """cuts: optional explicit partition (first unit of components 2..N); default: the FLOP-balanced one.
+        wrap: wrapped segmentation (N+1 segments, the first and the last are one component; then `cuts` has N
+        entries and the evaluations are numbered 1..N+1, see schedule.py)."""
         self.cfg, self.N, self.w, self.S, self.T = cfg, N, w, S, T
+        self.wrap = wrap
         self.wts = {k: np.asarray(v, F) for k, v in wts.items()}
         self.units = build_units(cfg)
-        if cuts is None:
+        if wrap:
+            self.ranges = segment_ranges_wrapped(cfg, N, cuts)
+        elif cuts is None:
             self.ranges = component_ranges(cfg, N)
         else:
             edges = [0] + list(cuts) + [len(self.units)]
@@ -28,7 +33,7 @@ class Pipeline:
         self.sampler, self.cfg_scale, self.time_shift = sampler, cfg_scale, time_shift
         self.taus = SM.timesteps(T)
         self.acp = SM.alphas_cumprod(kind=beta_kind)
-        self.rows = SC.build_schedule(T, N, w, S, time_shift)
+        self.rows = SC.build_schedule(T, N, w, S, time_shift, wrap)
         # producer component of every unit, and which components feed which
         self.owner = {}
         for n, (a, b) in enumerate(self.ranges, start=1):
@@ -84,8 +89,8 @@ class Pipeline:
         self._latent_step = 0
         if mode == "recursive":
             return SC.run_recursive(self.T, self.N, self.w, self.S, self.feeds, base, self.eps_fn,
-                                    self.sampler_fn, self.initial_latent(noise), self.time_shift)
+                                    self.sampler_fn, self.initial_latent(noise), self.time_shift, self.wrap)
         if mode == "sequential":
-            return SC.run_sequential(self.T, self.N, self.feeds, base, self.eps_fn, self.sampler_fn,
+            return SC.run_sequential(self.T, len(self.ranges), self.feeds, base, self.eps_fn, self.sampler_fn,
                                      self.initial_latent(noise))
         raise ValueError(mode)

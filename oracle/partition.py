@@ -72,6 +72,38 @@ def partition(costs: List[int], n: int) -> List[int]:
     return cuts
 
 
+def partition_wrapped(costs: List[int], n: int) -> List[int]:
+    """Wrapped segmentation (Appendix A, "Model Segmentation": for SDXL the first and the last blocks form one
+    segment, the rest is split sequentially).  Reading: the unit list is cut into n+1 contiguous segments; the
+    first and the last segment together are component 1, segments 1..n-1 are components 2..n.  Returns the n cut
+    positions that minimise the largest component cost; ties -> lexicographically smallest cut vector.
+    Exhaustive search (the unit lists here have a few dozen entries)."""
+    from itertools import combinations
+    m = len(costs)
+    assert n >= 2 and n + 1 <= m
+    pre = [0]
+    for c in costs:
+        pre.append(pre[-1] + c)
+    best, best_cuts = None, None
+    for cuts in combinations(range(1, m), n):
+        edges = (0,) + cuts + (m,)
+        loads = [pre[edges[k + 1]] - pre[edges[k]] for k in range(n + 1)]
+        worst = max([loads[0] + loads[n]] + loads[1:n])
+        if best is None or worst < best:          # combinations() come in lexicographic order
+            best, best_cuts = worst, list(cuts)
+    return best_cuts
+
+
+def segment_ranges_wrapped(cfg: UNetConfig, n: int, cuts=None):
+    """[(first_unit, last_unit)] of the n+1 segments of the wrapped segmentation (segments 0 and n = component 1)."""
+    units = build_units(cfg)
+    if cuts is None:
+        cuts = partition_wrapped([unit_flops(cfg, u) for u in units], n)
+    edges = [0] + list(cuts) + [len(units)]
+    assert len(cuts) == n and all(a < b for a, b in zip(edges, edges[1:])), "bad cuts"
+    return [(edges[k], edges[k + 1] - 1) for k in range(n + 1)]
+
+
 def component_ranges(cfg: UNetConfig, n: int):
     """[(first_unit, last_unit)] for the N components."""
     units = build_units(cfg)

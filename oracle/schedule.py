@@ -15,6 +15,12 @@ Rule (reading of the paper, with stride S >= 1 and warm-up w):
         component 1 reads the latent x_b available when the round starts;
       - a trailing round with fewer than S steps evaluates only the last component.
   * every cross-component input (main hidden state and skip features) is the stored one.
+
+Wrapped segmentation (Appendix A "Model Segmentation", the SDXL case; stride 1 only - the paper does not say how
+the two combine): the unit list has N+1 segments, numbered here as evaluations 1..N+1; segment 1 (head) and
+segment N+1 (tail) are one component and run back to back on one device.  In an asynchronous round the head reads
+the fresh latent, segments 2..N read stored inputs, and the tail reads the head's outputs of THIS round (they never
+left the device) and stored inputs from everybody else; the tail yields eps.  Warm-up runs all N+1 in order.
 """
 from dataclasses import dataclass
 from typing import Callable, Dict, List
@@ -29,13 +35,28 @@ class Row:
     write_slot: int   # slot the outputs are stored in, -1 = outputs other than eps are dropped
     latent_step: int  # i of the latent x_i read by component 1, else -1
     eps_step: int     # step whose noise prediction this evaluation yields (last component), else -1
+    fresh_from: int = 0  # wrapped segmentation: component whose outputs of this same round are read (0 = none)
 
 
-def build_schedule(T: int, N: int, w: int, S: int, time_shift: bool = False) -> List[Row]:
+def build_schedule(T: int, N: int, w: int, S: int, time_shift: bool = False, wrap: bool = False) -> List[Row]:
     assert T >= 1 and N >= 1 and S >= 1 and w >= 0 and (N == 1 or w >= 1)
     shift = lambda i: i - 1 if (time_shift and i >= w and i >= 1) else i
     rows: List[Row] = []
     g = 0
+    if wrap:
+        assert N >= 2 and S == 1
+        P = N + 1                                    # evaluations per step: head, N-1 middle segments, tail
+        for i in range(min(w, T)):
+            for n in range(1, P + 1):
+                rows.append(Row(g, n, i, g & 1, g & 1, i if n == 1 else -1, i if n == P else -1))
+            g += 1
+        for b in range(min(w, T), T):
+            rd, wr = (g - 1) & 1, g & 1
+            for n in range(1, P):
+                rows.append(Row(g, n, shift(b), rd, wr, b if n == 1 else -1, -1))
+            rows.append(Row(g, P, shift(b), rd, wr, -1, b, 1))
+            g += 1
+        return rows
     for i in range(min(w, T)):
         for n in range(1, N + 1):
             rows.append(Row(g, n, i, g & 1, g & 1, i if n == 1 else -1, i if n == N else -1))
@@ -77,6 +98,9 @@ def run_table(rows: List[Row], feeds: Dict[int, List[int]], comp_fn: Callable, e
         pending, eps = [], {}
         for r in group:
             stored = {m: slots[r.read_slot][m] for m in feeds[r.comp]}
+            if r.fresh_from and r.write_slot != r.read_slot:
+                # the producer ran earlier in this round on the same device: its output has not been stored yet
+                stored[r.fresh_from] = next(b for (_, n, b) in pending if n == r.fresh_from)
             x = xs[r.latent_step] if r.latent_step >= 0 else None
             bundle = comp_fn(r.comp, stored, x, r.tau_step)
             if trace is not None:
@@ -97,10 +121,31 @@ def run_table(rows: List[Row], feeds: Dict[int, List[int]], comp_fn: Callable, e
     return xs
 
 
-def run_recursive(T, N, w, S, feeds, comp_fn, eps_fn, sampler_fn, x0, time_shift=False):
+def run_recursive(T, N, w, S, feeds, comp_fn, eps_fn, sampler_fn, x0, time_shift=False, wrap=False):
     """Memoised evaluation straight from the rule in the module docstring (no table, no slots)."""
     memo_out, memo_x = {}, {0: x0}
     shift = lambda i: i - 1 if (time_shift and i >= w and i >= 1) else i
+    if wrap:
+        assert S == 1
+        P = N + 1
+
+        def latent_w(i):
+            if i not in memo_x:
+                memo_x[i] = sampler_fn(latent_w(i - 1), eps_fn(out_w(P, i - 1)), i - 1)
+            return memo_x[i]
+
+        def out_w(n, i):
+            if (n, i) not in memo_out:
+                if i < w:
+                    stored = {m: out_w(m, i) for m in feeds[n]}
+                    tau = i
+                else:       # stored inputs are one step old, except what the head hands to the tail
+                    stored = {m: out_w(m, i if (n == P and m == 1) else i - 1) for m in feeds[n]}
+                    tau = shift(i)
+                memo_out[(n, i)] = comp_fn(n, stored, latent_w(i) if n == 1 else None, tau)
+            return memo_out[(n, i)]
+
+        return [latent_w(i) for i in range(T + 1)]
 
     def round_start(i):
         return w + ((i - w) // S) * S

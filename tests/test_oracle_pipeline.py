@@ -60,3 +60,23 @@ def test_euler_and_ddim_pipelines_agree_for_same_schedule(setup):
     a = Pipeline(cfg, wts, N=2, w=1, S=2, T=7, sampler="euler", cfg_scale=1.0).run(noise, ctx)[-1]
     b = Pipeline(cfg, wts, N=2, w=1, S=2, T=7, sampler="ddim", cfg_scale=1.0).run(noise, ctx)[-1]
     np.testing.assert_allclose(a, b, rtol=1e-9, atol=1e-10)
+
+
+def test_wrapped_segmentation_pipeline(setup):
+    """Wrapped segmentation on the real (tiny) UNet: table and recursion agree, a warm-up that covers every step is
+    sequential denoising bit for bit, and because the tail sees this step's skip features the result differs from
+    the sequential segmentation's."""
+    cfg, wts, noise, text = setup
+    N, T = 2, 6
+    p = Pipeline(cfg, wts, N=N, w=1, S=1, T=T, cfg_scale=1.0, wrap=True)
+    assert len(p.ranges) == N + 1 and p.ranges[0][0] == 0 and p.ranges[-1][1] == len(p.units) - 1
+    a = p.run(noise, text, mode="table")
+    b = p.run(noise, text, mode="recursive")
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    seq = Pipeline(cfg, wts, N=1, w=0, S=1, T=T, cfg_scale=1.0).run(noise, text, mode="sequential")
+    full = Pipeline(cfg, wts, N=N, w=T, S=1, T=T, cfg_scale=1.0, wrap=True).run(noise, text)
+    assert all(np.array_equal(x, y) for x, y in zip(full, seq))
+    plain = Pipeline(cfg, wts, N=N, w=1, S=1, T=T, cfg_scale=1.0).run(noise, text)
+    assert not np.array_equal(a[-1], plain[-1])
+    rel = lambda x, y: np.linalg.norm(x - y) / np.linalg.norm(y)
+    assert rel(a[-1], seq[-1]) < 0.5

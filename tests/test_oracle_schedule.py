@@ -176,3 +176,80 @@ def test_slots_alternate_and_every_step_gets_one_eps():
                 assert r.read_slot == r.write_slot == r.round & 1
             else:
                 assert r.read_slot == (r.round - 1) & 1 and r.write_slot in (-1, r.round & 1)
+
+
+# ---- wrapped segmentation (Appendix A "Model Segmentation": first and last blocks in one segment) -------------
+
+def wrap_feeds(N, extra=()):
+    """Evaluations 1..N+1 on a chain; the tail (N+1) also reads the head's (1) skip features."""
+    return chain_feeds(N + 1, [(1, N + 1)] + list(extra))
+
+
+@pytest.mark.parametrize("N,w,T,shift", [(2, 1, 8, False), (3, 2, 10, False), (4, 1, 12, True)])
+def test_wrapped_table_equals_recursive_definition(N, w, T, shift):
+    comp, eps, samp = symbolic_fns()
+    for feeds in (wrap_feeds(N), wrap_feeds(N, [(2, N + 1)]) if N > 2 else wrap_feeds(N)):
+        rows = SC.build_schedule(T, N, w, 1, shift, wrap=True)
+        a = SC.run_table(rows, feeds, comp, eps, samp, "x0", N)
+        b = SC.run_recursive(T, N, w, 1, feeds, comp, eps, samp, "x0", shift, wrap=True)
+        assert a == b and len(a) == T + 1
+
+
+def test_wrapped_dependencies():
+    """The tail reads the head of the SAME step (fresh latent through the skip features) and the middle segments
+    one step behind each: eps_i is built from head and tail at step i, segment n (2..N) at step i-(N+1-n), and so
+    from the latents x_i (head of this step) and x_{i-N+1} (the head whose output went down the chain)."""
+    N, T, w = 3, 12, 1
+    comp, eps, samp = symbolic_fns()
+    trace = []
+    SC.run_table(SC.build_schedule(T, N, w, 1, wrap=True), wrap_feeds(N), comp, eps, samp, ("x", 0), N, trace)
+    heads = {r.eps_step: b for r, b in trace if r.eps_step >= 0}
+    for i in range(w + N, T):
+        d = deps(heads[i])
+        expect = {(N + 1, i), (1, i)} | {(n, i - (N + 1 - n)) for n in range(2, N + 1)} | {(1, i - N)}
+        assert d["c"] == expect
+        assert d["x"] == {i, i - N}
+    # per asynchronous round: N+1 evaluations, only the tail reads something of its own round, one eps
+    rows = SC.build_schedule(T, N, w, 1, wrap=True)
+    for g in range(w, T):
+        grp = [r for r in rows if r.round == g]
+        assert [r.comp for r in grp] == list(range(1, N + 2))
+        assert [r.fresh_from for r in grp] == [0] * N + [1]
+        assert [r.eps_step for r in grp] == [-1] * N + [g] and grp[0].latent_step == g
+        assert all(r.read_slot == (g - 1) & 1 and r.write_slot == g & 1 for r in grp)
+
+
+def test_wrapped_full_warmup_is_sequential():
+    N, T = 3, 6
+    comp, eps, samp = symbolic_fns()
+    feeds = wrap_feeds(N)
+    a = SC.run_table(SC.build_schedule(T, N, T, 1, wrap=True), feeds, comp, eps, samp, "x0", N)
+    assert a == SC.run_sequential(T, N + 1, feeds, comp, eps, samp, "x0")
+
+
+def test_wrapped_partition_rule():
+    """Independent derivation: for every head end and tail start, the best split of the middle comes from the
+    (separately pinned) sequential partition; the wrapped optimum is the best of those."""
+    from oracle.partition import partition, partition_wrapped
+    rng = np.random.default_rng(3)
+    for trial in range(25):
+        m = int(rng.integers(4, 13))
+        n = int(rng.integers(2, min(4, m - 1) + 1))
+        costs = [int(c) for c in rng.integers(1, 50, size=m)]
+        cuts = partition_wrapped(costs, n)
+        edges = [0] + cuts + [m]
+        assert len(cuts) == n and all(a < b for a, b in zip(edges, edges[1:]))
+        loads = [sum(costs[edges[k]:edges[k + 1]]) for k in range(n + 1)]
+        got = max([loads[0] + loads[n]] + loads[1:n])
+        best = None
+        for c1 in range(1, m):
+            for cn in range(c1 + n - 1, m):
+                mid = costs[c1:cn]
+                if n == 2:
+                    worst_mid = sum(mid)
+                else:
+                    mc = [0] + partition(mid, n - 1) + [len(mid)]
+                    worst_mid = max(sum(mid[mc[k]:mc[k + 1]]) for k in range(n - 1))
+                v = max(sum(costs[:c1]) + sum(costs[cn:]), worst_mid)
+                best = v if best is None else min(best, v)
+        assert got == best, (costs, n)
