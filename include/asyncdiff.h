@@ -99,6 +99,7 @@ typedef struct ad_sched_row {
   int write_slot;  /* 0/1, or -1 when only the noise prediction of this evaluation is kept */
   int latent_step; /* step index of the latent read by component 1, else -1 */
   int eps_step;    /* step whose noise prediction this evaluation yields (component N), else -1 */
+  int fresh_from;  /* wrapped segmentation: evaluation of the same round whose outputs are read fresh (0 = none) */
 } ad_sched_row;
 
 typedef struct ad_ctx ad_ctx;
@@ -121,6 +122,18 @@ ad_status ad_create_with_cuts(const ad_unet_cfg* cfg, int n_components, const in
  * splits the lexicographically smallest cut vector.  costs: HOST, non-negative; cuts: HOST, receives
  * n_components - 1 first-unit indices (the format ad_create_with_cuts takes). */
 ad_status ad_balance_cuts(const int64_t* costs, int n_units, int n_components, int* cuts);
+/* Wrapped segmentation (Appendix A "Model Segmentation": for SDXL the first and the last blocks are one segment, the
+ * rest is split sequentially).  The unit list is cut into n_components + 1 contiguous segments; segment 1 (head)
+ * and segment n_components + 1 (tail) are one component, run back to back on one stream; segments 2..n_components
+ * are the other components.  The schedule table, ad_component_forward and ad_component_io number the segments
+ * 1..n_components + 1 (ad_num_segments); in an asynchronous round the tail reads the head's outputs of the same
+ * round (fresh skip features) and everything else from the previous round, and yields the noise prediction.
+ * cuts: HOST, n_components first-unit indices of segments 2..n_components + 1, or NULL for the split that minimises
+ * the largest component cost in FLOPs (ties: lexicographically smallest; exhaustive search, n_components <= 6).
+ * Stride is 1 (the paper does not say how stride and this segmentation combine); n_components >= 2. */
+ad_status ad_create_wrapped(const ad_unet_cfg* cfg, int n_components, const int* cuts, int warmup, ad_ctx** out);
+/* Number of unit ranges ad_get_partition fills: n_components, or n_components + 1 for the wrapped segmentation. */
+int ad_num_segments(const ad_ctx* ctx);
 void ad_destroy(ad_ctx* ctx); /* NULL is allowed */
 const char* ad_last_error(void);
 
@@ -128,6 +141,7 @@ const char* ad_last_error(void);
 int ad_num_units(const ad_ctx* ctx);
 ad_status ad_get_unit(const ad_ctx* ctx, int unit, ad_unit_info* out);
 /* first[k], last[k]: unit range of component k+1; arrays of n_components ints (HOST). */
+/* first/last: HOST arrays of ad_num_segments() entries. */
 ad_status ad_get_partition(const ad_ctx* ctx, int* first, int* last);
 /* Tensors a component reads from earlier components / offers to later ones, named by producing
  * unit (-1 = the latent).  Arrays HOST, capacity cap each; n_in and n_out receive the counts.

@@ -58,10 +58,11 @@ class WeightInfo(C.Structure):
 
 class SchedRow(C.Structure):
     _fields_ = [("round", C.c_int), ("comp", C.c_int), ("tau_step", C.c_int), ("read_slot", C.c_int),
-                ("write_slot", C.c_int), ("latent_step", C.c_int), ("eps_step", C.c_int)]
+                ("write_slot", C.c_int), ("latent_step", C.c_int), ("eps_step", C.c_int), ("fresh_from", C.c_int)]
 
     def as_tuple(self):
-        return (self.round, self.comp, self.tau_step, self.read_slot, self.write_slot, self.latent_step, self.eps_step)
+        return (self.round, self.comp, self.tau_step, self.read_slot, self.write_slot, self.latent_step, self.eps_step,
+                self.fresh_from)
 
 
 class ProfileRec(C.Structure):
@@ -74,7 +75,7 @@ EXPORTS = [
     "ad_reset", "ad_get_timesteps", "ad_num_sched_rows", "ad_get_schedule", "ad_get_sampler_coeffs",
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
     "ad_conv_forward", "ad_conv_workspace_bytes", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
-    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode", "ad_create_with_cuts", "ad_balance_cuts", "ad_tune_conv_order",
+    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode", "ad_create_with_cuts", "ad_balance_cuts", "ad_tune_conv_order", "ad_create_wrapped", "ad_num_segments",
 ]
 
 
@@ -89,6 +90,8 @@ def _load():
     L.ad_create.argtypes = [P(UNetCfg), ci, ci, ci, P(vp)]
     L.ad_create_with_cuts.argtypes = [P(UNetCfg), ci, P(ci), ci, ci, P(vp)]
     L.ad_tune_conv_order.argtypes = [ci]
+    L.ad_create_wrapped.argtypes = [P(UNetCfg), ci, P(ci), ci, P(vp)]
+    L.ad_num_segments.argtypes = [vp]
     L.ad_balance_cuts.argtypes = [P(C.c_int64), ci, ci, P(ci)]
     L.ad_destroy.argtypes = [vp]; L.ad_destroy.restype = None
     L.ad_num_units.argtypes = [vp]
@@ -153,11 +156,18 @@ def balance_cuts(costs, n_components):
 class AsyncDiff:
     """Owns an ad_ctx plus the torch tensors that back its two device arenas."""
 
-    def __init__(self, cfg_dict, n_components, warmup, stride, dtype=AD_F32, cuts=None):
+    def __init__(self, cfg_dict, n_components, warmup, stride, dtype=AD_F32, cuts=None, wrap=False):
         self.cfg = UNetCfg.from_dict(cfg_dict, dtype)
         self.N, self.warmup, self.stride, self.dtype = n_components, warmup, stride, dtype
         self._h = C.c_void_p()
-        if cuts is None:
+        if wrap:
+            if stride != 1:
+                raise ValueError("the wrapped segmentation is defined for stride 1")
+            if cuts is not None and len(cuts) != n_components:
+                raise ValueError("cuts must hold n_components unit indices for the wrapped segmentation")
+            arr = (C.c_int * n_components)(*cuts) if cuts is not None else None
+            check(lib.ad_create_wrapped(C.byref(self.cfg), n_components, arr, warmup, C.byref(self._h)))
+        elif cuts is None:
             check(lib.ad_create(C.byref(self.cfg), n_components, warmup, stride, C.byref(self._h)))
         else:
             if len(cuts) != n_components - 1:
@@ -187,9 +197,10 @@ class AsyncDiff:
         return out
 
     def partition(self):
-        a, b = (C.c_int * self.N)(), (C.c_int * self.N)()
+        n = lib.ad_num_segments(self._h)
+        a, b = (C.c_int * n)(), (C.c_int * n)()
         check(lib.ad_get_partition(self._h, a, b))
-        return [(a[i], b[i]) for i in range(self.N)]
+        return [(a[i], b[i]) for i in range(n)]
 
     def component_io(self, comp):
         cap = 128

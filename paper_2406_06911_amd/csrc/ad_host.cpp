@@ -141,23 +141,55 @@ std::vector<int> partition_cuts(const std::vector<int64_t>& costs, int n) {
 }
 
 // Schedule table (Section 3.2; Appendix A "Stride Denoising", "Time Shifting").
-void build_schedule(int T, int N, int w, int S, bool time_shift, std::vector<ad_sched_row>& rows) {
+// Wrapped segmentation: the n cuts of the unit list into n + 1 segments that minimise
+// max(cost(first) + cost(last), cost of each middle segment); ties -> lexicographically smallest cut vector.
+// Cut vectors are enumerated in lexicographic order, the first optimum is kept.
+std::vector<int> partition_cuts_wrapped(const std::vector<int64_t>& costs, int n) {
+  const int m = (int)costs.size();
+  std::vector<int64_t> pre(m + 1, 0);
+  for (int i = 0; i < m; ++i) pre[i + 1] = pre[i] + costs[i];
+  std::vector<int> cuts(n), best;
+  for (int k = 0; k < n; ++k) cuts[k] = k + 1;
+  int64_t best_cost = -1;
+  while (true) {
+    int64_t worst = pre[cuts[0]] + (pre[m] - pre[cuts[n - 1]]);
+    for (int k = 0; k + 1 < n; ++k) worst = std::max(worst, pre[cuts[k + 1]] - pre[cuts[k]]);
+    if (best_cost < 0 || worst < best_cost) { best_cost = worst; best = cuts; }
+    int k = n - 1;                                   // next combination of n values out of 1..m-1
+    while (k >= 0 && cuts[k] == m - 1 - (n - 1 - k)) --k;
+    if (k < 0) break;
+    ++cuts[k];
+    for (int j = k + 1; j < n; ++j) cuts[j] = cuts[j - 1] + 1;
+  }
+  return best;
+}
+
+void build_schedule(int T, int N, int w, int S, bool time_shift, bool wrap, std::vector<ad_sched_row>& rows) {
   rows.clear();
   auto tau_of = [&](int i) { return (time_shift && i >= w && i >= 1) ? i - 1 : i; };
   int g = 0;
   const int wu = w < T ? w : T;
   for (int i = 0; i < wu; ++i, ++g)
     for (int n = 1; n <= N; ++n)
-      rows.push_back(ad_sched_row{g, n, i, g & 1, g & 1, n == 1 ? i : -1, n == N ? i : -1});
+      rows.push_back(ad_sched_row{g, n, i, g & 1, g & 1, n == 1 ? i : -1, n == N ? i : -1, 0});
+  if (wrap) {
+    // N evaluations per step (head, middle segments, tail); the tail reads the head of its own round
+    for (int b = wu; b < T; ++b, ++g) {
+      const int rd = (g - 1) & 1, wr = g & 1;
+      for (int n = 1; n < N; ++n) rows.push_back(ad_sched_row{g, n, tau_of(b), rd, wr, n == 1 ? b : -1, -1, 0});
+      rows.push_back(ad_sched_row{g, N, tau_of(b), rd, wr, -1, b, 1});
+    }
+    return;
+  }
   for (int b = wu; b < T; ++g) {
     const int steps = (T - b < S) ? T - b : S;
     const bool full = steps == S;
     const int rd = (g - 1) & 1, wr = g & 1;
     if (full)
       for (int n = 1; n < N; ++n)
-        rows.push_back(ad_sched_row{g, n, tau_of(b + S - 1), rd, wr, n == 1 ? b : -1, -1});
+        rows.push_back(ad_sched_row{g, n, tau_of(b + S - 1), rd, wr, n == 1 ? b : -1, -1, 0});
     for (int j = 0; j < steps; ++j)
-      rows.push_back(ad_sched_row{g, N, tau_of(b + j), rd, (full && j == S - 1) ? wr : -1, N == 1 ? b : -1, b + j});
+      rows.push_back(ad_sched_row{g, N, tau_of(b + j), rd, (full && j == S - 1) ? wr : -1, N == 1 ? b : -1, b + j, 0});
     b += steps;
   }
 }
@@ -510,7 +542,8 @@ extern "C" {
 
 const char* ad_last_error(void) { return g_err; }
 
-static ad_status create_ctx(const ad_unet_cfg* cfg, int n_components, const int* user_cuts, int warmup, int stride, ad_ctx** out) {
+static ad_status create_ctx(const ad_unet_cfg* cfg, int n_components, const int* user_cuts, int warmup, int stride, ad_ctx** out,
+                            bool wrap = false) {
   if (!cfg || !out) AD_FAIL(AD_ERR_INVALID, "null argument");
   *out = nullptr;
   ad_status st = validate(*cfg, n_components, warmup, stride);
@@ -518,6 +551,8 @@ static ad_status create_ctx(const ad_unet_cfg* cfg, int n_components, const int*
   Ctx* c = new (std::nothrow) Ctx();
   if (!c) AD_FAIL(AD_ERR_NOMEM, "host allocation failed");
   c->cfg = *cfg;
+  c->devices = n_components; c->wrap = wrap;
+  if (wrap) ++n_components;             // from here on: the number of segments
   c->N = n_components; c->warmup = warmup; c->stride = stride;
   c->temb_dim = 4 * cfg->channels[0];
   build_units(c->cfg, c->units);
@@ -541,7 +576,7 @@ static ad_status create_ctx(const ad_unet_cfg* cfg, int n_components, const int*
       cuts.push_back(user_cuts[k]);
     }
   } else {
-    cuts = partition_cuts(costs, n_components);
+    cuts = wrap ? partition_cuts_wrapped(costs, n_components - 1) : partition_cuts(costs, n_components);
   }
   std::vector<int> edges{0};
   edges.insert(edges.end(), cuts.begin(), cuts.end());
@@ -584,6 +619,12 @@ ad_status ad_balance_cuts(const int64_t* costs, int n_units, int n_components, i
   return AD_OK;
 }
 
+ad_status ad_create_wrapped(const ad_unet_cfg* cfg, int n_components, const int* cuts, int warmup, ad_ctx** out) {
+  if (n_components < 2) AD_FAIL(AD_ERR_INVALID, "the wrapped segmentation needs at least two components");
+  if (!cuts && n_components > 6) AD_FAIL(AD_ERR_INVALID, "automatic wrapped cuts are searched exhaustively: n_components <= 6");
+  return create_ctx(cfg, n_components, cuts, warmup, 1, out, true);
+}
+
 ad_status ad_create_with_cuts(const ad_unet_cfg* cfg, int n_components, const int* cuts, int warmup, int stride, ad_ctx** out) {
   if (n_components > 1 && !cuts) AD_FAIL(AD_ERR_INVALID, "null argument");
   return create_ctx(cfg, n_components, n_components > 1 ? cuts : nullptr, warmup, stride, out);
@@ -593,6 +634,7 @@ static inline const Ctx* C(const ad_ctx* p) { return reinterpret_cast<const Ctx*
 static inline Ctx* C(ad_ctx* p) { return reinterpret_cast<Ctx*>(p); }
 
 int ad_num_units(const ad_ctx* ctx) { return ctx ? (int)C(ctx)->units.size() : 0; }
+int ad_num_segments(const ad_ctx* ctx) { return ctx ? C(ctx)->N : 0; }
 
 ad_status ad_get_unit(const ad_ctx* ctx, int unit, ad_unit_info* out) {
   if (!ctx || !out) AD_FAIL(AD_ERR_INVALID, "null argument");
@@ -656,7 +698,7 @@ ad_status ad_reset(ad_ctx* ctx, int T, int sampler_kind, int beta_kind, float cf
   c.taus.resize(T);
   for (int i = 0; i < T; ++i) c.taus[i] = (T - 1 - i) * (kTrainSteps / T);
   alphas_cumprod(beta_kind, c.acp);
-  build_schedule(T, c.N, c.warmup, c.stride, c.time_shift != 0, c.rows);
+  build_schedule(T, c.N, c.warmup, c.stride, c.time_shift != 0, c.wrap, c.rows);
   c.next_row = 0;
   c.steps_done = 0;
   c.text_cached = nullptr;

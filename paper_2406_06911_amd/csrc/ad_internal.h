@@ -85,7 +85,9 @@ struct Workspace {
 
 struct Ctx {
   ad_unet_cfg cfg{};
-  int N = 1, warmup = 0, stride = 1;
+  int N = 1, warmup = 0, stride = 1;   // N: evaluations per step (segments); equals `devices` unless wrapped
+  int devices = 1;                      // components that run side by side (streams of an asynchronous round)
+  bool wrap = false;                    // wrapped segmentation: segments 1 and N are one component
   std::vector<Unit> units;
   std::vector<Component> comps;
   std::vector<Weight> weights;
@@ -138,7 +140,8 @@ struct Ctx {
 // host logic
 int64_t unit_flops(const ad_unet_cfg& c, const ad_unit_info& u);
 std::vector<int> partition_cuts(const std::vector<int64_t>& costs, int n);
-void build_schedule(int T, int N, int w, int S, bool time_shift, std::vector<ad_sched_row>& rows);
+void build_schedule(int T, int N, int w, int S, bool time_shift, bool wrap, std::vector<ad_sched_row>& rows);
+std::vector<int> partition_cuts_wrapped(const std::vector<int64_t>& costs, int n);
 void sampler_coeffs(const Ctx& c, int step, double* cx, double* ce, double* in_scale, double* init_scale);
 size_t tensor_bytes(const Ctx& c, int unit);
 

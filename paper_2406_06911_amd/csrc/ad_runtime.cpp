@@ -462,7 +462,7 @@ static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const
                                const ad_stream* streams, int ns, bool capturing, std::vector<int>* steps_out) {
   const bool warm = c.rows[r0].read_slot == c.rows[r0].write_slot;
   const int nu = (int)c.units.size();
-  const int max_par = c.N + c.stride - 1;
+  const int max_par = c.devices + c.stride - 1;
   hipStream_t s0 = (hipStream_t)streams[0];
   const StepRec* table = (const StepRec*)(c.work_dev + c.step_table_off);
   int* counter = (int*)(c.work_dev + c.step_counter_off);
@@ -472,6 +472,7 @@ static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const
   AD_HIP(hipEventRecord(c.events[0], s0));
   for (int k = 1; k < ns; ++k) AD_HIP(hipStreamWaitEvent((hipStream_t)streams[k], c.events[0], 0));
 
+  std::vector<hipStream_t> comp_stream(c.N + 1, s0);
   std::vector<int> eps_steps, eps_lane;
   std::vector<hipStream_t> eps_stream;
   int lane_next = 0;
@@ -481,11 +482,18 @@ static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const
     const ad_sched_row& row = c.rows[r];
     const Component& cp = c.comps[row.comp - 1];
     hipStream_t s = warm ? s0 : (hipStream_t)streams[(r - r0) % ns];
+    // an evaluation that reads another one of its own round fresh follows it on its stream (wrapped segmentation)
+    if (!warm && row.fresh_from > 0) s = comp_stream[row.fresh_from];
+    comp_stream[row.comp] = s;
     const void* in[64];
     void* out[64];
     if (cp.in_units.size() > 64 || cp.out_units.size() > 64) AD_FAIL(AD_ERR_INVALID, "too many component tensors");
-    for (size_t i = 0; i < cp.in_units.size(); ++i)
-      in[i] = cp.in_units[i] < 0 ? latent : (const void*)(c.work_dev + c.slot_off[row.read_slot][cp.in_units[i]]);
+    for (size_t i = 0; i < cp.in_units.size(); ++i) {
+      if (cp.in_units[i] < 0) { in[i] = latent; continue; }
+      const int u = cp.in_units[i];
+      const int slot = (row.fresh_from > 0 && c.units[u].comp == row.fresh_from) ? row.write_slot : row.read_slot;
+      in[i] = c.work_dev + c.slot_off[slot][u];
+    }
     int lane = 0;
     if (row.comp == c.N) lane = lane_next++;
     for (size_t i = 0; i < cp.out_units.size(); ++i) {
@@ -552,7 +560,7 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
     if (steps_done) *steps_done = c.steps_done;
     return AD_ERR_DONE;
   }
-  const int max_par = c.N + c.stride - 1;
+  const int max_par = c.devices + c.stride - 1;
   const int ns = n_streams < max_par ? n_streams : max_par;
   while ((int)c.events.size() < 2 * max_par + 2) {
     hipEvent_t ev;
@@ -590,7 +598,7 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
   size_t r1 = r0;
   while (r1 < c.rows.size() && c.rows[r1].round == c.rows[r0].round) ++r1;
   const bool warm = c.rows[r0].read_slot == c.rows[r0].write_slot;
-  const bool full = !warm && (int)(r1 - r0) == max_par;
+  const bool full = !warm && (int)(r1 - r0) == c.N + c.stride - 1;
   Profiler* prof = prof_of(c);
   const bool profiling = prof && prof->on;
   std::vector<int> done;

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 class Case:
     """A model instance on the GPU plus the oracle pipeline over the same seeded inputs."""
 
-    def __init__(self, name, dtype, N, w, S, T, sampler="ddim", cfg_scale=1.0, std=0.02, time_shift=False, cuts=None):
+    def __init__(self, name, dtype, N, w, S, T, sampler="ddim", cfg_scale=1.0, std=0.02, time_shift=False, cuts=None, wrap=False):
         d = CONFIGS[name]
         self.d, self.dtype, self.N, self.S, self.T = d, dtype, N, S, T
         ocfg = UNetConfig(**d)
@@ -25,8 +25,8 @@ class Case:
         self.noise = SI.make_latent(d["latent_channels"], d["height"], d["width"])
         self.text = quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), dtype)
         self.pooled = SI.make_pooled(d["batch"], d["pooled_dim"]) if d["pooled_dim"] else None
-        self.oracle = Pipeline(ocfg, self.wts, N=N, w=w, S=S, T=T, sampler=sampler, cfg_scale=cfg_scale, time_shift=time_shift, cuts=cuts)
-        self.m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts)
+        self.oracle = Pipeline(ocfg, self.wts, N=N, w=w, S=S, T=T, sampler=sampler, cfg_scale=cfg_scale, time_shift=time_shift, cuts=cuts, wrap=wrap)
+        self.m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts, wrap=wrap)
         self.m.allocate(DEV)
         self.m.load_weights(self.wts)
         self.m.reset(T, sampler=B.AD_DDIM if sampler == "ddim" else B.AD_EULER, cfg_scale=cfg_scale, time_shift=time_shift)
@@ -65,17 +65,21 @@ def run_components_isolated(case, log=None):
         while k < len(trace) and trace[k][0].round == rnd:
             group.append(trace[k]); k += 1
         pending, heads = [], 0
+        this_round = {}                    # evaluation -> its oracle bundle of this round (wrapped segmentation)
         for row, obundle in group:
             ins, outs = m.component_io(row.comp)
+            this_round[row.comp] = obundle
             hin = []
             for u in ins:
                 if u < 0:
                     hin.append(dev_f32(xs[row.latent_step].astype(np.float32)))
+                elif row.fresh_from and row.write_slot != row.read_slot and orc.owner[u] == row.fresh_from:
+                    hin.append(dev(nchw_to_nhwc(this_round[row.fresh_from][u]), case.dtype))
                 else:
                     hin.append(dev(nchw_to_nhwc(ostore[row.read_slot][u]), case.dtype))
             hout = [case.alloc_unit(u) for u in outs]
             lane = 0
-            if row.comp == case.N:
+            if row.comp == len(orc.ranges):
                 lane, heads = heads, heads + 1
             scale = m.sampler_coeffs(row.latent_step)[2] if row.latent_step >= 0 else 1.0
             m.component_forward(row.comp, hin, row.tau_step, case.d_text, hout, stream, lane=lane, latent_scale=scale, pooled=case.d_pooled)
@@ -420,3 +424,47 @@ def test_full_size_bench_configuration_properties(full_size_weights):
     full = trajectory(1, None, 0, 1, False)
     dev_async = rel_l2(direct[-1], full[-1])
     assert 0 < dev_async < 0.2, dev_async
+
+
+# ---------------------------------------------------------------------------------------------------
+# Wrapped segmentation (Appendix A "Model Segmentation": first and last segment in one component)
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N,w,graphs,streams,shift", [(2, 1, False, 2, False), (3, 2, True, 3, False), (3, 1, False, 2, True), (4, 1, True, 4, False)])
+def test_wrapped_tiny_fp32_matches_oracle(N, w, graphs, streams, shift):
+    T = 9
+    case = Case("tiny", B.AD_F32, N, w, 1, T, cfg_scale=2.0, std=0.1, wrap=True, time_shift=shift)
+    case.m.set_graph_mode(graphs)
+    assert case.m.partition() == case.oracle.ranges
+    worst = run_components_isolated(case)
+    xs = case.oracle.run(case.noise, case.text)
+    case.m.reset(T, cfg_scale=2.0, time_shift=shift)
+    latent = case.init_latent()
+    ss = [torch.cuda.Stream(device=DEV) for _ in range(streams)]
+    torch.cuda.synchronize()
+    done = 0
+    while True:
+        r = case.m.step(latent, case.d_text, ss)
+        if r is None:
+            break
+        done = r
+        torch.cuda.synchronize()
+        assert rel_l2(host(latent), xs[done]) < 1e-4, f"after step {done}"
+    assert done == T
+    # the fresh skip features matter: the sequential segmentation with the same number of components ends elsewhere
+    plain = Case("tiny", B.AD_F32, N, w, 1, T, cfg_scale=2.0, std=0.1, time_shift=shift)
+    assert rel_l2(plain.oracle.run(plain.noise, plain.text)[-1], xs[-1]) > 1e-6
+
+
+def test_wrapped_narrow_sdxl_bf16():
+    """SDXL-shaped reduced-width model (the case the paper names), N = 4 wrapped, Euler, pooled branch."""
+    r = RUNS["sdxl_narrow"]
+    T = 12
+    case = Case("sdxl_narrow", B.AD_BF16, r["N"], r["w"], 1, T, sampler=r["sampler"], cfg_scale=r["cfg_scale"], wrap=True)
+    worst = run_components_isolated(case)
+    xs = case.oracle.run(case.noise, case.text, case.pooled)
+    case.m.set_graph_mode(True)
+    case.m.reset(T, sampler=B.AD_EULER, cfg_scale=r["cfg_scale"])
+    got, rounds = run_steps(case, r["N"])
+    assert rounds == T
+    assert rel_l2(got, xs[-1]) < 5e-2
+    print(f"wrapped sdxl_narrow bf16: worst per-evaluation rel L2 {worst:.2e}, final latent {rel_l2(got, xs[-1]):.2e}")
