@@ -34,9 +34,12 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+POOLED = None
+
+
 def run_rounds(m, latent, text, streams, n):
     for _ in range(n):
-        if m.step(latent, text, streams) is None:
+        if m.step(latent, text, streams, pooled=POOLED) is None:
             raise RuntimeError("schedule exhausted")
 
 
@@ -50,6 +53,7 @@ def main():
     ap.add_argument("--graphs", type=int, default=1, help="1 (default): replay full asynchronous rounds from HIP graphs; 0: launch every kernel directly")
     ap.add_argument("--cuts", default="auto", help="partition of the units into components: 'auto' (default: balanced by unit times measured on this GPU "
                     "before the timed region), 'flops' (FLOP-balanced, the library default) or N-1 comma-separated first units of components 2..N")
+    ap.add_argument("--wrap", type=int, default=0, help="1: wrapped segmentation (first and last segment in one component; stride 1, FLOP-balanced cuts)")
     ap.add_argument("--tile", type=int, default=-1, help="GEMM kernel family override for measurements (ad_tune_conv_tile); -1 = automatic")
     ap.add_argument("--order", type=int, default=-1, help="GEMM workgroup order override for measurements (ad_tune_conv_order); -1 = automatic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -69,6 +73,8 @@ def main():
     d, r = CONFIGS[args.config], RUNS[args.config]
     dtype = ad.AD_BF16 if r["dtype"] == "bf16" else ad.AD_F32
     N, w, S = r["N"], r["w"], r["S"]
+    if args.wrap:
+        S = 1
     K, W = args.steps, args.warmup
     dev = "cuda:0"
     t0 = time.time()
@@ -80,14 +86,16 @@ def main():
     wts = SI.make_weights(probe.weight_manifest(), bf16_exact=(dtype == ad.AD_BF16))
     probe.close()
     unit_us = None
-    if args.cuts == "auto":
+    if args.wrap:
+        cuts = None if args.cuts in ("auto", "flops") else [int(x) for x in args.cuts.split(",")]
+    elif args.cuts == "auto":
         # components of comparable measured time: every unit is timed alone on this GPU, then split by the library's rule
         from paper_2406_06911_amd.tuning import time_balanced_cuts
         cuts, unit_us = time_balanced_cuts(d, N, dtype, wts, dev) if N > 1 else (None, None)
         log(f"unit times measured in {time.time() - t0:.1f}s; time-balanced cuts {cuts}")
     else:
         cuts = None if args.cuts == "flops" else [int(x) for x in args.cuts.split(",")]
-    m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts)
+    m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts, wrap=bool(args.wrap))
     m.allocate(dev)
     m.load_weights(wts)
     del wts
@@ -95,6 +103,8 @@ def main():
     tdt = torch.bfloat16 if dtype == ad.AD_BF16 else torch.float32
     text = torch.from_numpy(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"])).to(dev).to(tdt)
     noise = torch.from_numpy(SI.make_latent(d["latent_channels"], d["height"], d["width"])).to(dev)
+    global POOLED
+    POOLED = torch.from_numpy(SI.make_pooled(d["batch"], d["pooled_dim"])).to(dev) if d.get("pooled_dim") else None
     units = m.units()
     flops_step = float(sum(u.flops for u in units))
     sampler = ad.AD_DDIM if r["sampler"] == "ddim" else ad.AD_EULER
@@ -230,13 +240,14 @@ def main():
                           f"{flops_step / 1e9:.0f} GFLOP) in {cpu_sec:.1f}s, scaled by FLOPs to a full step",
                    sample_seconds=round(cpu_sec, 2))
     out = {
-        "metric": "UNet denoising steps/sec, 768px SD2.1-shape N=4, 1 GPU; % bf16 MFMA peak",
+        "metric": "UNet denoising steps/sec, 768px SD2.1-shape N=4, 1 GPU; % bf16 MFMA peak" if args.config == "sd21_768" and not args.wrap
+                  else f"UNet denoising steps/sec, {args.config}, N={N}{' wrapped' if args.wrap else ''}, 1 GPU",
         "value": round(steps_per_s, 3), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtype == ad.AD_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: latent {d['latent_channels']}x{d['height']}x{d['width']}, batch {d['batch']} (guidance), "
                                f"N={N} components on {n_streams} HIP streams, warm-up {w}, stride {S}, {r['sampler']}",
-                   "n_components": N, "stride": S, "streams": n_streams, "hip_graphs": bool(args.graphs), "partition": args.cuts if args.cuts in ("auto", "flops") else "given",
+                   "n_components": N, "stride": S, "streams": n_streams, "hip_graphs": bool(args.graphs), "partition": ("wrapped, " if args.wrap else "") + (("flops" if args.wrap else args.cuts) if args.cuts in ("auto", "flops") else "given"),
                    "component_first_units": [a for a, _ in m.partition()], "flops_per_step": flops_step},
         "component_evals_per_s": round(steps_per_s / S * n_par, 2),
         "sequential_steps_per_s": round(seq_steps_per_s, 3),
