@@ -79,6 +79,21 @@ __device__ __forceinline__ int xcd_remap(int lid, int nblocks) {
 // tiles.  One k-tile is 128 bytes of K per row (64 bf16 / 32 fp32), staged through LDS with a
 // 16-byte row pad; the next k-tile is fetched into registers while the current one is multiplied.
 // =================================================================================================
+// Division of a 32-bit unsigned by a divisor that is the same for the whole launch (Granlund-Montgomery): the host
+// derives a multiplier and two shifts, the device needs a high multiply, a subtract, an add and two shifts.
+// Exact for every numerator below 2^32.
+struct FastDiv { unsigned mul, sh1, sh2; };
+static FastDiv make_fastdiv(unsigned d) {
+  unsigned l = 0;
+  while ((1ull << l) < d) ++l;                                  // ceil(log2 d)
+  const unsigned long long m = ((1ull << 32) * ((1ull << l) - d)) / d + 1;
+  return FastDiv{(unsigned)m, l < 1 ? l : 1u, l > 0 ? l - 1 : 0u};
+}
+__device__ __forceinline__ unsigned fast_div(unsigned n, FastDiv f) {
+  const unsigned t = __umulhi(f.mul, n);
+  return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
 struct IgemmParams {
   const void* src0; const void* src1;
   int c0, c1, ctot;
@@ -91,6 +106,7 @@ struct IgemmParams {
   int kt_per_split;                   // k-tiles handled by one workgroup along grid.y (split-K), else ktiles
   float* partial;                     // split-K: fp32 partial sums [splits][M][N]; nullptr otherwise
   void* out2; void* out3;             // OUT_QKV
+  FastDiv div_hw, div_w;              // by hw_out and by wout (row index -> sample, output row, output column)
   int tiles_m;                        // row tiles
   int n_major;                        // workgroup order: 0 = an XCD owns a run of row tiles (all column tiles of each),
                                       // 1 = an XCD owns a run of column tiles (all row tiles of each); see tile_of()
@@ -329,8 +345,8 @@ __global__ __launch_bounds__(256) void k_igemm(IgemmParams p) {
   for (int i = 0; i < AV; ++i) {
     const int m = m0 + vrow + 32 * i;
     if (m < p.M) {
-      const int b = m / p.hw_out, r = m - b * p.hw_out;
-      const int oy = r / p.wout, ox = r - oy * p.wout;
+      const int b = (int)fast_div((unsigned)m, p.div_hw), r = m - b * p.hw_out;
+      const int oy = (int)fast_div((unsigned)r, p.div_w), ox = r - oy * p.wout;
       a_b[i] = b * p.hs; a_iy0[i] = oy * p.stride - p.pad; a_ix0[i] = ox * p.stride - p.pad;
     } else {
       a_b[i] = -1; a_iy0[i] = 0; a_ix0[i] = 0;
@@ -486,8 +502,8 @@ __global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
   for (int i = 0; i < AV; ++i) {
     const int m = m0 + drow + 32 * i;
     if (m < p.M) {
-      const int b = m / p.hw_out, r = m - b * p.hw_out;
-      const int oy = r / p.wout, ox = r - oy * p.wout;
+      const int b = (int)fast_div((unsigned)m, p.div_hw), r = m - b * p.hw_out;
+      const int oy = (int)fast_div((unsigned)r, p.div_w), ox = r - oy * p.wout;
       a_b[i] = b * p.hs; a_iy0[i] = oy * p.stride - p.pad; a_ix0[i] = ox * p.stride - p.pad;
     } else {
       a_b[i] = -1; a_iy0[i] = 0; a_ix0[i] = 0;
@@ -615,21 +631,33 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
 
   // load i of a k-tile covers rows (4 i + wave) * 8 .. + 7 of the A tile (i < AG) or of the B tile
   const int r8 = lane >> 3, scol = (lane & 7) ^ r8;
+  const int kt_begin = tid3.split * p.kt_per_split;
+  const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
+  const unsigned grp = (unsigned)wave * 8 * kRowBytes;
+  unsigned b_off[BG];
+#pragma unroll
+  for (int i = 0; i < BG; ++i) b_off[i] = (unsigned)((n0 + (4 * i + wave) * 8 + r8) * p.Kp + scol * VN) * ES;
+  // the weight tiles of the first two k-tiles go out before the row arithmetic below, which they do not need
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t)
+    if (t < nkt) {
+#pragma unroll
+      for (int i = 0; i < BG; ++i)
+        dma_load16(rsw, b_off[i], (unsigned)((kt_begin + t) * BK * ES), lds_base + t * STAGE + grp + (BM + i * 32) * kRowBytes);
+    }
   int a_iy0[AG], a_ix0[AG], a_b[AG];
 #pragma unroll
   for (int i = 0; i < AG; ++i) {
     const int m = m0 + (4 * i + wave) * 8 + r8;
     if (m < p.M) {
-      const int b = m / p.hw_out, r = m - b * p.hw_out;
-      const int oy = r / p.wout, ox = r - oy * p.wout;
+      const int b = (int)fast_div((unsigned)m, p.div_hw), r = m - b * p.hw_out;
+      const int oy = (int)fast_div((unsigned)r, p.div_w), ox = r - oy * p.wout;
       a_b[i] = b * p.hs; a_iy0[i] = oy * p.stride - p.pad; a_ix0[i] = ox * p.stride - p.pad;
     } else {
       a_b[i] = -1; a_iy0[i] = 0; a_ix0[i] = 0;
     }
   }
-  unsigned b_off[BG];
-#pragma unroll
-  for (int i = 0; i < BG; ++i) b_off[i] = (unsigned)((n0 + (4 * i + wave) * 8 + r8) * p.Kp + scol * VN) * ES;
   unsigned a_off0[AG], a_off1[AG];
   auto set_tap = [&](int tap) {
     const int u = tap / p.ksize, v = tap - u * p.ksize;
@@ -642,13 +670,9 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
       a_off1[i] = ok ? (pix * (unsigned)p.c1 + scol * VN) * ES : kOob;
     }
   };
-  const int kt_begin = tid3.split * p.kt_per_split;
-  const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
   int f_k0 = kt_begin * BK;
   int f_tap = f_k0 / p.ctot, f_cc = f_k0 - f_tap * p.ctot;
   set_tap(f_tap);
-  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
-  const unsigned grp = (unsigned)wave * 8 * kRowBytes;
   // per-tile state of the loads being issued: which source holds the channels, and the scalar offsets
   bool second = false;
   u32x4 rsa = rs0;
@@ -687,7 +711,7 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
     if (t < nkt) {
       begin_tile();
 #pragma unroll
-      for (int i = 0; i < OPS; ++i) issue_one(t, i);
+      for (int i = 0; i < AG; ++i) issue_one(t, i);      // the B part of these tiles is already on its way
       end_tile();
     }
   // fragment reads: row * 128 + ((chunk ^ (row & 7)) * 16), chunk = 2 ks + half
@@ -744,7 +768,8 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
     if (PHASE == 2) end_tile();
     stage = next;
   };
-  if (nkt > 1) wait_vmcnt<OPS>(); else wait_vmcnt<0>();
+  // issue order so far: B(0), B(1), A(0), A(1): tile 0 is complete once only A(1) is outstanding
+  if (nkt > 1) wait_vmcnt<AG>(); else wait_vmcnt<0>();
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < TM + TN; ++r) read_frag(lds, 0, r);
@@ -962,6 +987,8 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   p.hout = (p.hin + 2 * p.pad - a.ksize) / a.stride + 1;
   p.wout = (p.win + 2 * p.pad - a.ksize) / a.stride + 1;
   p.hw_out = p.hout * p.wout;
+  p.div_hw = make_fastdiv((unsigned)p.hw_out);
+  p.div_w = make_fastdiv((unsigned)p.wout);
   const long long m = (long long)a.batch * p.hw_out;
   if (m > 0x7fffffffLL / 4) AD_FAIL(AD_ERR_INVALID, "conv: too many output positions");
   p.M = (int)m; p.N = a.n_out;
