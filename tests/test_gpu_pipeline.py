@@ -119,7 +119,8 @@ def run_components_along_schedule(case, max_rows=None):
     trace = []
     orc.run(case.noise, case.text, case.pooled, trace=trace)
     rows = m.schedule()
-    assert [tuple(r) for r in rows] == [(r.round, r.comp, r.tau_step, r.read_slot, r.write_slot, r.latent_step, r.eps_step) for r, _ in trace]
+    assert [tuple(r) for r in rows] == [(r.round, r.comp, r.tau_step, r.read_slot, r.write_slot, r.latent_step, r.eps_step, r.fresh_from)
+                                        for r, _ in trace]
     nu = len(orc.units)
     slots = [dict(), dict()]
     latent = case.init_latent()
@@ -132,7 +133,7 @@ def run_components_along_schedule(case, max_rows=None):
     for idx, (row, (orow, obundle)) in enumerate(zip(rows, trace)):
         if max_rows is not None and idx >= max_rows:
             break
-        rnd, comp, tau_step, rd, wr, lat, eps_step = row
+        rnd, comp, tau_step, rd, wr, lat, eps_step, _fresh = row
         if rnd != last_round:
             for (slot, unit, t) in pending:
                 slots[slot][unit] = t
