@@ -1358,42 +1358,57 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
 }
 
 // =================================================================================================
-// GroupNorm (+SiLU), NHWC.  Pass 1: every workgroup reduces a run of pixels to per-channel
-// (sum, sum of squares) partials with fully coalesced row reads.  Pass 2: one wavefront per
-// (sample, group) folds the partials in double precision into per-channel scale and shift.
-// Pass 3: y = silu(x * scale + shift).  No atomics: the result does not depend on scheduling.
+// GroupNorm (+SiLU), NHWC, two launches.  Pass 1: every workgroup reduces a run of pixels of one source to
+// per-channel (sum, sum of squares) with fully coalesced row reads and folds the channels of each group in a
+// fixed order: one (sum, sumsq) pair per (source, sample, pixel chunk, group).  Pass 2: every workgroup first
+// folds those pairs of its sample in double precision (a few KiB, L2-resident) into mean and 1/std per group,
+// then applies y = silu(x * scale + shift) to its run of pixels.  No atomics, no fences: the result does not
+// depend on scheduling.
 // =================================================================================================
-constexpr int kGnMaxChunks = 128;
+constexpr int kGnMaxChunks = 64;
+constexpr int kGnMaxChannels = 4096;      // channels of one source (LDS staging of the per-channel sums)
+constexpr int kGnMaxGroups = 256;
 
 static int gn_chunks(int hw) {
   int n = hw / 8;
   return n < 1 ? 1 : (n > kGnMaxChunks ? kGnMaxChunks : n);
 }
 
+// gpart layout: [source 0/1][sample][chunk][group][2]
 template <typename T>
-__global__ __launch_bounds__(256) void k_gn_partial(const T* __restrict__ src, int cs, int hw, int nchunk, int ctot,
-                                                    int coff, float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void k_gn_partial(const T* __restrict__ src, int cs, int hw, int nchunk, int groups, int cpg,
+                                                    int coff, float* __restrict__ gpart) {
   typedef typename Vec<T>::type V;
   constexpr int VN = Vec<T>::N;
   __shared__ float red[256 * 2 * VN];
+  __shared__ float csum[kGnMaxChannels * 2];
   const int chunk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int p0 = (int)((long long)hw * chunk / nchunk), p1 = (int)((long long)hw * (chunk + 1) / nchunk);
   const int nv = cs / VN;
   const int cvb = nv < 256 ? nv : 256;      // column vectors handled per pass
   const int pl = 256 / cvb;                 // pixel lanes
   const int cv = tid % cvb, lanep = tid / cvb;
-  float* dst = partial + ((size_t)b * nchunk + chunk) * ctot * 2;
   for (int cb = 0; cb < nv; cb += cvb) {
     float s[VN], q[VN];
 #pragma unroll
     for (int e = 0; e < VN; ++e) { s[e] = 0.f; q[e] = 0.f; }
     const bool on = lanep < pl && cb + cv < nv;
-    if (on)
-      for (int p = p0 + lanep; p < p1; p += pl) {
-        const V v = *(const V*)(src + ((size_t)b * hw + p) * cs + (size_t)(cb + cv) * VN);
+    if (on) {
+      constexpr int UN = 4;                     // rows in flight per thread; summed in row order
+      const T* sp = src + (size_t)b * hw * cs + (size_t)(cb + cv) * VN;
+      for (int p = p0 + lanep; p < p1; p += pl * UN) {
+        V v[UN];
 #pragma unroll
-        for (int e = 0; e < VN; ++e) { const float f = to_f(v[e]); s[e] += f; q[e] += f * f; }
+        for (int u = 0; u < UN; ++u)
+          if (p + u * pl < p1) v[u] = *(const V*)(sp + (size_t)(p + u * pl) * cs);
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+          if (p + u * pl >= p1) break;
+#pragma unroll
+          for (int e = 0; e < VN; ++e) { const float f = to_f(v[u][e]); s[e] += f; q[e] += f * f; }
+        }
       }
+    }
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < VN; ++e) { red[(tid * VN + e) * 2] = s[e]; red[(tid * VN + e) * 2 + 1] = q[e]; }
@@ -1403,80 +1418,95 @@ __global__ __launch_bounds__(256) void k_gn_partial(const T* __restrict__ src, i
       for (int e = 0; e < VN; ++e) {
         float ts = 0.f, tq = 0.f;
         for (int j = 0; j < pl; ++j) { ts += red[((j * cvb + cv) * VN + e) * 2]; tq += red[((j * cvb + cv) * VN + e) * 2 + 1]; }
-        const int c = coff + (cb + cv) * VN + e;
-        dst[c * 2] = ts; dst[c * 2 + 1] = tq;
+        const int c = (cb + cv) * VN + e;
+        csum[c * 2] = ts; csum[c * 2 + 1] = tq;
       }
     }
   }
-}
-
-__global__ __launch_bounds__(256) void k_gn_finalize(const float* __restrict__ partial, int nchunk, int ctot, int groups,
-                                                     int hw, const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                     float eps, float* __restrict__ scale_shift) {
-  __shared__ double red[8];
-  const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int cpg = ctot / groups;
-  double s = 0.0, q = 0.0;
-  for (int i = tid; i < nchunk * cpg; i += 256) {
-    const int ch = i / cpg, j = i - ch * cpg;
-    const float* pp = partial + (((size_t)b * nchunk + ch) * ctot + g * cpg + j) * 2;
-    s += pp[0]; q += pp[1];
-  }
-  s = wave_sum_d(s); q = wave_sum_d(q);
-  if (lane == 0) { red[wave * 2] = s; red[wave * 2 + 1] = q; }
   __syncthreads();
-  s = red[0] + red[2] + red[4] + red[6];      // fixed order: the result does not depend on scheduling
-  q = red[1] + red[3] + red[5] + red[7];
-  const double n = (double)hw * cpg;
-  const double mean = s / n;
-  double var = q / n - mean * mean;
-  if (var < 0) var = 0;
-  const double rstd = 1.0 / sqrt(var + (double)eps);
-  for (int j = tid; j < cpg; j += 256) {
-    const int c = g * cpg + j;
-    const double sc = rstd * gamma[c];
-    scale_shift[((size_t)b * ctot + c) * 2] = (float)sc;
-    scale_shift[((size_t)b * ctot + c) * 2 + 1] = (float)(beta[c] - mean * sc);
+  // channels -> groups, in channel order; a group may extend into the other source, which adds its own pair
+  float* dst = gpart + ((size_t)b * nchunk + chunk) * groups * 2;
+  for (int g = tid; g < groups; g += 256) {
+    const int lo = max(g * cpg, coff) - coff, hi = min((g + 1) * cpg, coff + cs) - coff;
+    if (lo >= hi) continue;
+    float ts = 0.f, tq = 0.f;
+    for (int c = lo; c < hi; ++c) { ts += csum[c * 2]; tq += csum[c * 2 + 1]; }
+    dst[g * 2] = ts; dst[g * 2 + 1] = tq;
   }
 }
-
-constexpr int kGnRows = 8;   // rows handled per thread in the apply pass (scale and shift stay in registers)
 
 template <typename T>
-__global__ __launch_bounds__(256) void k_gn_apply(const T* __restrict__ src0, const T* __restrict__ src1, int c0, int c1,
-                                                  long long rows, int hw, const float* __restrict__ scale_shift, int silu,
-                                                  T* __restrict__ out) {
+__global__ __launch_bounds__(256) void k_gn_apply(const T* __restrict__ src0, const T* __restrict__ src1, int c0, int c1, int hw,
+                                                  int rows_per_block, int nchunk, int groups, const float* __restrict__ gpart,
+                                                  size_t src_stride, const float* __restrict__ gamma,
+                                                  const float* __restrict__ beta, float eps, int silu, T* __restrict__ out) {
   typedef typename Vec<T>::type V;
   constexpr int VN = Vec<T>::N;
-  const int ctot = c0 + c1, nv = ctot / VN;
-  const long long groups = (rows + kGnRows - 1) / kGnRows;
-  const long long total = groups * nv;
-  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-    const long long grp = i / nv;
-    const int c = (int)(i - grp * nv) * VN;
-    const long long row0 = grp * kGnRows;
-    int b = -1;
+  __shared__ double dred[256 * 2];
+  __shared__ float smean[kGnMaxGroups], srstd[kGnMaxGroups];
+  const int tid = threadIdx.x, b = blockIdx.y;
+  const int ctot = c0 + c1, cpg = ctot / groups;
+  // statistics of this sample: thread (group, part) sums every parts-th chunk, the parts are folded in order
+  const int parts = groups < 256 ? 256 / groups : 1;
+  for (int g0 = 0; g0 < groups; g0 += 256) {
+    const int g = g0 + tid % (groups < 256 ? groups : 256), part = tid / (groups < 256 ? groups : 256);
+    double s = 0.0, q = 0.0;
+    if (g < groups && part < parts) {
+      const bool in0 = g * cpg < c0, in1 = (g + 1) * cpg > c0;
+      for (int ch = part; ch < nchunk; ch += parts) {
+        const size_t o = (((size_t)b * nchunk + ch) * groups + g) * 2;
+        if (in0) { s += gpart[o]; q += gpart[o + 1]; }
+        if (in1) { s += gpart[src_stride + o]; q += gpart[src_stride + o + 1]; }
+      }
+    }
+    dred[tid * 2] = s; dred[tid * 2 + 1] = q;
+    __syncthreads();
+    if (part == 0 && g < groups) {
+      const int gw = groups < 256 ? groups : 256;
+      for (int j = 1; j < parts; ++j) { s += dred[(j * gw + tid) * 2]; q += dred[(j * gw + tid) * 2 + 1]; }
+      const double n = (double)hw * cpg;
+      const double mean = s / n;
+      double var = q / n - mean * mean;
+      if (var < 0) var = 0;
+      smean[g] = (float)mean;
+      srstd[g] = (float)(1.0 / sqrt(var + (double)eps));
+    }
+    __syncthreads();
+  }
+  const int nv = ctot / VN;
+  const int cvb = nv < 256 ? nv : 256, pl = 256 / cvb;
+  const int cv = tid % cvb, lanep = tid / cvb;
+  const int r0 = blockIdx.x * rows_per_block, r1 = min(hw, r0 + rows_per_block);
+  for (int cb = 0; cb < nv; cb += cvb) {
+    if (lanep >= pl || cb + cv >= nv) continue;
+    const int c = (cb + cv) * VN;
     float sc[VN], sh[VN];
 #pragma unroll
-    for (int r = 0; r < kGnRows; ++r) {
-      const long long row = row0 + r;
-      if (row >= rows) break;
-      const int rb = (int)(row / hw);
-      if (rb != b) {
-        b = rb;
-        const float* ss = scale_shift + ((size_t)b * ctot + c) * 2;
+    for (int e = 0; e < VN; ++e) {
+      const int g = (c + e) / cpg;
+      sc[e] = srstd[g] * gamma[c + e];
+      sh[e] = beta[c + e] - smean[g] * sc[e];
+    }
+    const T* sp = c < c0 ? src0 + c : src1 + (c - c0);
+    const size_t ld = c < c0 ? c0 : c1;
+    constexpr int UN = 4;                       // rows in flight per thread
+    for (int p = r0 + lanep; p < r1; p += pl * UN) {
+      V v[UN];
 #pragma unroll
-        for (int e = 0; e < VN; ++e) { sc[e] = ss[2 * e]; sh[e] = ss[2 * e + 1]; }
-      }
-      const V v = c < c0 ? *(const V*)(src0 + row * c0 + c) : *(const V*)(src1 + row * c1 + (c - c0));
-      V o;
+      for (int u = 0; u < UN; ++u)
+        if (p + u * pl < r1) v[u] = *(const V*)(sp + ((size_t)b * hw + p + u * pl) * ld);
 #pragma unroll
-      for (int e = 0; e < VN; ++e) {
-        float y = to_f(v[e]) * sc[e] + sh[e];
-        if (silu) y = silu_f(y);
-        o[e] = from_f<T>(y);
+      for (int u = 0; u < UN; ++u) {
+        if (p + u * pl >= r1) break;
+        V o;
+#pragma unroll
+        for (int e = 0; e < VN; ++e) {
+          float y = to_f(v[u][e]) * sc[e] + sh[e];
+          if (silu) y = silu_f(y);
+          o[e] = from_f<T>(y);
+        }
+        *(V*)(out + ((size_t)b * hw + p + u * pl) * ctot + c) = o;
       }
-      *(V*)(out + row * ctot + c) = o;
     }
   }
 }
@@ -1541,7 +1571,7 @@ __global__ __launch_bounds__(256) void k_gn_small(const T* __restrict__ src0, co
 
 extern "C" size_t ad_groupnorm_scratch_bytes(int batch, int hw, int c) {
   (void)hw;
-  return ((size_t)batch * ad::kGnMaxChunks * c * 2 + (size_t)batch * c * 2) * 4;
+  return (size_t)batch * ad::kGnMaxChunks * c * 4 * sizeof(float);     // two sources x (sum, sumsq) per chunk and group (groups <= c)
 }
 
 namespace ad {
@@ -1559,26 +1589,26 @@ static ad_status run_groupnorm(const void* src0, const void* src1, int c0, int c
     AD_HIP(hipGetLastError());
     return AD_OK;
   }
-  float* partial = (float*)scratch;
-  float* ss = partial + (size_t)batch * kGnMaxChunks * ctot * 2;
+  if (c0 > kGnMaxChannels || c1 > kGnMaxChannels || groups > kGnMaxGroups)
+    AD_FAIL(AD_ERR_INVALID, "groupnorm: at most %d channels per source and %d groups", kGnMaxChannels, kGnMaxGroups);
+  float* gpart = (float*)scratch;
+  const size_t src_stride = (size_t)batch * nchunk * groups * 2;
   const long long rows = (long long)batch * hw;
   {
     ProfLaunch pl("gn_partial", 0, (double)rows * c0 * sizeof(T), s, (int)rows, c0, 0);
-    hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src0, c0, hw, nchunk, ctot, 0, partial);
+    hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src0, c0, hw, nchunk, groups, cpg, 0, gpart);
   }
   if (c1) {
     ProfLaunch pl("gn_partial", 0, (double)rows * c1 * sizeof(T), s, (int)rows, c1, 0);
-    hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src1, c1, hw, nchunk, ctot, c0, partial);
+    hipLaunchKernelGGL(k_gn_partial<T>, dim3(nchunk, batch), dim3(256), 0, s, (const T*)src1, c1, hw, nchunk, groups, cpg, c0, gpart + src_stride);
   }
-  {
-    ProfLaunch pl("gn_finalize", 0, 0, s, (int)rows, ctot, 0);
-    hipLaunchKernelGGL(k_gn_finalize, dim3(groups, batch), dim3(256), 0, s, partial, nchunk, ctot, groups, hw, gamma, beta, eps, ss);
-  }
-  const long long vecs = ((rows + kGnRows - 1) / kGnRows) * (ctot / Vec<T>::N);
-  int blocks = (int)((vecs + 255) / 256 < 8192 ? (vecs + 255) / 256 : 8192);
-  if (blocks < 1) blocks = 1;
+  // about 768 workgroups: each folds the statistics of its sample once and then streams its rows
+  int rows_per_block = (hw * batch + 767) / 768;
+  if (rows_per_block < 8) rows_per_block = 8;
+  const int row_blocks = (hw + rows_per_block - 1) / rows_per_block;
   ProfLaunch pl("gn_apply", 0, 2.0 * rows * ctot * sizeof(T), s, (int)rows, ctot, 0);
-  hipLaunchKernelGGL(k_gn_apply<T>, dim3(blocks), dim3(256), 0, s, (const T*)src0, (const T*)src1, c0, c1, rows, hw, ss, silu, (T*)out);
+  hipLaunchKernelGGL(k_gn_apply<T>, dim3(row_blocks, batch), dim3(256), 0, s, (const T*)src0, (const T*)src1, c0, c1, hw, rows_per_block, nchunk,
+                     groups, gpart, src_stride, gamma, beta, eps, silu, (T*)out);
   AD_HIP(hipGetLastError());
   return AD_OK;
 }
