@@ -24,10 +24,10 @@ PEAK_HBM_GBS = 8000.0
 # `rocprofv3 --pmc` runs of this file (FETCH_SIZE, WRITE_SIZE; KiB per dispatch scaled by the factors 2.00 and 1.00 that the
 # same counters show for the 2^26-element sampler launch).  Commands and tables: profiles/bench_sd21_768_all_kernels.md.
 MEASURED_TRAFFIC = {"sd21_768": {
-    "attn_mfma_bf16": 22606529, "igemm_bf16_128x128_p3": 135523489, "igemm_bf16_128x128_dma": 56125384,
-    "igemm_bf16_256x128_p3": 76287400, "igemm_bf16_64x64_p3": 25208776, "igemm_bf16_128x128_p3_splitk": 53056367,
-    "igemm_bf16_256x128_p3_splitk": 119105773, "splitk_reduce": 17837781, "gn_apply": 17453181, "gn_partial": 8349800,
-    "layernorm": 13111232, "gn_finalize": 2068316, "linear_rows": 5907990, "gn_small": 3065651}}
+    "attn_mfma_bf16": 22607347, "igemm_bf16_128x128_p3": 135831880, "igemm_bf16_128x128_dma": 56102124,
+    "igemm_bf16_256x128_p3": 76241607, "igemm_bf16_64x64_p3": 25201794, "igemm_bf16_128x128_p3_splitk": 53032738,
+    "igemm_bf16_256x128_p3_splitk": 119036038, "splitk_reduce": 17822420, "gn_apply": 17523399, "gn_partial": 7280059,
+    "layernorm": 13111235, "linear_rows": 5918259, "gn_small": 3070908}}
 
 
 def log(*a):
