@@ -4,7 +4,7 @@
 //                  optional channel concatenation) and linear layers on MFMA, with fused epilogues
 //   k_attn_mfma    fused attention (online softmax, K and V^T tiles in LDS, MFMA for QK^T and PV)
 //   k_attn_simple  generic attention, one wavefront per query (fp32 mode, odd head sizes)
-//   k_gn_*         GroupNorm (+SiLU) in three passes: per-channel partial sums, group statistics, apply
+//   k_gn_*         GroupNorm (+SiLU) in two passes: per-group partial sums, then statistics + apply
 //   k_layernorm    one wavefront per token
 //   k_linear_rows  skinny linear layer for the time-embedding path
 //   k_sampler      guidance combination + DDIM / Euler latent update
