@@ -56,14 +56,16 @@ class Pipeline:
                     if self.sampler == "euler":
                         # the latent's noise level is that of the step it belongs to
                         xin = xin * SM.euler_input_scale(self._latent_step, self.taus, self.acp)
-                    avail[-1] = np.broadcast_to(xin, (self.cfg.batch,) + xin.shape).copy()
+                    # image model: the guidance rows share the latent; video model: one latent per frame
+                    avail[-1] = xin.copy() if self.cfg.frames else np.broadcast_to(xin, (self.cfg.batch,) + xin.shape).copy()
                 else:
                     avail[i] = stored[self.owner[i]][i]
             return run_units(self.cfg, self.units, a, b, self.wts, avail, self.taus[tau_step], ctx, pooled)
         return fn
 
     def eps_fn(self, bundle):
-        return SM.cfg_combine(bundle[len(self.units) - 1], self.cfg_scale)
+        eps = bundle[len(self.units) - 1]
+        return np.asarray(eps, F) if self.cfg.frames else SM.cfg_combine(eps, self.cfg_scale)
 
     def sampler_fn(self, x, eps, i):
         step = SM.ddim_step if self.sampler == "ddim" else SM.euler_step

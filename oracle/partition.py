@@ -29,9 +29,13 @@ def unit_flops(cfg: UNetConfig, u: Unit) -> int:
         lin = 2 * b * l * c * c
         f = 2 * lin                                   # proj_in, proj_out
         per = 4 * lin + 4 * b * l * l * c             # self: q,k,v,o + QK^T and PV over all heads
-        per += 2 * lin + 2 * (2 * b * lk * c * cfg.ctx_dim) + 4 * b * l * lk * c   # cross
+        bt = 1 if cfg.frames else b                   # rows of the text embedding (shared by the frames of a video)
+        per += 2 * lin + 2 * (2 * bt * lk * c * cfg.ctx_dim) + 4 * b * l * lk * c  # cross
         per += 24 * b * l * c * c                     # GEGLU: C->8C and 4C->C
-        return f + u.depth * per
+        f += u.depth * per
+        if cfg.temporal_heads:                        # q,k,v,o + QK^T and PV over the frame axis at every position
+            f += 4 * lin + 4 * b * l * cfg.frames * c
+        return f
     raise ValueError(u.kind)
 
 

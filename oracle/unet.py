@@ -35,6 +35,11 @@ class UNetConfig:
     ctx_len: int = 8
     ctx_dim: int = 32
     pooled_dim: int = 0
+    # video model: `frames` > 0 makes the batch axis the frame axis (batch == frames, one latent per frame, no
+    # guidance, one text embedding shared by all frames); `temporal_heads` > 0 adds a temporal attention layer
+    # after every spatial transformer
+    frames: int = 0
+    temporal_heads: int = 0
     gn_eps: float = 1e-5
     ln_eps: float = 1e-5
 
@@ -140,6 +145,10 @@ def weight_manifest(cfg: UNetConfig):
                       (f"{p}.ff1.w", (8 * c, c)), (f"{p}.ff1.b", (8 * c,)),
                       (f"{p}.ff2.w", (c, 4 * c)), (f"{p}.ff2.b", (c,))]
             m += [(f"{n}.proj_out.w", (c, c)), (f"{n}.proj_out.b", (c,))]
+            if cfg.temporal_heads:
+                m += [(f"{n}.temp.ln.g", (c,)), (f"{n}.temp.ln.b", (c,)),
+                      (f"{n}.temp.q.w", (c, c)), (f"{n}.temp.k.w", (c, c)), (f"{n}.temp.v.w", (c, c)),
+                      (f"{n}.temp.o.w", (c, c)), (f"{n}.temp.o.b", (c,))]
     return m
 
 
@@ -166,10 +175,25 @@ def _res(cfg, u, wts, x, temb):
     return x + h
 
 
+def _temporal(cfg, u, wts, z):
+    """Temporal attention layer of the video model: at every spatial position the frames are the tokens.
+    z: [frames, C, H, W] -> z + Out(MHA_over_frames(LN(z))); no positional term, no feed-forward."""
+    n = u.name
+    f, c, hh, ww = z.shape
+    t = z.reshape(f, c, hh * ww).transpose(2, 0, 1)            # [positions, frames, C]: batch = position
+    y = P.layer_norm(t, wts[f"{n}.temp.ln.g"], wts[f"{n}.temp.ln.b"], cfg.ln_eps)
+    a = P.attention(P.linear(y, wts[f"{n}.temp.q.w"]), P.linear(y, wts[f"{n}.temp.k.w"]),
+                    P.linear(y, wts[f"{n}.temp.v.w"]), cfg.temporal_heads)
+    t = t + P.linear(a, wts[f"{n}.temp.o.w"], wts[f"{n}.temp.o.b"])
+    return t.transpose(1, 2, 0).reshape(f, c, hh, ww)
+
+
 def _tfm(cfg, u, wts, x, ctx):
     n = u.name
     b, c, hh, ww = x.shape
     heads = c // cfg.head_dim
+    if ctx.shape[0] != b:                                      # one text embedding shared by all frames
+        ctx = np.broadcast_to(ctx, (b,) + ctx.shape[1:])
     h = P.group_norm(x, cfg.gn_groups, wts[f"{n}.gn.g"], wts[f"{n}.gn.b"], cfg.gn_eps)
     h = h.reshape(b, c, hh * ww).transpose(0, 2, 1)            # [B, L, C] tokens
     h = P.linear(h, wts[f"{n}.proj_in.w"], wts[f"{n}.proj_in.b"])
@@ -186,7 +210,8 @@ def _tfm(cfg, u, wts, x, ctx):
         y = P.layer_norm(h, wts[f"{p}.ln3.g"], wts[f"{p}.ln3.b"], cfg.ln_eps)
         h = h + P.geglu_ff(y, wts[f"{p}.ff1.w"], wts[f"{p}.ff1.b"], wts[f"{p}.ff2.w"], wts[f"{p}.ff2.b"])
     h = P.linear(h, wts[f"{n}.proj_out.w"], wts[f"{n}.proj_out.b"])
-    return x + h.transpose(0, 2, 1).reshape(b, c, hh, ww)
+    z = x + h.transpose(0, 2, 1).reshape(b, c, hh, ww)
+    return _temporal(cfg, u, wts, z) if cfg.temporal_heads else z
 
 
 def run_unit(cfg, units, i, wts, x, skip, temb, ctx):

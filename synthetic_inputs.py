@@ -51,6 +51,11 @@ def make_latent(channels, h, w, seed=SEED_LATENT):
     return rng.standard_normal((channels, h, w), dtype=np.float32)
 
 
+def make_video_latent(frames, channels, h, w, seed=SEED_LATENT):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return rng.standard_normal((frames, channels, h, w), dtype=np.float32)
+
+
 def make_text(batch, ctx_len, ctx_dim, seed=SEED_TEXT):
     rng = np.random.Generator(np.random.PCG64(seed))
     return rng.standard_normal((batch, ctx_len, ctx_dim), dtype=np.float32)
