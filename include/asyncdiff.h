@@ -20,6 +20,8 @@
  *     classifier-free guidance share it).  The noise prediction is DEVICE fp32
  *     [batch][latent_channels][H][W].  The text embedding is DEVICE, element type = cfg.dtype,
  *     [batch][ctx_len][ctx_dim]; the pooled embedding DEVICE fp32 [batch][pooled_dim].
+ *     Video model (cfg.frames > 0): latent and noise prediction are both fp32 [frames][latent_channels][H][W],
+ *     the text embedding is [1][ctx_len][ctx_dim], the sampler applies no guidance.
  *   - Steps are numbered i = 0..T-1 in execution order; tau_i is the training timestep of step i.
  *   - Calls that take a stream only enqueue work; they never synchronise.
  *   - Every call returns an ad_status; no exception crosses the boundary.  ad_last_error()
@@ -72,6 +74,14 @@ typedef struct ad_unet_cfg {
   int pooled_dim;                       /* 0 = no pooled-embedding branch */
   float gn_eps, ln_eps;
   int dtype;                            /* ad_dtype: storage type of weights and hidden states */
+  /* Video model (Section 4, "Experimental Results on Video Diffusion Models", Table 4: the same schedule on a UNet
+   * with temporal layers).  frames > 0: the batch axis is the frame axis (batch == frames <= 16), every frame has its own latent,
+   * there is no guidance pair, one text embedding [1][ctx_len][ctx_dim] serves all frames.  temporal_heads > 0 adds,
+   * after every spatial transformer, a temporal attention layer: LayerNorm, multi-head attention whose tokens are
+   * the frames of one spatial position (head width = channels / temporal_heads, no positional term), output
+   * projection, residual.  Both 0: image model. */
+  int frames;
+  int temporal_heads;
 } ad_unet_cfg;
 
 typedef struct ad_unit_info {
@@ -296,6 +306,12 @@ ad_status ad_layernorm_forward(int dtype, const void* src, int rows, int c, cons
 ad_status ad_attention_forward(int dtype, const void* q, const void* k, const void* v, int v_is_transposed,
                                int batch, int l, int lk, int c, int head_dim, int ldq, int ldk, int ldv, int ldo,
                                void* out, ad_stream stream);
+
+/* Attention over the frame axis (temporal layer of the video model): at each of `positions` spatial positions the
+ * `frames` (<= 16) rows f * positions + p, f = 0..frames-1, are one sequence; heads of width c / heads;
+ * out[row][h*d+j] = softmax(q k^T / sqrt(d)) v within the sequence.  q, k, v, out: [frames*positions][ld*]. */
+ad_status ad_attention_frames_forward(int dtype, const void* q, const void* k, const void* v, int frames, int positions,
+                                      int c, int heads, int ldq, int ldk, int ldv, int ldo, void* out, ad_stream stream);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,8 @@ class UNetCfg(C.Structure):
                 ("n_levels", C.c_int), ("channels", C.c_int * 4), ("layers_per_block", C.c_int),
                 ("transformer_depth", C.c_int * 4), ("mid_depth", C.c_int), ("head_dim", C.c_int),
                 ("gn_groups", C.c_int), ("ctx_len", C.c_int), ("ctx_dim", C.c_int), ("pooled_dim", C.c_int),
-                ("gn_eps", C.c_float), ("ln_eps", C.c_float), ("dtype", C.c_int)]
+                ("gn_eps", C.c_float), ("ln_eps", C.c_float), ("dtype", C.c_int),
+                ("frames", C.c_int), ("temporal_heads", C.c_int)]
 
     @classmethod
     def from_dict(cls, d, dtype):
@@ -43,6 +44,7 @@ class UNetCfg(C.Structure):
         c.gn_groups, c.ctx_len, c.ctx_dim, c.pooled_dim = d["gn_groups"], d["ctx_len"], d["ctx_dim"], d.get("pooled_dim", 0)
         c.gn_eps, c.ln_eps = d.get("gn_eps", 1e-5), d.get("ln_eps", 1e-5)
         c.dtype = dtype
+        c.frames, c.temporal_heads = d.get("frames", 0), d.get("temporal_heads", 0)
         return c
 
 
@@ -76,6 +78,7 @@ EXPORTS = [
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
     "ad_conv_forward", "ad_conv_workspace_bytes", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
     "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode", "ad_create_with_cuts", "ad_balance_cuts", "ad_tune_conv_order", "ad_create_wrapped", "ad_num_segments",
+    "ad_attention_frames_forward",
 ]
 
 
@@ -122,6 +125,7 @@ def _load():
     L.ad_groupnorm_forward.argtypes = [ci, vp, vp, ci, ci, ci, ci, ci, vp, vp, cf, ci, vp, vp, vp]
     L.ad_layernorm_forward.argtypes = [ci, vp, ci, ci, vp, vp, cf, vp, vp]
     L.ad_attention_forward.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
+    L.ad_attention_frames_forward.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
     L.ad_tune_conv_tile.argtypes = [ci]
     L.ad_precompute_text.argtypes = [vp, vp, vp]
     L.ad_set_graph_mode.argtypes = [vp, ci]

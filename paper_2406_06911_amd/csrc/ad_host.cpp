@@ -98,10 +98,13 @@ int64_t unit_flops(const ad_unet_cfg& c, const ad_unit_info& u) {
     case AD_UNIT_TFM: {
       int64_t C = u.c_in, L = (int64_t)u.h_in * u.w_in, Lk = c.ctx_len;
       int64_t lin = 2 * B * L * C * C;
+      const int64_t Bt = c.frames > 0 ? 1 : B;                                     // rows of the text embedding
       int64_t per = 4 * lin + 4 * B * L * L * C;                                  // self attention
-      per += 2 * lin + 2 * (2 * B * Lk * C * c.ctx_dim) + 4 * B * L * Lk * C;      // cross attention
+      per += 2 * lin + 2 * (2 * Bt * Lk * C * c.ctx_dim) + 4 * B * L * Lk * C;     // cross attention
       per += 24 * B * L * C * C;                                                  // GEGLU feed-forward
-      return 2 * lin + u.depth * per;
+      int64_t f = 2 * lin + u.depth * per;
+      if (c.temporal_heads > 0) f += 4 * lin + 4 * B * L * c.frames * C;           // temporal layer: q, k, v, o + scores over frames
+      return f;
     }
   }
   return 0;
@@ -299,6 +302,12 @@ static void build_manifest(Ctx& c) {
           add_w(c, p + ".ff2.w", W_CONV1, {C, 4 * C}); add_w(c, p + ".ff2.b", W_VEC_F32, {C});
         }
         add_w(c, n + ".proj_out.w", W_CONV1, {C, C}); add_w(c, n + ".proj_out.b", W_VEC_F32, {C});
+        if (g.temporal_heads > 0) {
+          const std::string p = n + ".temp";
+          add_w(c, p + ".ln.g", W_VEC_F32, {C}); add_w(c, p + ".ln.b", W_VEC_F32, {C});
+          add_w(c, p + ".q.w", W_QKV_Q, {C, C}); add_w(c, p + ".k.w", W_QKV_KV, {C, C}); add_w(c, p + ".v.w", W_QKV_KV, {C, C});
+          add_w(c, p + ".o.w", W_CONV1, {C, C}); add_w(c, p + ".o.b", W_VEC_F32, {C});
+        }
         break;
       }
     }
@@ -352,7 +361,7 @@ void pack_rows(int dtype, const float* w, size_t n, void* out) {
 // ------------------------------------------------------------------------------------------------
 size_t tensor_bytes(const Ctx& c, int unit) {
   const ad_unet_cfg& g = c.cfg;
-  if (unit < 0) return (size_t)g.latent_channels * g.height * g.width * 4;
+  if (unit < 0) return (size_t)(g.frames > 0 ? g.frames : 1) * g.latent_channels * g.height * g.width * 4;
   const ad_unit_info& u = c.units[unit].info;
   if (unit == (int)c.units.size() - 1) return (size_t)g.batch * u.c_out * u.h_out * u.w_out * 4;
   return (size_t)g.batch * u.h_out * u.w_out * u.c_out * esize(g.dtype);
@@ -407,9 +416,10 @@ static void plan_work(Ctx& c) {
     const ad_unit_info& u = c.units[ui].info;
     if (u.kind != AD_UNIT_TFM) continue;
     const bool vt = g.dtype == AD_BF16 && g.head_dim == 64;
+    const size_t bt = g.frames > 0 ? 1 : g.batch;          // rows of the text embedding
     for (int k = 0; k < u.depth; ++k) {
-      c.text_k_off[ui].push_back(take((size_t)g.batch * g.ctx_len * u.c_in * es));
-      c.text_v_off[ui].push_back(take(vt ? (size_t)g.batch * u.c_in * round_up(g.ctx_len, 64) * es : (size_t)g.batch * g.ctx_len * u.c_in * es));
+      c.text_k_off[ui].push_back(take(bt * g.ctx_len * u.c_in * es));
+      c.text_v_off[ui].push_back(take(vt ? bt * u.c_in * round_up(g.ctx_len, 64) * es : bt * g.ctx_len * u.c_in * es));
     }
   }
   // per (component, lane) activation workspaces
@@ -526,6 +536,18 @@ static ad_status validate(const ad_unet_cfg& g, int n, int warmup, int stride) {
     if (g.head_dim > 128 || g.head_dim % 8) AD_FAIL(AD_ERR_INVALID, "head_dim must be a multiple of 8, at most 128");
   }
   if (g.pooled_dim < 0 || g.pooled_dim % 8) AD_FAIL(AD_ERR_INVALID, "pooled_dim must be a non-negative multiple of 8");
+  if (g.frames < 0 || g.frames > 16) AD_FAIL(AD_ERR_INVALID, "frames must be 0 (image model) or 1..16");
+  if (g.frames > 0 && g.batch != g.frames) AD_FAIL(AD_ERR_INVALID, "a video model has batch == frames");
+  if (g.frames > 0 && g.pooled_dim > 0) AD_FAIL(AD_ERR_INVALID, "the pooled-embedding branch is not defined for the video model");
+  if (g.temporal_heads < 0 || (g.temporal_heads > 0 && g.frames == 0)) AD_FAIL(AD_ERR_INVALID, "temporal_heads needs frames > 0");
+  if (g.temporal_heads > 0) {
+    for (int l = 0; l < g.n_levels; ++l)
+      if (g.transformer_depth[l] > 0 && (g.channels[l] % g.temporal_heads || g.channels[l] / g.temporal_heads > 320))
+        AD_FAIL(AD_ERR_INVALID, "channels[%d] must split into temporal_heads heads of at most 320 channels", l);
+    const int cm_ = g.channels[g.n_levels - 1];
+    if (g.mid_depth > 0 && (cm_ % g.temporal_heads || cm_ / g.temporal_heads > 320))
+      AD_FAIL(AD_ERR_INVALID, "mid channels must split into temporal_heads heads of at most 320 channels");
+  }
   if (!(g.gn_eps > 0) || !(g.ln_eps > 0)) AD_FAIL(AD_ERR_INVALID, "eps values must be positive");
   if (n < 1) AD_FAIL(AD_ERR_INVALID, "n_components must be >= 1");
   if (stride < 1 || stride > 8) AD_FAIL(AD_ERR_INVALID, "stride must be 1..8");
@@ -665,7 +687,7 @@ ad_status ad_tensor_shape(const ad_ctx* ctx, int unit, int* b, int* h, int* w, i
   const Ctx& x = *C(ctx);
   if (unit < -1 || unit >= (int)x.units.size()) AD_FAIL(AD_ERR_INVALID, "unit %d out of range", unit);
   int bb, hh, ww, cc;
-  if (unit < 0) { bb = 1; hh = x.cfg.height; ww = x.cfg.width; cc = x.cfg.latent_channels; }
+  if (unit < 0) { bb = x.cfg.frames > 0 ? x.cfg.frames : 1; hh = x.cfg.height; ww = x.cfg.width; cc = x.cfg.latent_channels; }
   else { const ad_unit_info& u = x.units[unit].info; bb = x.cfg.batch; hh = u.h_out; ww = u.w_out; cc = u.c_out; }
   if (b) *b = bb; if (h) *h = hh; if (w) *w = ww; if (c) *c = cc;
   if (bytes) *bytes = tensor_bytes(x, unit);

@@ -59,6 +59,9 @@ ad_status launch_layernorm(int dtype, const void* src, int rows, int c, const fl
                            void* out, hipStream_t s);
 ad_status launch_attention(int dtype, const void* q, const void* k, const void* v, int v_t, int batch, int l, int lk, int c,
                            int head_dim, int ldq, int ldk, int ldv, int ldo, void* out, hipStream_t s);
+// attention over the frame axis: row (f, p) = f * positions + p of q / k / v / out; heads = c / head width
+ad_status launch_attention_frames(int dtype, const void* q, const void* k, const void* v, int frames, int positions, int c,
+                                  int heads, int ldq, int ldk, int ldv, int ldo, void* out, hipStream_t s);
 // out[r][n] = act_out(bias[n] + sum_k act_in(in[r*in_ld + k]) w[n][k]); in/out fp32, w in dtype; rows <= 16;
 // in_ld = 0 feeds every row the same input
 ad_status launch_linear_rows(int dtype, const float* in, int in_ld, int rows, int k, const void* w, const float* bias, int n,
@@ -73,8 +76,9 @@ struct StepRef {
 };
 ad_status launch_sinusoid(float tau, StepRef ref, int dim, float* out, hipStream_t s);
 ad_status launch_advance(int* counter, int by, hipStream_t s);
-// im2col of the fp32 latent [cl][h][w] (times scale) for the first 3x3 convolution: out [batch*h*w][kConvInK]
-ad_status launch_pack_latent(int dtype, const float* latent, float scale, StepRef ref, int cl, int h, int w, int batch,
+// im2col of the fp32 latent (times scale) for the first 3x3 convolution: out [batch*h*w][kConvInK]; the latent is
+// [cl][h][w] shared by all batch rows, or [batch][cl][h][w] when per_sample is set
+ad_status launch_pack_latent(int dtype, const float* latent, int per_sample, float scale, StepRef ref, int cl, int h, int w, int batch,
                              void* out, hipStream_t s);
 ad_status launch_sampler(float* x, const float* eps, size_t n, int batch, float cx, float ce, StepRef ref, float g, hipStream_t s);
 

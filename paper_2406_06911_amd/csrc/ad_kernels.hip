@@ -4,6 +4,7 @@
 //                  optional channel concatenation) and linear layers on MFMA, with fused epilogues
 //   k_attn_mfma    fused attention (online softmax, K and V^T tiles in LDS, MFMA for QK^T and PV)
 //   k_attn_simple  generic attention, one wavefront per query (fp32 mode, odd head sizes)
+//   k_attn_frames  attention over the frame axis of a video model (one wavefront per position and head)
 //   k_gn_*         GroupNorm (+SiLU) in two passes: per-group partial sums, then statistics + apply
 //   k_layernorm    one wavefront per token
 //   k_linear_rows  skinny linear layer for the time-embedding path
@@ -1357,6 +1358,104 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
   return AD_OK;
 }
 
+// Attention over the frame axis of a video model: the tokens of one sequence are the `frames` rows (f, p),
+// f = 0..frames-1, of one spatial position p; row (f, p) of q / k / v / out is f * positions + p.  One wavefront
+// per (position, head): q, k and v of its `frames` x d slice are staged in LDS with coalesced reads (row stride
+// padded to an odd number of 32-bit words), lane 4 f + part owns the channels t = part (mod 4) of frame f,
+// partial scores are folded over the four parts with two lane exchanges, the softmax lives in registers.
+constexpr int kMaxFrames = 16;
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_attn_frames(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                                                     T* __restrict__ O, int frames, int positions, int heads, int d, int ds,
+                                                     int ldq, int ldk, int ldv, int ldo, float scale) {
+  extern __shared__ __align__(16) char frames_lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+  const long long item = (long long)blockIdx.x * waves + wave;
+  const bool active = item < (long long)positions * heads;
+  const int p = active ? (int)(item / heads) : 0, h = active ? (int)(item % heads) : 0;
+  T* qs = (T*)frames_lds + (size_t)wave * 3 * kMaxFrames * ds;
+  T* ks = qs + kMaxFrames * ds;
+  T* vs = ks + kMaxFrames * ds;
+  if (active) {
+    for (int idx = lane; idx < frames * d; idx += 64) {
+      const int f = idx / d, t = idx - f * d;
+      const size_t row = (size_t)f * positions + p;
+      qs[f * ds + t] = Q[row * ldq + h * d + t];
+      ks[f * ds + t] = K[row * ldk + h * d + t];
+      vs[f * ds + t] = V[row * ldv + h * d + t];
+    }
+  }
+  __syncthreads();
+  if (!active) return;
+  const int f = lane >> 2, part = lane & 3;
+  const bool mine = f < frames;
+  float sc[kMaxFrames];
+#pragma unroll
+  for (int j = 0; j < kMaxFrames; ++j) sc[j] = 0.f;
+  if (mine)
+    for (int t = part; t < d; t += 4) {
+      const float qv = to_f(qs[f * ds + t]);
+#pragma unroll
+      for (int j = 0; j < kMaxFrames; ++j)
+        if (j < frames) sc[j] += qv * to_f(ks[j * ds + t]);
+    }
+  float m = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < kMaxFrames; ++j) {
+    sc[j] += __shfl_xor(sc[j], 1);
+    sc[j] += __shfl_xor(sc[j], 2);
+    sc[j] *= scale;
+    if (j < frames) m = fmaxf(m, sc[j]);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < kMaxFrames; ++j) {
+    sc[j] = j < frames ? __expf(sc[j] - m) : 0.f;
+    sum += sc[j];
+  }
+  if (!mine) return;
+  const float inv = 1.f / sum;
+  T* orow = O + ((size_t)f * positions + p) * ldo + h * d;
+  for (int t = part; t < d; t += 4) {
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < kMaxFrames; ++j)
+      if (j < frames) acc += sc[j] * to_f(vs[j * ds + t]);
+    orow[t] = from_f<T>(acc * inv);
+  }
+}
+
+ad_status launch_attention_frames(int dtype, const void* q, const void* k, const void* v, int frames, int positions, int c,
+                                  int heads, int ldq, int ldk, int ldv, int ldo, void* out, hipStream_t s) {
+  if (!q || !k || !v || !out) AD_FAIL(AD_ERR_INVALID, "frame attention: null pointer");
+  if (dtype != AD_BF16 && dtype != AD_F32) AD_FAIL(AD_ERR_INVALID, "frame attention: bad dtype");
+  if (frames < 1 || frames > kMaxFrames) AD_FAIL(AD_ERR_INVALID, "frame attention: 1..%d frames", kMaxFrames);
+  if (positions < 1 || heads < 1 || c < 1 || c % heads) AD_FAIL(AD_ERR_INVALID, "frame attention: bad shape");
+  if (ldq < c || ldk < c || ldv < c || ldo < c) AD_FAIL(AD_ERR_INVALID, "frame attention: bad leading dimension");
+  const int d = c / heads;
+  const size_t es = esize(dtype);
+  int ds = d;                                             // LDS row stride: a whole, odd number of 32-bit words
+  while ((ds * es) % 4 || ((ds * es) / 4) % 2 == 0) ++ds;
+  const size_t per_wave = (size_t)3 * kMaxFrames * ds * es;
+  if (per_wave > 65536) AD_FAIL(AD_ERR_INVALID, "frame attention: head width %d too large", d);
+  const int waves = (int)std::min<size_t>(4, 65536 / per_wave);
+  const long long items = (long long)positions * heads;
+  const long long blocks = (items + waves - 1) / waves;
+  if (blocks > 0x7fffffffLL) AD_FAIL(AD_ERR_INVALID, "frame attention: too many positions");
+  const float scale = 1.f / sqrtf((float)d);
+  ProfLaunch pl(dtype == AD_BF16 ? "attn_frames_bf16" : "attn_frames_f32", 4.0 * positions * frames * frames * c,
+                4.0 * es * positions * frames * c, s, positions * frames, frames, c);
+  if (dtype == AD_BF16)
+    hipLaunchKernelGGL(k_attn_frames<bf16>, dim3((unsigned)blocks), dim3(64 * waves), waves * per_wave, s, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (bf16*)out, frames, positions, heads, d, ds, ldq, ldk, ldv, ldo, scale);
+  else
+    hipLaunchKernelGGL(k_attn_frames<float>, dim3((unsigned)blocks), dim3(64 * waves), waves * per_wave, s, (const float*)q, (const float*)k,
+                       (const float*)v, (float*)out, frames, positions, heads, d, ds, ldq, ldk, ldv, ldo, scale);
+  AD_HIP(hipGetLastError());
+  return AD_OK;
+}
+
 // =================================================================================================
 // GroupNorm (+SiLU), NHWC, two launches.  Pass 1: every workgroup reduces a run of pixels of one source to
 // per-channel (sum, sum of squares) with fully coalesced row reads and folds the channels of each group in a
@@ -1765,8 +1864,8 @@ ad_status launch_sinusoid(float tau, StepRef ref, int dim, float* out, hipStream
 
 // im2col of the latent for the first convolution: row (b, y, x), column tap * cl + c, zero padded to kConvInK.
 template <typename T>
-__global__ __launch_bounds__(256) void k_pack_latent(const float* __restrict__ latent, float scale, StepRef ref, int cl, int h,
-                                                     int w, int batch, T* __restrict__ out) {
+__global__ __launch_bounds__(256) void k_pack_latent(const float* __restrict__ latent, size_t sample_stride, float scale, StepRef ref,
+                                                     int cl, int h, int w, int batch, T* __restrict__ out) {
   if (ref.table) scale = ref.table[*ref.counter + ref.offset].in_scale;
   const long long total = (long long)batch * h * w * kConvInK;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
@@ -1778,20 +1877,21 @@ __global__ __launch_bounds__(256) void k_pack_latent(const float* __restrict__ l
     if (kk < 9 * cl) {
       const int tap = kk / cl, c = kk - tap * cl;
       const int iy = y + tap / 3 - 1, ix = x + tap % 3 - 1;
-      if (iy >= 0 && iy < h && ix >= 0 && ix < w) v = latent[((size_t)c * h + iy) * w + ix] * scale;
+      if (iy >= 0 && iy < h && ix >= 0 && ix < w) v = latent[(size_t)(m / (h * w)) * sample_stride + ((size_t)c * h + iy) * w + ix] * scale;
     }
     out[i] = from_f<T>(v);
   }
 }
 
-ad_status launch_pack_latent(int dtype, const float* latent, float scale, StepRef ref, int cl, int h, int w, int batch,
+ad_status launch_pack_latent(int dtype, const float* latent, int per_sample, float scale, StepRef ref, int cl, int h, int w, int batch,
                              void* out, hipStream_t s) {
+  const size_t sample_stride = per_sample ? (size_t)cl * h * w : 0;
   if (!latent || !out || cl < 1 || 9 * cl > kConvInK || h < 1 || w < 1 || batch < 1) AD_FAIL(AD_ERR_INVALID, "pack_latent: bad argument");
   const long long total = (long long)batch * h * w * kConvInK;
   const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
   ProfLaunch pl("pack_latent", 0, (double)total * (dtype == AD_BF16 ? 2 : 4), s);
-  if (dtype == AD_BF16) hipLaunchKernelGGL(k_pack_latent<bf16>, dim3(blocks), dim3(256), 0, s, latent, scale, ref, cl, h, w, batch, (bf16*)out);
-  else hipLaunchKernelGGL(k_pack_latent<float>, dim3(blocks), dim3(256), 0, s, latent, scale, ref, cl, h, w, batch, (float*)out);
+  if (dtype == AD_BF16) hipLaunchKernelGGL(k_pack_latent<bf16>, dim3(blocks), dim3(256), 0, s, latent, sample_stride, scale, ref, cl, h, w, batch, (bf16*)out);
+  else hipLaunchKernelGGL(k_pack_latent<float>, dim3(blocks), dim3(256), 0, s, latent, sample_stride, scale, ref, cl, h, w, batch, (float*)out);
   AD_HIP(hipGetLastError());
   return AD_OK;
 }
@@ -1870,6 +1970,11 @@ ad_status ad_attention_forward(int dtype, const void* q, const void* k, const vo
                                int l, int lk, int c, int head_dim, int ldq, int ldk, int ldv, int ldo, void* out,
                                ad_stream stream) {
   return launch_attention(dtype, q, k, v, v_is_transposed, batch, l, lk, c, head_dim, ldq, ldk, ldv, ldo, out, (hipStream_t)stream);
+}
+
+ad_status ad_attention_frames_forward(int dtype, const void* q, const void* k, const void* v, int frames, int positions, int c,
+                                      int heads, int ldq, int ldk, int ldv, int ldo, void* out, ad_stream stream) {
+  return launch_attention_frames(dtype, q, k, v, frames, positions, c, heads, ldq, ldk, ldv, ldo, out, (hipStream_t)stream);
 }
 
 size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n_out, int c_in_total, int ksize, int out_mode) {

@@ -103,7 +103,8 @@ struct Eval {
   }
   // cross-attention key / value projections of the text embedding for the layer whose weights start at w
   ad_status text_kv(int w, void* kdst, void* vdst) const {
-    const int B = c.cfg.batch, Lk = c.cfg.ctx_len, lkp = round_up(Lk, 64);
+    const int B = c.cfg.frames > 0 ? 1 : c.cfg.batch;        // a video has one text embedding for all frames
+    const int Lk = c.cfg.ctx_len, lkp = round_up(Lk, 64);
     const bool vt = dt == AD_BF16 && c.cfg.head_dim == 64;
     AD_TRY(linear(text, B * Lk, c.cfg.ctx_dim, w + 10, -1, nullptr, kdst));
     if (vt) return linear(text, B * Lk, c.cfg.ctx_dim, w + 11, -1, nullptr, vdst, OUT_TRANSPOSED, B, lkp);
@@ -145,13 +146,28 @@ struct Eval {
       } else {
         AD_TRY(text_kv(w, temp(7), temp(8)));
       }
-      AD_TRY(launch_attention(dt, temp(2), tk, tv, vt, B, L, Lk, Cc, d, Cc, Cc, vt ? lkp : Cc, Cc, temp(5), s));
+      // video: every frame attends to the one text embedding, so the frames' tokens form one long query sequence
+      if (c.cfg.frames > 0) AD_TRY(launch_attention(dt, temp(2), tk, tv, vt, 1, M, Lk, Cc, d, Cc, Cc, vt ? lkp : Cc, Cc, temp(5), s));
+      else AD_TRY(launch_attention(dt, temp(2), tk, tv, vt, B, L, Lk, Cc, d, Cc, Cc, vt ? lkp : Cc, Cc, temp(5), s));
       AD_TRY(linear(temp(5), M, Cc, w + 12, w + 13, h, h));
       AD_TRY(ln(h, M, Cc, w + 14, temp(0)));
       AD_TRY(linear(temp(0), M, Cc, w + 16, w + 17, nullptr, temp(6), OUT_GEGLU));
       AD_TRY(linear(temp(6), M, 4 * Cc, w + 18, w + 19, h, h));
     }
-    return linear(h, M, Cc, w + 0, w + 1, x, tensor_out(ui));
+    void* z = tensor_out(ui);
+    AD_TRY(linear(h, M, Cc, w + 0, w + 1, x, z));
+    if (c.cfg.temporal_heads == 0) return AD_OK;
+    // temporal layer: temp.ln.g temp.ln.b temp.q temp.k temp.v temp.o.w temp.o.b; tokens = the frames of one position
+    w += 2;
+    AD_TRY(ln(z, M, Cc, w + 0, temp(0)));
+    {
+      WView wv{c};
+      ConvArgs a{dt, temp(0), nullptr, Cc, 0, B, L, 1, 0, 1, 1, wv.at(w + 2), 3 * Cc, nullptr, nullptr, 0, nullptr, temp(2), OUT_QKV,
+                 0, temp(9), ws.temp_bytes[9], temp(3), temp(4)};
+      AD_TRY(launch_conv(a, s));
+    }
+    AD_TRY(launch_attention_frames(dt, temp(2), temp(3), temp(4), c.cfg.frames, L, Cc, c.cfg.temporal_heads, Cc, Cc, Cc, Cc, temp(5), s));
+    return linear(temp(5), M, Cc, w + 5, w + 6, z, z);
   }
 };
 
@@ -199,7 +215,7 @@ static ad_status run_component(Ctx& c, int comp, int lane, const void* const* in
       case AD_UNIT_CONV_IN: {
         const void* latent = e.tensor_in(-1);
         if (!latent) AD_FAIL(AD_ERR_STATE, "conv_in: missing latent");
-        AD_TRY(launch_pack_latent(e.dt, (const float*)latent, latent_scale, scale_ref, g.latent_channels, g.height, g.width, g.batch, e.temp(0), s));
+        AD_TRY(launch_pack_latent(e.dt, (const float*)latent, g.frames > 0, latent_scale, scale_ref, g.latent_channels, g.height, g.width, g.batch, e.temp(0), s));
         if (latent_consumed) AD_HIP(hipEventRecord(latent_consumed, s));
         AD_TRY(e.conv(e.temp(0), nullptr, kConvInK, 0, g.height, g.width, 0, 1, 1, u.w_first, u.w_first + 1, nullptr, nullptr, e.tensor_out(ui)));
         break;
@@ -424,9 +440,10 @@ ad_status ad_ddim_update(ad_ctx* ctx, void* x, const void* eps, int step_index, 
   if (step_index < 0 || step_index >= c.T) AD_FAIL(AD_ERR_INVALID, "step %d out of range", step_index);
   double cx, ce, s0, s1;
   sampler_coeffs(c, step_index, &cx, &ce, &s0, &s1);
-  const size_t n = (size_t)c.cfg.latent_channels * c.cfg.height * c.cfg.width;
+  // video: one latent per frame and no guidance, i.e. one long vector with a single row of predictions
+  const size_t n = (size_t)(c.cfg.frames > 0 ? c.cfg.frames : 1) * c.cfg.latent_channels * c.cfg.height * c.cfg.width;
   set_profiler(prof_of(c));
-  ad_status st = launch_sampler((float*)x, (const float*)eps, n, c.cfg.batch, (float)cx, (float)ce, StepRef{}, cfg_scale, (hipStream_t)stream);
+  ad_status st = launch_sampler((float*)x, (const float*)eps, n, c.cfg.frames > 0 ? 1 : c.cfg.batch, (float)cx, (float)ce, StepRef{}, cfg_scale, (hipStream_t)stream);
   set_profiler(nullptr);
   return st;
 }
@@ -518,9 +535,9 @@ static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const
       AD_HIP(hipStreamWaitEvent(ss, c.events[1 + j], 0));
     }
   if (pack_recorded && pack_stream != ss) AD_HIP(hipStreamWaitEvent(ss, c.ev_pack, 0));
-  const size_t n = (size_t)c.cfg.latent_channels * c.cfg.height * c.cfg.width;
+  const size_t n = (size_t)(c.cfg.frames > 0 ? c.cfg.frames : 1) * c.cfg.latent_channels * c.cfg.height * c.cfg.width;
   for (size_t j = 0; j < eps_steps.size(); ++j)
-    AD_TRY(launch_sampler((float*)latent, (const float*)(c.work_dev + c.eps_off[eps_lane[j]]), n, c.cfg.batch, 0.f, 0.f,
+    AD_TRY(launch_sampler((float*)latent, (const float*)(c.work_dev + c.eps_off[eps_lane[j]]), n, c.cfg.frames > 0 ? 1 : c.cfg.batch, 0.f, 0.f,
                           StepRef{table, counter, eps_steps[j] - base}, c.cfg_scale, ss));
   // close the round: streams[0] joins every other stream, then moves the step counter on
   for (int k = 1; k < ns; ++k) {

@@ -29,10 +29,10 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(B.EXPORTS)
 
 
-@pytest.mark.parametrize("name", ["tiny", "sd_512", "sd21_768", "sdxl_1024", "sd21_narrow"])
+@pytest.mark.parametrize("name", ["tiny", "sd_512", "sd21_768", "sdxl_1024", "sd21_narrow", "video_16f", "video_narrow", "video_tiny"])
 def test_units_flops_partition_manifest_match_oracle(name):
     d = CONFIGS[name]
-    dtype = B.AD_F32 if name == "tiny" else B.AD_BF16
+    dtype = B.AD_F32 if name.endswith("tiny") else B.AD_BF16
     ocfg = UNetConfig(**d)
     ounits = build_units(ocfg)
     for n in (1, 2, 3, 4):
@@ -186,3 +186,16 @@ def test_weight_packing_layout():
     pg = B.pack_conv_weight(B.AD_F32, g, geglu=True).view(np.float32).reshape(128, 32)
     assert np.array_equal(pg[0:32], g[0:32]) and np.array_equal(pg[32:64], g[64:96])
     assert np.array_equal(pg[64:96], g[32:64]) and np.array_equal(pg[96:128], g[96:128])
+
+
+def test_video_configuration_shapes_and_checks():
+    d = CONFIGS["video_16f"]
+    m = ad.AsyncDiff(d, 4, 2, 1, B.AD_BF16)
+    nu = len(m.units())
+    assert m.tensor_shape(-1)[0] == (16, 64, 64, 4) and m.tensor_shape(-1)[1] == 16 * 4 * 64 * 64 * 4      # one latent per frame
+    assert m.tensor_shape(nu - 1)[0] == (16, 64, 64, 4)
+    m.close()
+    for bad in (dict(d, batch=2), dict(d, frames=17, batch=17), dict(d, frames=0), dict(d, temporal_heads=7),
+                dict(d, pooled_dim=1280)):
+        with pytest.raises(B.AsyncDiffError):
+            ad.AsyncDiff(bad, 4, 2, 1, B.AD_BF16)

@@ -315,3 +315,22 @@ def test_sampler_update(batch):
         B.check(lib.ad_sampler_update_raw(p(dx), p(de), n, batch, cx, ce, 7.5, stream_ptr()))
         sync()
         assert rel_l2(host(dx), ref) < 1e-6
+
+
+@pytest.mark.parametrize("dtype", [B.AD_F32, B.AD_BF16])
+@pytest.mark.parametrize("frames,positions,c,heads", [(16, 37, 320, 8), (3, 64, 64, 4), (16, 5, 1280, 8), (1, 9, 64, 8), (7, 130, 96, 2)])
+def test_attention_over_frames(dtype, frames, positions, c, heads):
+    """Temporal layer kernel: the sequences are the frames of each spatial position (row = frame * positions + p)."""
+    rows = frames * positions
+    ld = c + 8                                               # padded leading dimension
+    q, k, v = (quantize(SI.make_array((rows, ld), 700 + i), dtype) for i in range(3))
+    out = torch.full((rows, ld), float("nan"), device=DEV, dtype=tdtype(dtype))
+    dq, dk, dv = dev(q, dtype), dev(k, dtype), dev(v, dtype)
+    B.check(B.lib.ad_attention_frames_forward(dtype, p(dq), p(dk), p(dv), frames, positions, c, heads,
+                                              ld, ld, ld, ld, p(out), stream_ptr()))
+    torch.cuda.synchronize()
+    seq = lambda a: a[:, :c].reshape(frames, positions, c).transpose(1, 0, 2)        # [positions][frames][c]
+    ref = P.attention(seq(q), seq(k), seq(v), heads).transpose(1, 0, 2).reshape(rows, c)
+    got = host(out)
+    assert np.isnan(got[:, c:]).all()                        # nothing written past the row
+    assert rel_l2(got[:, :c], ref) < TOL[dtype]

@@ -22,8 +22,11 @@ class Case:
         self.d, self.dtype, self.N, self.S, self.T = d, dtype, N, S, T
         ocfg = UNetConfig(**d)
         self.wts = SI.make_weights(weight_manifest(ocfg), std=std, bf16_exact=(dtype == B.AD_BF16))
-        self.noise = SI.make_latent(d["latent_channels"], d["height"], d["width"])
-        self.text = quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), dtype)
+        frames = d.get("frames", 0)
+        # video model: one latent per frame, one text embedding for all frames
+        self.noise = (SI.make_video_latent(frames, d["latent_channels"], d["height"], d["width"]) if frames
+                      else SI.make_latent(d["latent_channels"], d["height"], d["width"]))
+        self.text = quantize(SI.make_text(1 if frames else d["batch"], d["ctx_len"], d["ctx_dim"]), dtype)
         self.pooled = SI.make_pooled(d["batch"], d["pooled_dim"]) if d["pooled_dim"] else None
         self.oracle = Pipeline(ocfg, self.wts, N=N, w=w, S=S, T=T, sampler=sampler, cfg_scale=cfg_scale, time_shift=time_shift, cuts=cuts, wrap=wrap)
         self.m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts, wrap=wrap)
@@ -469,3 +472,36 @@ def test_wrapped_narrow_sdxl_bf16():
     assert rounds == T
     assert rel_l2(got, xs[-1]) < 5e-2
     print(f"wrapped sdxl_narrow bf16: worst per-evaluation rel L2 {worst:.2e}, final latent {rel_l2(got, xs[-1]):.2e}")
+
+
+# ---- video model: frames as the batch axis, temporal attention after every spatial transformer ----------------
+
+def test_video_tiny_fp32_components_and_trajectory():
+    r = RUNS["video_tiny"]
+    case = Case("video_tiny", B.AD_F32, r["N"], r["w"], r["S"], r["T"], std=0.1)
+    worst, latent = run_components_along_schedule(case)
+    xs = case.oracle.run(case.noise, case.text)
+    assert host(latent).shape == xs[-1].shape == (3, 4, 8, 8)
+    assert rel_l2(host(latent), xs[-1]) < 1e-4
+    # the round driver: three components on three streams, with and without graph replay
+    for graphs in (0, 1):
+        c2 = Case("video_tiny", B.AD_F32, 3, 1, 1, 8, std=0.1)
+        c2.m.set_graph_mode(graphs)
+        got, _ = run_steps(c2, 3)
+        assert rel_l2(got, c2.oracle.run(c2.noise, c2.text)[-1]) < 1e-4
+    print(f"video tiny fp32: worst per-component rel L2 {worst:.2e}")
+
+
+def test_video_narrow_bf16_components_and_trajectory():
+    """Reduced-width clone of the video configuration (16 frames, 8 temporal heads, N=4, 2 warm-up steps, DDIM)."""
+    r = RUNS["video_narrow"]
+    T = 5
+    case = Case("video_narrow", B.AD_BF16, r["N"], r["w"], r["S"], T)
+    worst = run_components_isolated(case)
+    assert worst < 2e-2
+    got, rounds = run_steps(case, r["N"])
+    xs = case.oracle.run(case.noise, case.text)
+    assert rounds == T
+    err = rel_l2(got, xs[-1])
+    assert err < 5e-2, f"final latent rel L2 {err:.3e}"
+    print(f"video narrow bf16: worst per-component rel L2 {worst:.2e}, final latent {err:.2e}")
