@@ -101,8 +101,10 @@ def main():
     del wts
     log(f"model ready in {time.time() - t0:.1f}s; arenas {[round(b / 2**20) for b in m.device_bytes()]} MiB")
     tdt = torch.bfloat16 if dtype == ad.AD_BF16 else torch.float32
-    text = torch.from_numpy(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"])).to(dev).to(tdt)
-    noise = torch.from_numpy(SI.make_latent(d["latent_channels"], d["height"], d["width"])).to(dev)
+    frames = d.get("frames", 0)     # video model: one latent per frame, one text embedding for all frames, no guidance
+    text = torch.from_numpy(SI.make_text(1 if frames else d["batch"], d["ctx_len"], d["ctx_dim"])).to(dev).to(tdt)
+    noise = torch.from_numpy(SI.make_video_latent(frames, d["latent_channels"], d["height"], d["width"]) if frames
+                             else SI.make_latent(d["latent_channels"], d["height"], d["width"])).to(dev)
     global POOLED
     POOLED = torch.from_numpy(SI.make_pooled(d["batch"], d["pooled_dim"])).to(dev) if d.get("pooled_dim") else None
     units = m.units()
@@ -222,9 +224,12 @@ def main():
         names = {nm for nm, _ in weight_manifest(ocfg) if nm.startswith(("time.", "pool.", "conv_in.", ounits[1].name, ounits[last].name))}
         sub = [(nm, sh) for nm, sh in weight_manifest(ocfg) if nm in names]
         ow = {k: v.astype(np.float64) for k, v in SI.make_weights(sub).items()}
-        x = SI.make_latent(d["latent_channels"], d["height"], d["width"]).astype(np.float64)
-        xin = np.broadcast_to(x, (d["batch"],) + x.shape).copy()
-        ctx = SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]).astype(np.float64)
+        if frames:
+            xin = SI.make_video_latent(frames, d["latent_channels"], d["height"], d["width"]).astype(np.float64)
+        else:
+            x = SI.make_latent(d["latent_channels"], d["height"], d["width"]).astype(np.float64)
+            xin = np.broadcast_to(x, (d["batch"],) + x.shape).copy()
+        ctx = SI.make_text(1 if frames else d["batch"], d["ctx_len"], d["ctx_dim"]).astype(np.float64)
         pooled = SI.make_pooled(d["batch"], d["pooled_dim"]) if d["pooled_dim"] else None
         tc = time.perf_counter()
         run_units(ocfg, ounits, 0, last, ow, {-1: xin}, 500, ctx, pooled)
@@ -245,7 +250,7 @@ def main():
         "value": round(steps_per_s, 3), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtype == ad.AD_BF16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.config}: latent {d['latent_channels']}x{d['height']}x{d['width']}, batch {d['batch']} (guidance), "
+        "config": {"workload": f"{args.config}: latent {d['latent_channels']}x{d['height']}x{d['width']}, batch {d['batch']} ({'frames' if frames else 'guidance'}), "
                                f"N={N} components on {n_streams} HIP streams, warm-up {w}, stride {S}, {r['sampler']}",
                    "n_components": N, "stride": S, "streams": n_streams, "hip_graphs": bool(args.graphs), "partition": ("wrapped, " if args.wrap else "") + (("flops" if args.wrap else args.cuts) if args.cuts in ("auto", "flops") else "given"),
                    "component_first_units": [a for a, _ in m.partition()], "flops_per_step": flops_step},

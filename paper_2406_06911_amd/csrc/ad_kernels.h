@@ -36,7 +36,7 @@ struct ConvArgs {
   int ksize, stride;
   const void* w;                        // packed [n_pad][k_pad]
   int n_out;                            // GEMM N (for GEGLU: the 2x-wide packed projection)
-  const float* bias; const float* rowvec; int rowvec_ld;   // rowvec [batch][rowvec_ld]
+  const float* bias; const float* rowvec; int rowvec_ld;   // rowvec [batch][rowvec_ld]; 0: ld = n_out, < 0: one row for every sample
   const void* residual;
   void* out; int out_mode; int ld_t;
   void* splitk_ws = nullptr;            // fp32 scratch for split-K partial sums (optional)

@@ -4,7 +4,8 @@
 //                  optional channel concatenation) and linear layers on MFMA, with fused epilogues
 //   k_attn_mfma    fused attention (online softmax, K and V^T tiles in LDS, MFMA for QK^T and PV)
 //   k_attn_simple  generic attention, one wavefront per query (fp32 mode, odd head sizes)
-//   k_attn_frames  attention over the frame axis of a video model (one wavefront per position and head)
+//   k_attn_frames_mfma / k_attn_frames  attention over the frame axis of a video model (one wavefront per
+//                  position and head; MFMA without LDS for bf16, LDS-staged generic kernel otherwise)
 //   k_gn_*         GroupNorm (+SiLU) in two passes: per-group partial sums, then statistics + apply
 //   k_layernorm    one wavefront per token
 //   k_linear_rows  skinny linear layer for the time-embedding path
@@ -996,7 +997,7 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   p.Kp = a.ksize * a.ksize * p.ctot;      // a multiple of the k-tile because ctot is
   p.ktiles = p.Kp / bk;
   p.w = a.w; p.bias = a.bias; p.rowvec = a.rowvec; p.residual = a.residual;
-  p.out = a.out; p.out_mode = a.out_mode; p.ld_t = a.ld_t; p.rowvec_ld = a.rowvec_ld > 0 ? a.rowvec_ld : a.n_out;
+  p.out = a.out; p.out_mode = a.out_mode; p.ld_t = a.ld_t; p.rowvec_ld = a.rowvec_ld > 0 ? a.rowvec_ld : (a.rowvec_ld < 0 ? 0 : a.n_out);
   p.out2 = a.out2; p.out3 = a.out3;
   if (a.out_mode < OUT_ROWMAJOR || a.out_mode > OUT_QKV) AD_FAIL(AD_ERR_INVALID, "conv: bad out_mode");
   if (a.out_mode == OUT_QKV && (a.n_out % 3 || !a.out2 || !a.out3 || a.residual || a.rowvec || (a.ld_t > 0 && a.ld_t < p.hw_out)))
@@ -1074,7 +1075,7 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   if (st != AD_OK || splits <= 1) return st;
   const long long quads = m * (a.n_out / 4);
   const int blocks = (int)((quads + 255) / 256 < 2048 ? (quads + 255) / 256 : 2048);
-  const int rowvec_ld = a.rowvec_ld > 0 ? a.rowvec_ld : a.n_out;
+  const int rowvec_ld = a.rowvec_ld > 0 ? a.rowvec_ld : (a.rowvec_ld < 0 ? 0 : a.n_out);
   ProfLaunch pl("splitk_reduce", 0, (double)splits * m * a.n_out * 4 + (double)m * a.n_out * esize(a.dtype), s);
   if (a.dtype == AD_BF16)
     hipLaunchKernelGGL(k_splitk_reduce<bf16>, dim3(blocks), dim3(256), 0, s, p.partial, splits, p.M, p.N, p.hw_out, a.bias, a.rowvec,
@@ -1426,6 +1427,82 @@ __global__ __launch_bounds__(256) void k_attn_frames(const T* __restrict__ Q, co
   }
 }
 
+// The same for bf16 on the matrix cores, without LDS: one wavefront per (position, head).  Scores are computed
+// transposed, S^T = K Q^T, with 16x16x32 MFMAs whose operands are 16-byte row segments straight from global
+// memory (lane = frame + 16 * segment); lane (f, g) then holds S^T[4g..4g+3][f], which is exactly the A-operand
+// layout of the 16x16x16 MFMA that multiplies the probabilities with V (B operand: four 2-byte loads per lane and
+// 16-channel step).  Frames beyond `frames` are zero rows with -inf scores.  Needs d % 8 == 0, 16-byte aligned rows.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void k_attn_frames_mfma(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+                                                          const bf16* __restrict__ V, bf16* __restrict__ O, int frames,
+                                                          int positions, int heads, int d, int ldq, int ldk, int ldv, int ldo,
+                                                          float scale_log2e) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long item = (long long)blockIdx.x * 4 + wave;
+  if (item >= (long long)positions * heads) return;          // the kernel has no barrier: a wavefront may leave
+  const int p = (int)(item / heads), h = (int)(item % heads);
+  const int r = lane & 15, g = lane >> 4;
+  const bool row_ok = r < frames;
+  const size_t row = (size_t)(row_ok ? r : 0) * positions + p;
+  const bf16* qrow = Q + row * ldq + h * d;
+  const bf16* krow = K + row * ldk + h * d;
+  f32x4 st = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < d; k0 += 32) {
+    const int kk = k0 + 8 * g;
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (bf16)0.f; b[e] = (bf16)0.f; }
+    if (row_ok && kk < d) {
+      a = *(const bf16x8*)(krow + kk);
+      b = *(const bf16x8*)(qrow + kk);
+    }
+    st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, st, 0, 0, 0);
+  }
+  // st[i] = q_f . k_j for key j = 4g + i and query f = r
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    st[i] = (4 * g + i) < frames ? st[i] * scale_log2e : -INFINITY;
+    m = fmaxf(m, st[i]);
+  }
+  m = fmaxf(m, __shfl_xor(m, 16));
+  m = fmaxf(m, __shfl_xor(m, 32));
+  float sum = 0.f;
+  bf16x4 pb;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float e = exp2f(st[i] - m);
+    sum += e;
+    pb[i] = (bf16)e;
+  }
+  sum += __shfl_xor(sum, 16);
+  sum += __shfl_xor(sum, 32);
+  const float inv = 1.f / sum;                                // of query r; the output rows of this lane are 4g..4g+3
+  float inv_f[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) inv_f[i] = __shfl(inv, 4 * g + i);
+  const s16x4 pa = __builtin_bit_cast(s16x4, pb);
+  for (int t0 = 0; t0 < d; t0 += 16) {
+    const int t = t0 + r;
+    bf16x4 vb;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = 4 * g + i;
+      vb[i] = (t < d && j < frames) ? V[((size_t)j * positions + p) * ldv + h * d + t] : (bf16)0.f;
+    }
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(s16x4, vb), o, 0, 0, 0);
+    if (t < d) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int f = 4 * g + i;
+        if (f < frames) O[((size_t)f * positions + p) * ldo + h * d + t] = (bf16)(o[i] * inv_f[i]);
+      }
+    }
+  }
+}
+
 ad_status launch_attention_frames(int dtype, const void* q, const void* k, const void* v, int frames, int positions, int c,
                                   int heads, int ldq, int ldk, int ldv, int ldo, void* out, hipStream_t s) {
   if (!q || !k || !v || !out) AD_FAIL(AD_ERR_INVALID, "frame attention: null pointer");
@@ -1435,16 +1512,25 @@ ad_status launch_attention_frames(int dtype, const void* q, const void* k, const
   if (ldq < c || ldk < c || ldv < c || ldo < c) AD_FAIL(AD_ERR_INVALID, "frame attention: bad leading dimension");
   const int d = c / heads;
   const size_t es = esize(dtype);
+  const long long items = (long long)positions * heads;
+  if ((items + 3) / 4 > 0x7fffffffLL) AD_FAIL(AD_ERR_INVALID, "frame attention: too many positions");
+  const float scale = 1.f / sqrtf((float)d);
+  const bool aligned16 = (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) == 0;
+  if (dtype == AD_BF16 && d % 8 == 0 && (ldq | ldk | ldv | ldo) % 8 == 0 && aligned16) {
+    ProfLaunch pl("attn_frames_bf16", 4.0 * positions * frames * frames * c, 4.0 * es * positions * frames * c, s,
+                  positions * frames, frames, c);
+    hipLaunchKernelGGL(k_attn_frames_mfma, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
+                       (const bf16*)v, (bf16*)out, frames, positions, heads, d, ldq, ldk, ldv, ldo, scale * 1.44269504088896341f);
+    AD_HIP(hipGetLastError());
+    return AD_OK;
+  }
   int ds = d;                                             // LDS row stride: a whole, odd number of 32-bit words
   while ((ds * es) % 4 || ((ds * es) / 4) % 2 == 0) ++ds;
   const size_t per_wave = (size_t)3 * kMaxFrames * ds * es;
   if (per_wave > 65536) AD_FAIL(AD_ERR_INVALID, "frame attention: head width %d too large", d);
   const int waves = (int)std::min<size_t>(4, 65536 / per_wave);
-  const long long items = (long long)positions * heads;
   const long long blocks = (items + waves - 1) / waves;
-  if (blocks > 0x7fffffffLL) AD_FAIL(AD_ERR_INVALID, "frame attention: too many positions");
-  const float scale = 1.f / sqrtf((float)d);
-  ProfLaunch pl(dtype == AD_BF16 ? "attn_frames_bf16" : "attn_frames_f32", 4.0 * positions * frames * frames * c,
+  ProfLaunch pl(dtype == AD_BF16 ? "attn_frames_generic_bf16" : "attn_frames_f32", 4.0 * positions * frames * frames * c,
                 4.0 * es * positions * frames * c, s, positions * frames, frames, c);
   if (dtype == AD_BF16)
     hipLaunchKernelGGL(k_attn_frames<bf16>, dim3((unsigned)blocks), dim3(64 * waves), waves * per_wave, s, (const bf16*)q, (const bf16*)k,

@@ -175,7 +175,9 @@ struct Eval {
 // component in one launch: proj[b][row] = temb_b[row] + sum_k SiLU(temb[b][k]) W[row][k].
 static ad_status time_projection(Eval& e, int tau, StepRef tau_ref, const void* pooled) {
   Ctx& c = e.c;
-  const int B = c.cfg.batch, td = c.temb_dim, c0 = c.cfg.channels[0], dt = e.dt;
+  // without the pooled branch every batch row has the same embedding: one row is computed and shared
+  const int B = c.cfg.pooled_dim > 0 ? c.cfg.batch : 1;
+  const int td = c.temb_dim, c0 = c.cfg.channels[0], dt = e.dt;
   float* sinus = e.f32area();
   float* t1 = sinus + c0;
   float* temb = t1 + (size_t)B * td;
@@ -192,7 +194,7 @@ static ad_status time_projection(Eval& e, int tau, StepRef tau_ref, const void* 
     AD_TRY(launch_linear_rows(dt, pool1, td, B, td, wv.at(6), wv.f32(7), td, 0, 0, 1, temb, e.s));
   }
   e.proj = proj;
-  e.proj_ld = e.cp.temb_rows;
+  e.proj_ld = c.cfg.pooled_dim > 0 ? e.cp.temb_rows : -1;
   if (e.cp.temb_rows > 0) {
     const char* wmat = c.weights_dev + c.temb_w_off + (size_t)e.cp.temb_row0 * td * esize(dt);
     const float* bvec = (const float*)(c.weights_dev + c.temb_b_off) + e.cp.temb_row0;

@@ -20,9 +20,10 @@ def measure_unit_times(cfg_dict, dtype, weights, device="cuda:0", reps=5):
     m.load_weights(weights)
     m.reset(50)
     tdt = torch.bfloat16 if dtype == AD_BF16 else torch.float32
-    text = torch.randn(cfg_dict["batch"], cfg_dict["ctx_len"], cfg_dict["ctx_dim"], device=device).to(tdt)
+    frames = cfg_dict.get("frames", 0)           # video model: one latent per frame, one text embedding for all frames
+    text = torch.randn(1 if frames else cfg_dict["batch"], cfg_dict["ctx_len"], cfg_dict["ctx_dim"], device=device).to(tdt)
     pooled = torch.randn(cfg_dict["batch"], cfg_dict["pooled_dim"], device=device) if cfg_dict.get("pooled_dim") else None
-    latent = torch.randn(1, cfg_dict["latent_channels"], cfg_dict["height"], cfg_dict["width"], device=device)
+    latent = torch.randn(max(1, frames), cfg_dict["latent_channels"], cfg_dict["height"], cfg_dict["width"], device=device)
 
     def alloc(u):
         (b, h, w, c), _ = m.tensor_shape(u)

@@ -318,7 +318,8 @@ def test_sampler_update(batch):
 
 
 @pytest.mark.parametrize("dtype", [B.AD_F32, B.AD_BF16])
-@pytest.mark.parametrize("frames,positions,c,heads", [(16, 37, 320, 8), (3, 64, 64, 4), (16, 5, 1280, 8), (1, 9, 64, 8), (7, 130, 96, 2)])
+@pytest.mark.parametrize("frames,positions,c,heads", [(16, 37, 320, 8), (3, 64, 64, 4), (16, 5, 1280, 8), (1, 9, 64, 8), (7, 130, 96, 2), (16, 33, 640, 8),
+                                                      (5, 21, 60, 4), (13, 4097, 64, 1)])
 def test_attention_over_frames(dtype, frames, positions, c, heads):
     """Temporal layer kernel: the sequences are the frames of each spatial position (row = frame * positions + p)."""
     rows = frames * positions
