@@ -505,3 +505,81 @@ def test_video_narrow_bf16_components_and_trajectory():
     err = rel_l2(got, xs[-1])
     assert err < 5e-2, f"final latent rel L2 {err:.3e}"
     print(f"video narrow bf16: worst per-component rel L2 {worst:.2e}, final latent {err:.2e}")
+
+
+def test_video_full_size_first_units_and_properties():
+    """The video configuration at its real shape (16 frames of 64x64 latents).  Against the oracle on the same
+    seeded inputs: the first convolution, the first ResBlock and the temporal layer over all 65536 tokens (the
+    spatial transformer in front of it is switched off by a zero output projection, so that the oracle does not
+    have to evaluate sixteen 4096-token self-attentions in fp64; that part runs at full size in the test of the
+    768px model).  Then the launch configuration the benchmark uses (four streams, graph replay), with the real
+    weights, against direct launches on one stream, bit for bit."""
+    from oracle.unet import _temporal, build_units, run_units
+    d = CONFIGS["video_16f"]
+    ocfg = UNetConfig(**d)
+    units = build_units(ocfg)
+    last = 2
+    assert units[last].kind == "tfm"
+    print("drawing weights", flush=True)
+    wts = SI.make_weights(weight_manifest(ocfg), bf16_exact=True)
+    off = dict(wts)
+    tname = units[last].name
+    off[tname + ".proj_out.w"] = np.zeros_like(wts[tname + ".proj_out.w"])
+    off[tname + ".proj_out.b"] = np.zeros_like(wts[tname + ".proj_out.b"])
+    prefixes = tuple(units[i].name + "." for i in range(last + 1)) + ("time.",)
+    sub = {k: np.asarray(v, np.float64) for k, v in off.items() if k.startswith(prefixes)}
+    noise = SI.make_video_latent(d["frames"], d["latent_channels"], d["height"], d["width"])
+    text = quantize(SI.make_text(1, d["ctx_len"], d["ctx_dim"]), B.AD_BF16)
+    taus = __import__("oracle.sampler", fromlist=["timesteps"]).timesteps(25)
+    print("oracle: first two units", flush=True)
+    ref = run_units(ocfg, units, 0, 1, sub, {-1: noise.astype(np.float64)}, taus[0], text.astype(np.float64), None)
+    # the temporal layer never mixes positions: its reference is evaluated on a sample of them (corners included)
+    print("oracle: temporal layer on sampled positions", flush=True)
+    hw = d["height"] * d["width"]
+    pos = np.unique(np.concatenate([[0, d["width"] - 1, hw - d["width"], hw - 1],
+                                    np.random.default_rng(11).integers(0, hw, 252)]))
+    z = ref[1].reshape(d["frames"], -1, hw)[:, :, pos][..., None]             # [frames, C, n, 1]
+    ref_t = _temporal(ocfg, units[last], sub, z)[..., 0]                        # [frames, C, n]
+    print("gpu", flush=True)
+
+    cuts = [last + 1, 28, 39]
+    d_text = dev(text, B.AD_BF16)
+    m = ad.AsyncDiff(d, 4, 2, 1, B.AD_BF16, cuts=cuts)
+    m.allocate(DEV)
+    m.load_weights(off)
+    m.reset(25)
+    ins, outs = m.component_io(1)
+    assert ins == [-1] and outs == [0, 2]        # the ResBlock's output stays inside; it is checked through the temporal layer
+    hout = []
+    for u in outs:
+        (b, h, w, c), _ = m.tensor_shape(u)
+        hout.append(torch.full((b, h, w, c), float("nan"), device=DEV, dtype=torch.bfloat16))
+    m.component_forward(1, [dev_f32(noise)], 0, d_text, hout, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    err = rel_l2(nhwc_to_nchw(host(hout[0])), ref[0])
+    assert err < 2e-2, f"unit 0: rel L2 {err:.3e}"
+    got_t = nhwc_to_nchw(host(hout[1])).reshape(d["frames"], -1, hw)
+    assert np.isfinite(got_t).all()
+    err = rel_l2(got_t[:, :, pos], ref_t)
+    assert err < 2e-2, f"temporal layer on sampled positions: rel L2 {err:.3e}"
+    del hout
+    m.load_weights(wts)
+
+    def trajectory(streams, graphs, T=5):
+        m.set_graph_mode(graphs)
+        m.reset(T)
+        latent = dev_f32(noise)
+        ss = [torch.cuda.Stream(device=DEV) for _ in range(streams)]
+        torch.cuda.synchronize()
+        snaps = []
+        while m.step(latent, d_text, ss) is not None:
+            torch.cuda.synchronize()
+            snaps.append(latent.cpu().numpy().copy())
+        return snaps
+
+    direct, replay = trajectory(1, False), trajectory(4, True)
+    assert len(direct) == len(replay) == 5
+    for r, (a, b) in enumerate(zip(direct, replay)):
+        assert np.array_equal(a, b), f"round {r}"
+    assert np.isfinite(replay[-1]).all() and replay[-1].shape == (16, 4, 64, 64)
+    m.close()
