@@ -296,6 +296,22 @@ def test_narrow_sd_bf16_components():
     assert err < 5e-2
 
 
+def test_narrow_sd_bf16_two_components_one_warmup_step():
+    """The run parameters of the 512px configuration (N=2, one warm-up step, stride 1, guidance 7.5) on the
+    reduced-width clone: per-component parity, then the trajectory through the round driver with graph replay."""
+    r = RUNS["sd_512"]
+    T = 10
+    case = Case("sd21_narrow", B.AD_BF16, r["N"], r["w"], r["S"], T, cfg_scale=r["cfg_scale"])
+    worst = run_components_isolated(case)
+    xs = case.oracle.run(case.noise, case.text)
+    case.m.set_graph_mode(True)
+    case.m.reset(T, cfg_scale=r["cfg_scale"])
+    latent, rounds = run_steps(case, r["N"])
+    err = rel_l2(latent, xs[-1])
+    print(f"narrow bf16 N=2 w=1: worst per-component rel L2 {worst:.2e}, latent after {T} steps {err:.2e}")
+    assert rounds == T and err < 5e-2
+
+
 def test_narrow_sd_bf16_full_trajectory():
     """All 50 steps of the reduced-width clone (N=4, w=3, guidance 7.5): final latent within 5e-2."""
     r = RUNS["sd21_narrow"]
