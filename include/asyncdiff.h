@@ -190,7 +190,7 @@ ad_status ad_get_sampler_coeffs(const ad_ctx* ctx, int step, double* c_x, double
  *   lane        which private activation workspace to use: 0, or 0..stride-1 for the last component
  *               (two evaluations that run concurrently must use different lanes);
  *   hidden_in   HOST array of DEVICE pointers, one per input of ad_component_io() in its order
- *               (for component 1 the single entry is the fp32 latent);
+ *               (for component 1 the single entry is the fp32 latent, [frames][C][H][W] for the video model);
  *   t_index     step index i whose timestep tau_i feeds the time embedding (0..T-1);
  *   latent_scale  factor applied to the latent on entry (component 1 only; ad_get_sampler_coeffs);
  *   text_emb, pooled_emb  DEVICE (pooled_emb may be NULL when cfg.pooled_dim == 0);
@@ -212,7 +212,7 @@ ad_status ad_precompute_text(ad_ctx* ctx, const void* text_emb, ad_stream stream
  * trailing partial round): evaluates the round's components concurrently on the given streams
  * (evaluation e runs on streams[e % n_streams]; n_streams = 1 gives the serial order), stores their
  * outputs in the slot the table names, then applies the sampler once per completed step.
- *   latent      DEVICE fp32, updated in place;
+ *   latent      DEVICE fp32 [C][H][W] ([frames][C][H][W] for the video model), updated in place;
  *   streams     HOST array of hipStream_t;
  *   steps_done  HOST out: total steps completed after this call.
  * On return all work is enqueued; the last used event is waited on by streams[0], so synchronising
@@ -230,7 +230,8 @@ ad_status ad_set_graph_mode(ad_ctx* ctx, int on);
 
 /* Sampler update of step `step_index` (Section 3.1, Eq. 3, read as deterministic DDIM; or Euler),
  * fused with the guidance combination eps = eps_u + g (eps_c - eps_u) (batch row 0 = conditional):
- *   x  DEVICE fp32 [C][H][W] in place;  eps  DEVICE fp32 [batch][C][H][W]. */
+ *   x  DEVICE fp32 [C][H][W] in place;  eps  DEVICE fp32 [batch][C][H][W].
+ * Video model: x and eps are both [frames][C][H][W] and cfg_scale is ignored (no guidance pair). */
 ad_status ad_ddim_update(ad_ctx* ctx, void* x, const void* eps, int step_index, float cfg_scale, ad_stream stream);
 /* The same kernel on an arbitrary element count (used to measure it at a bandwidth-bound size):
  *   x DEVICE fp32 [n] in place; eps DEVICE fp32 [batch][n]; x' = c_x * x + c_eps * guided eps. */
