@@ -599,3 +599,25 @@ def test_video_full_size_first_units_and_properties():
         assert np.array_equal(a, b), f"round {r}"
     assert np.isfinite(replay[-1]).all() and replay[-1].shape == (16, 4, 64, 64)
     m.close()
+
+
+@pytest.mark.parametrize("N,w,S,sampler,wrap,shift", [(2, 1, 2, "euler", False, False), (3, 2, 1, "ddim", True, False),
+                                                      (3, 1, 3, "ddim", False, True)])
+def test_video_tiny_schedule_variants(N, w, S, sampler, wrap, shift):
+    """The video model under stride denoising, the Euler sampler, time shifting and the wrapped segmentation:
+    the latent of every completed step against the oracle."""
+    T = 9
+    case = Case("video_tiny", B.AD_F32, N, w, S, T, sampler=sampler, std=0.1, wrap=wrap, time_shift=shift)
+    xs = case.oracle.run(case.noise, case.text)
+    latent = case.init_latent()
+    ss = [torch.cuda.Stream(device=DEV) for _ in range(N + S - 1)]
+    torch.cuda.synchronize()
+    done = 0
+    while True:
+        r = case.m.step(latent, case.d_text, ss)
+        if r is None:
+            break
+        done = r
+        torch.cuda.synchronize()
+        assert rel_l2(host(latent), xs[done]) < 1e-4, f"after step {done}"
+    assert done == T
