@@ -478,7 +478,7 @@ ad_status ad_get_eps_buffer(const ad_ctx* ctx, int j, void** ptr, size_t* bytes)
 // Every per-step scalar is looked up on the device (table[counter + offset]) so that the launch arguments of
 // an asynchronous round depend only on its slot parity: such a round can be captured once and replayed.
 static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const void* text_emb, const void* pooled_emb,
-                               const ad_stream* streams, int ns, bool capturing, std::vector<int>* steps_out) {
+                               const ad_stream* streams, int ns, std::vector<int>* steps_out) {
   const bool warm = c.rows[r0].read_slot == c.rows[r0].write_slot;
   const int nu = (int)c.units.size();
   const int max_par = c.devices + c.stride - 1;
@@ -547,7 +547,6 @@ static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const
     AD_HIP(hipStreamWaitEvent(s0, c.events[max_par + k], 0));
   }
   AD_TRY(launch_advance(counter, (int)eps_steps.size(), s0));
-  (void)capturing;
   if (steps_out) *steps_out = eps_steps;
   return AD_OK;
 }
@@ -633,7 +632,7 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
       if (g.exec) AD_HIP(hipStreamSynchronize(s0));   // a replay of the old graph may still be running
       drop_graph(g);
       AD_HIP(hipStreamBeginCapture(s0, hipStreamCaptureModeRelaxed));
-      st = enqueue_round(c, r0, r1, latent, text_emb, pooled_emb, streams, ns, true, &done);
+      st = enqueue_round(c, r0, r1, latent, text_emb, pooled_emb, streams, ns, &done);
       hipGraph_t graph = nullptr;
       const hipError_t e = hipStreamEndCapture(s0, &graph);
       if (st != AD_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
@@ -649,7 +648,7 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
     AD_HIP(hipGraphLaunch(g.exec, s0));
   } else {
     set_profiler(prof);
-    st = enqueue_round(c, r0, r1, latent, text_emb, pooled_emb, streams, ns, false, &done);
+    st = enqueue_round(c, r0, r1, latent, text_emb, pooled_emb, streams, ns, &done);
     set_profiler(nullptr);
     if (st != AD_OK) return st;
   }
