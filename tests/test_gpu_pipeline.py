@@ -621,3 +621,32 @@ def test_video_tiny_schedule_variants(N, w, S, sampler, wrap, shift):
         torch.cuda.synchronize()
         assert rel_l2(host(latent), xs[done]) < 1e-4, f"after step {done}"
     assert done == T
+
+
+def test_full_size_whole_unet_matches_oracle(full_size_weights):
+    """The complete noise prediction of the 768px model (all 46 units as one component, 4.3 TFLOP in fp64 on the
+    oracle side: about a minute of CPU time) against the GPU's first denoising step, element by element."""
+    from oracle.unet import unet_forward
+    d = CONFIGS["sd21_768"]
+    ocfg = UNetConfig(**d)
+    noise = SI.make_latent(d["latent_channels"], d["height"], d["width"])
+    text = quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), B.AD_BF16)
+    taus = __import__("oracle.sampler", fromlist=["timesteps"]).timesteps(50)
+    m = ad.AsyncDiff(d, 1, 0, 1, B.AD_BF16)
+    m.allocate(DEV)
+    m.load_weights(full_size_weights)
+    m.reset(50)
+    nu = len(m.units())
+    (b, h, w, c), _ = m.tensor_shape(nu - 1)
+    eps = torch.full((b, c, h, w), float("nan"), device=DEV, dtype=torch.float32)
+    m.component_forward(1, [dev_f32(noise)], 0, dev(text, B.AD_BF16), [eps], torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = host(eps)
+    m.close()
+    torch.cuda.empty_cache()
+    print("oracle: whole UNet forward", flush=True)
+    x = np.broadcast_to(noise.astype(np.float64), (d["batch"],) + noise.shape).copy()
+    ref = unet_forward(ocfg, full_size_weights, x, taus[0], text.astype(np.float64))
+    err = rel_l2(got, ref)
+    print(f"whole UNet at full size: rel L2 {err:.3e}", flush=True)
+    assert got.shape == ref.shape and err < 2e-2
