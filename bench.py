@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", default="sd21_768")
+    ap.add_argument("--refine", type=int, default=1, help="with --cuts auto: refine the time-balanced split by timing whole rounds of neighbouring splits")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams for the timed region (0 = one per concurrent evaluation)")
     ap.add_argument("--graphs", type=int, default=1, help="1 (default): replay full asynchronous rounds from HIP graphs; 0: launch every kernel directly")
     ap.add_argument("--cuts", default="auto", help="partition of the units into components: 'auto' (default: balanced by unit times measured on this GPU "
@@ -93,6 +94,13 @@ def main():
         from paper_2406_06911_amd.tuning import time_balanced_cuts
         cuts, unit_us = time_balanced_cuts(d, N, dtype, wts, dev) if N > 1 else (None, None)
         log(f"unit times measured in {time.time() - t0:.1f}s; time-balanced cuts {cuts}")
+        if N > 1 and args.refine:
+            # the components share the GPU: neighbouring splits are timed as whole asynchronous rounds
+            from paper_2406_06911_amd.tuning import refine_cuts
+            t1 = time.time()
+            cuts, ms_round, tried = refine_cuts(d, N, w, S, dtype, wts, cuts, dev)
+            log(f"partition refined in {time.time() - t1:.1f}s over {len(tried)} splits: cuts {cuts}, {ms_round:.3f} ms per round")
+            log("  splits tried: " + ", ".join(f"{list(k)}: {v:.3f}" for k, v in tried.items()))
     else:
         cuts = None if args.cuts == "flops" else [int(x) for x in args.cuts.split(",")]
     m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts, wrap=bool(args.wrap))

@@ -2,7 +2,8 @@
 component through ad_component_forward) and split the units into N components of comparable measured time
 with the library's own partition rule (ad_balance_cuts).  Section 3.2 of the paper asks for components of
 comparable load; FLOPs are the default measure (ad_create), measured time is the better one on a device
-whose small layers run far below its peak."""
+whose small layers run far below its peak.  The components of a round share the GPU, so the split that balances
+the units' times in isolation is refined by timing whole asynchronous rounds for neighbouring splits."""
 import time
 
 import torch
@@ -54,3 +55,69 @@ def time_balanced_cuts(cfg_dict, n_components, dtype, weights, device="cuda:0"):
     """Cuts for AsyncDiff(..., cuts=...) that balance the measured unit times; also returns the times."""
     times = measure_unit_times(cfg_dict, dtype, weights, device)
     return balance_cuts(times, n_components), times
+
+
+def time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", rounds=12, settle=2):
+    """Milliseconds per asynchronous round (graph replay, one stream per concurrent evaluation) for a given split."""
+    m = AsyncDiff(cfg_dict, n_components, warmup, stride, dtype, cuts=cuts)
+    m.allocate(device)
+    m.load_weights(weights)
+    m.set_graph_mode(True)
+    m.reset(warmup + (settle + rounds + 2) * stride)
+    tdt = torch.bfloat16 if dtype == AD_BF16 else torch.float32
+    frames = cfg_dict.get("frames", 0)
+    text = torch.randn(1 if frames else cfg_dict["batch"], cfg_dict["ctx_len"], cfg_dict["ctx_dim"], device=device).to(tdt)
+    pooled = torch.randn(cfg_dict["batch"], cfg_dict["pooled_dim"], device=device) if cfg_dict.get("pooled_dim") else None
+    latent = torch.randn(max(1, frames), cfg_dict["latent_channels"], cfg_dict["height"], cfg_dict["width"], device=device)
+    if not frames:
+        latent = latent[0].contiguous()
+    streams = [torch.cuda.Stream(device=device) for _ in range(n_components + stride - 1)]
+    torch.cuda.synchronize()
+    for _ in range(warmup + settle):
+        m.step(latent, text, streams, pooled=pooled)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(rounds):
+        m.step(latent, text, streams, pooled=pooled)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / rounds * 1e3
+    m.close()
+    del m
+    torch.cuda.empty_cache()
+    return ms
+
+
+def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", max_evals=40, gain=0.002):
+    """Steepest descent around `cuts`: every split with one cut moved by one or two units is timed, the best one is
+    taken while the measured round time drops by more than `gain` (relative) and fewer than `max_evals` splits
+    have been timed.  Returns (cuts, ms per round, {cuts tuple: ms})."""
+    probe = AsyncDiff(cfg_dict, 1, 0, 1, dtype)
+    nu = len(probe.units())
+    probe.close()
+    seen = {}
+
+    def measure(c):
+        key = tuple(c)
+        if key not in seen:
+            seen[key] = time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, list(c), device)
+        return seen[key]
+
+    best = list(cuts)
+    best_ms = measure(best)
+    while len(seen) < max_evals:
+        # steepest descent: time every neighbour of the current split (one cut moved by one or two units)
+        cand_best, cand_ms = None, best_ms
+        for k in range(len(best)):
+            for step in (-1, 1, -2, 2):
+                cand = list(best)
+                cand[k] += step
+                edges = [0] + cand + [nu]
+                if any(a >= b for a, b in zip(edges, edges[1:])) or (tuple(cand) not in seen and len(seen) >= max_evals):
+                    continue
+                ms = measure(cand)
+                if ms < cand_ms:
+                    cand_best, cand_ms = cand, ms
+        if cand_best is None or cand_ms > best_ms * (1.0 - gain):
+            break
+        best, best_ms = cand_best, cand_ms
+    return best, best_ms, seen

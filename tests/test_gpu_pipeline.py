@@ -650,3 +650,21 @@ def test_full_size_whole_unet_matches_oracle(full_size_weights):
     err = rel_l2(got, ref)
     print(f"whole UNet at full size: rel L2 {err:.3e}", flush=True)
     assert got.shape == ref.shape and err < 2e-2
+
+
+def test_partition_tuning_helpers():
+    """Profile-guided partition: measured unit times balanced by the library's rule, then refined by timing whole
+    rounds; the result is a valid split that the library accepts and the oracle reproduces."""
+    from paper_2406_06911_amd.tuning import refine_cuts, time_balanced_cuts
+    d = CONFIGS["sd21_narrow"]
+    wts = SI.make_weights(weight_manifest(UNetConfig(**d)), bf16_exact=True)
+    cuts, times = time_balanced_cuts(d, 3, B.AD_BF16, wts, DEV)
+    nu = len(times)
+    assert len(cuts) == 2 and 0 < cuts[0] < cuts[1] < nu and all(t > 0 for t in times)
+    assert cuts == ad.balance_cuts(times, 3)
+    best, ms, tried = refine_cuts(d, 3, 1, 1, B.AD_BF16, wts, cuts, DEV, max_evals=6)
+    assert tuple(cuts) in tried and tuple(best) in tried and ms == tried[tuple(best)] <= tried[tuple(cuts)]
+    assert 0 < best[0] < best[1] < nu and len(tried) <= 6
+    case = Case("sd21_narrow", B.AD_BF16, 3, 1, 1, 5, cuts=best)
+    got, _ = run_steps(case, 3)
+    assert rel_l2(got, case.oracle.run(case.noise, case.text)[-1]) < 5e-2
