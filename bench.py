@@ -24,10 +24,11 @@ PEAK_HBM_GBS = 8000.0
 # `rocprofv3 --pmc` runs of this file (FETCH_SIZE, WRITE_SIZE; KiB per dispatch scaled by the factors 2.00 and 1.00 that the
 # same counters show for the 2^26-element sampler launch).  Commands and tables: profiles/bench_sd21_768_all_kernels.md.
 MEASURED_TRAFFIC = {"sd21_768": {
-    "attn_mfma_bf16": 22607347, "igemm_bf16_128x128_p3": 135831880, "igemm_bf16_128x128_dma": 56102124,
-    "igemm_bf16_256x128_p3": 76241607, "igemm_bf16_64x64_p3": 25201794, "igemm_bf16_128x128_p3_splitk": 53032738,
-    "igemm_bf16_256x128_p3_splitk": 119036038, "splitk_reduce": 17822420, "gn_apply": 17523399, "gn_partial": 7280059,
-    "layernorm": 13111235, "linear_rows": 5918259, "gn_small": 3070908}}
+    "igemm_bf16_128x128_p3": 92210413, "igemm_bf16_128x128_dma": 56103632, "igemm_bf16_256x128_p3": 76244019,
+    "igemm_bf16_64x64_p3": 25199724, "igemm_bf16_128x128_p3_splitk": 52933017,
+    "igemm_bf16_256x128_p3_splitk": 119020846, "splitk_reduce": 17823279, "attn_mfma_bf16": 22606982,
+    "gn_apply": 17511113, "gn_partial": 7280061, "layernorm": 13111232, "igemm_bf16_64x64_splitk": 31000200,
+    "linear_rows": 5868024, "gn_small": 3070976}}
 
 
 def log(*a):
