@@ -229,8 +229,11 @@ def main():
         from oracle.partition import unit_flops
         ocfg = UNetConfig(**d)
         ounits = build_units(ocfg)
-        last = 2 if len(ounits) > 3 else len(ounits) - 1           # conv_in + first ResBlock + first transformer
-        names = {nm for nm, _ in weight_manifest(ocfg) if nm.startswith(("time.", "pool.", "conv_in.", ounits[1].name, ounits[last].name))}
+        # bounded sample: the first of four FLOP-balanced components (about a quarter of a step, 10-20 s of CPU time)
+        from oracle.partition import component_ranges
+        last = component_ranges(ocfg, 4)[0][1] if len(ounits) > 12 else len(ounits) - 1
+        prefixes = ("time.", "pool.") + tuple(u.name + "." for u in ounits[:last + 1])
+        names = {nm for nm, _ in weight_manifest(ocfg) if nm.startswith(prefixes)}
         sub = [(nm, sh) for nm, sh in weight_manifest(ocfg) if nm in names]
         ow = {k: v.astype(np.float64) for k, v in SI.make_weights(sub).items()}
         if frames:
