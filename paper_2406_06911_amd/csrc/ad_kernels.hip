@@ -1108,6 +1108,9 @@ constexpr int kAttnStage = 2 * 64 * kPitch;   // one K tile and one V^T tile (64
 // three wavefronts per SIMD: the register budget of that occupancy (170) holds the score and output tiles in
 // ordinary VGPRs; left alone the compiler aims for four, spills the MFMA results to accumulation registers
 // and copies them back and forth around every softmax (about a third of the vector instructions of the loop)
+// RAGGED (Lk not a multiple of 64) is a template parameter: left as a run-time flag, the masking of the last key
+// tile is turned into unconditional compares and selects on every tile (65-100 vector instructions per tile).
+template <bool RAGGED>
 __global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                    const bf16* __restrict__ Vt, bf16* __restrict__ O, int L, int Lk,
                                                    int C, int ldq, int ldk, int ldv, int ldo, float scale_log2, int qblocks) {
@@ -1135,7 +1138,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) voi
   float m_run = -INFINITY, l_run = 0.f;
   const int srow = tid >> 3, scol = tid & 7;
   const int ntiles = (Lk + 63) / 64;
-  const bool ragged = (Lk & 63) != 0;
+  constexpr bool ragged = RAGGED;
   // running pointers of this thread's two rows of the K tile (keys) and of the V^T tile (channels)
   const bf16* kp[2];
   const bf16* vp[2];
@@ -1178,10 +1181,16 @@ __global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) voi
         for (int e = 0; e < 8; ++e)
           if (kb + e >= Lk) vr[i][e] = (bf16)0.f;
     }
+    // V^T rows are stored with the keys of every group of 16 in the order 0-3, 8-11, 4-7, 12-15: that is the order
+    // in which the probabilities come out of the score tile (a lane holds keys 4 half + 0..3 and 8 + 4 half + 0..3
+    // of a group), so that the matching V^T fragment is one 16-byte read
+    const int vslot = (scol >> 1) * 32 + (scol & 1) * 8;       // byte offset of keys 8 scol .. +3; keys +4 .. +7 follow 16 bytes on
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       *(bf16x8*)(st + (srow + 32 * i) * kPitch + scol * 16) = kr[i];
-      *(bf16x8*)(st + 64 * kPitch + (srow + 32 * i) * kPitch + scol * 16) = vr[i];
+      char* vrow = st + 64 * kPitch + (srow + 32 * i) * kPitch + vslot;
+      *(bf16x4*)vrow = bf16x4{vr[i][0], vr[i][1], vr[i][2], vr[i][3]};
+      *(bf16x4*)(vrow + 16) = bf16x4{vr[i][4], vr[i][5], vr[i][6], vr[i][7]};
     }
   };
   // one key tile; PAR (the LDS stage) is a compile-time constant so that every LDS address is base + immediate
@@ -1247,11 +1256,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) voi
         for (int e = 0; e < 8; ++e) pb[e] = (bf16)sc[j][8 * s2 + e];
 #pragma unroll
         for (int d = 0; d < 2; ++d) {
-          const char* vrow = Vs + (d * 32 + l32) * kPitch + (j * 32 + 16 * s2 + 4 * half) * 2;
-          const bf16x4 lo = *(const bf16x4*)vrow, hi = *(const bf16x4*)(vrow + 16);
-          bf16x8 a;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { a[e] = lo[e]; a[4 + e] = hi[e]; }
+          const bf16x8 a = *(const bf16x8*)(Vs + (d * 32 + l32) * kPitch + (j * 32 + 16 * s2) * 2 + 16 * half);
           o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[d], 0, 0, 0);
         }
       }
@@ -1344,8 +1349,12 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
     if (ldv < round_up(lk, 64) || (ldq | ldk | ldv | ldo) % 8) AD_FAIL(AD_ERR_INVALID, "attention: MFMA path needs padded, 8-aligned strides");
     ProfLaunch pl("attn_mfma_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s, batch * l, lk, c);
     const int qblocks = (l + 127) / 128;
-    hipLaunchKernelGGL(k_attn_mfma, dim3(qblocks * heads * batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
-                       (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, scale * 1.44269504088896341f, qblocks);
+    if (lk & 63)
+      hipLaunchKernelGGL(k_attn_mfma<true>, dim3(qblocks * heads * batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
+                         (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, scale * 1.44269504088896341f, qblocks);
+    else
+      hipLaunchKernelGGL(k_attn_mfma<false>, dim3(qblocks * heads * batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
+                         (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, scale * 1.44269504088896341f, qblocks);
   } else if (dtype == AD_BF16) {
     ProfLaunch pl("attn_simple_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s);
     hipLaunchKernelGGL(k_attn_simple<bf16>, dim3((l + 3) / 4, heads, batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
