@@ -1105,13 +1105,14 @@ __device__ __forceinline__ float other_half(float x, bool low) {
 
 constexpr int kAttnStage = 2 * 64 * kPitch;   // one K tile and one V^T tile (64 rows of 128 bytes + pad each)
 
-// three wavefronts per SIMD: the register budget of that occupancy (170) holds the score and output tiles in
-// ordinary VGPRs; left alone the compiler aims for four, spills the MFMA results to accumulation registers
-// and copies them back and forth around every softmax (about a third of the vector instructions of the loop)
+// four wavefronts per SIMD: with 32-bit running offsets instead of pointers the score and output tiles, the query
+// fragments and the tile in flight fit the 128 VGPRs of that occupancy without accumulation-register copies
+// (with pointers the compiler moved the MFMA results through accumulation registers around every softmax, about a
+// third of the loop's vector instructions, and three wavefronts per SIMD were the better choice)
 // RAGGED (Lk not a multiple of 64) is a template parameter: left as a run-time flag, the masking of the last key
 // tile is turned into unconditional compares and selects on every tile (65-100 vector instructions per tile).
 template <bool RAGGED>
-__global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+__global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(256) void k_attn_mfma(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                    const bf16* __restrict__ Vt, bf16* __restrict__ O, int L, int Lk,
                                                    int C, int ldq, int ldk, int ldv, int ldo, float scale_log2, int qblocks) {
   __shared__ __attribute__((aligned(16))) char lds[2 * kAttnStage];
@@ -1139,15 +1140,17 @@ __global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) voi
   const int srow = tid >> 3, scol = tid & 7;
   const int ntiles = (Lk + 63) / 64;
   constexpr bool ragged = RAGGED;
-  // running pointers of this thread's two rows of the K tile (keys) and of the V^T tile (channels)
-  const bf16* kp[2];
-  const bf16* vp[2];
+  // running 32-bit element offsets of this thread's two rows of the K tile (keys) and of the V^T tile (channels)
+  // from bases that are uniform over the workgroup (the launcher checks that they fit)
+  const bf16* kbase = K + (size_t)b * Lk * ldk + h * 64;
+  const bf16* vbase = Vt + ((size_t)b * C + h * 64) * ldv;
+  unsigned kp[2], vp[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    kp[i] = K + ((size_t)b * Lk + srow + 32 * i) * ldk + h * 64 + scol * 8;
-    vp[i] = Vt + ((size_t)b * C + h * 64 + srow + 32 * i) * ldv + scol * 8;
+    kp[i] = (unsigned)((srow + 32 * i) * ldk + scol * 8);
+    vp[i] = (unsigned)((srow + 32 * i) * ldv + scol * 8);
   }
-  const size_t kstep = (size_t)64 * ldk;
+  const unsigned kstep = 64u * (unsigned)ldk;
 
   // the next tile travels through registers while the current one is multiplied; tiles are loaded in order.
   // Only the last tile can be ragged: every test on key indices sits behind a workgroup-uniform branch.
@@ -1155,18 +1158,18 @@ __global__ __attribute__((amdgpu_waves_per_eu(3, 3))) __launch_bounds__(256) voi
   auto load_tile = [&](int t) {
     if (!ragged || t + 1 < ntiles) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) kr[i] = *(const bf16x8*)kp[i];
+      for (int i = 0; i < 2; ++i) kr[i] = *(const bf16x8*)(kbase + kp[i]);
     } else {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) kr[i][e] = (bf16)0.f;
-        if (t * 64 + srow + 32 * i < Lk) kr[i] = *(const bf16x8*)kp[i];
+        if (t * 64 + srow + 32 * i < Lk) kr[i] = *(const bf16x8*)(kbase + kp[i]);
       }
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      vr[i] = *(const bf16x8*)vp[i];          // in bounds: ldv is padded to 64 keys
+      vr[i] = *(const bf16x8*)(vbase + vp[i]);          // in bounds: ldv is padded to 64 keys
       kp[i] += kstep;
       vp[i] += 64;
     }
@@ -1347,6 +1350,8 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
   const float scale = 1.f / sqrtf((float)head_dim);
   if (dtype == AD_BF16 && head_dim == 64 && v_t) {
     if (ldv < round_up(lk, 64) || (ldq | ldk | ldv | ldo) % 8) AD_FAIL(AD_ERR_INVALID, "attention: MFMA path needs padded, 8-aligned strides");
+    // the kernel walks K and V^T with 32-bit element offsets from the (sample, head) base
+    if ((long long)(lk + 64) * ldk >= (1LL << 32) || 64LL * ldv + lk >= (1LL << 32)) AD_FAIL(AD_ERR_INVALID, "attention: key tensor too large");
     ProfLaunch pl("attn_mfma_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s, batch * l, lk, c);
     const int qblocks = (l + 127) / 128;
     if (lk & 63)
