@@ -87,7 +87,7 @@ def time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, de
     return ms
 
 
-def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", max_evals=40, gain=0.002):
+def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", max_evals=40, gain=0.0005):
     """Steepest descent around `cuts`: every split with one cut moved by one or two units is timed, the best one is
     taken while the measured round time drops by more than `gain` (relative) and fewer than `max_evals` splits
     have been timed.  Returns (cuts, ms per round, {cuts tuple: ms})."""
