@@ -199,3 +199,22 @@ def test_video_configuration_shapes_and_checks():
                 dict(d, pooled_dim=1280)):
         with pytest.raises(B.AsyncDiffError):
             ad.AsyncDiff(bad, 4, 2, 1, B.AD_BF16)
+
+
+def test_kernel_entry_points_reject_bad_shapes_before_touching_the_gpu():
+    """Shape checks sit on the host, in front of every launch: a bad call comes back with AD_ERR_INVALID."""
+    import ctypes as C
+    L = B.lib
+    fake = C.c_void_p(256)                     # never dereferenced: every call below fails validation first
+    none = C.c_void_p(0)
+    bad = [
+        L.ad_attention_frames_forward(B.AD_BF16, none, fake, fake, 16, 64, 320, 8, 320, 320, 320, 320, fake, none),   # null q
+        L.ad_attention_frames_forward(B.AD_BF16, fake, fake, fake, 17, 64, 320, 8, 320, 320, 320, 320, fake, none),   # too many frames
+        L.ad_attention_frames_forward(B.AD_BF16, fake, fake, fake, 16, 64, 320, 7, 320, 320, 320, 320, fake, none),   # heads do not divide c
+        L.ad_attention_frames_forward(B.AD_BF16, fake, fake, fake, 16, 64, 320, 8, 319, 320, 320, 320, fake, none),   # leading dimension < c
+        L.ad_attention_frames_forward(7, fake, fake, fake, 16, 64, 320, 8, 320, 320, 320, 320, fake, none),           # dtype
+        L.ad_attention_forward(B.AD_BF16, fake, fake, fake, 1, 2, 128, 128, 320, 64, 320, 320, 100, 320, fake, none),  # V^T rows shorter than the keys
+        L.ad_attention_forward(B.AD_BF16, fake, fake, fake, 0, 2, 128, 128, 320, 256, 320, 320, 320, 320, fake, none),  # head_dim > 128
+    ]
+    assert all(st == B.AD_ERR_INVALID for st in bad), bad
+    assert b"frame attention" in L.ad_last_error() or b"attention" in L.ad_last_error()
