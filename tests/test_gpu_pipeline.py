@@ -623,11 +623,13 @@ def test_video_tiny_schedule_variants(N, w, S, sampler, wrap, shift):
     assert done == T
 
 
-def test_full_size_whole_unet_matches_oracle(full_size_weights):
-    """The complete noise prediction of the 768px model (all 46 units as one component, 4.3 TFLOP in fp64 on the
-    oracle side: about a minute of CPU time) against the GPU's first denoising step, element by element."""
+@pytest.mark.parametrize("name", ["sd21_768", "sd_512"])
+def test_full_size_whole_unet_matches_oracle(full_size_weights, name):
+    """The complete noise prediction of the 768px and of the 512px model (all 46 units as one component; 4.3 and 1.9
+    TFLOP in fp64 on the oracle side, up to half a minute of CPU time) against the GPU's first denoising step,
+    element by element.  The two configurations share the architecture and therefore the weights."""
     from oracle.unet import unet_forward
-    d = CONFIGS["sd21_768"]
+    d = CONFIGS[name]
     ocfg = UNetConfig(**d)
     noise = SI.make_latent(d["latent_channels"], d["height"], d["width"])
     text = quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), B.AD_BF16)
@@ -648,7 +650,7 @@ def test_full_size_whole_unet_matches_oracle(full_size_weights):
     x = np.broadcast_to(noise.astype(np.float64), (d["batch"],) + noise.shape).copy()
     ref = unet_forward(ocfg, full_size_weights, x, taus[0], text.astype(np.float64))
     err = rel_l2(got, ref)
-    print(f"whole UNet at full size: rel L2 {err:.3e}", flush=True)
+    print(f"whole UNet at full size ({name}): rel L2 {err:.3e}", flush=True)
     assert got.shape == ref.shape and err < 2e-2
 
 
