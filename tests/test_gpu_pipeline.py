@@ -670,3 +670,41 @@ def test_partition_tuning_helpers():
     case = Case("sd21_narrow", B.AD_BF16, 3, 1, 1, 5, cuts=best)
     got, _ = run_steps(case, 3)
     assert rel_l2(got, case.oracle.run(case.noise, case.text)[-1]) < 5e-2
+
+
+def test_full_size_sdxl_first_units_match_oracle():
+    """The SDXL-shaped configuration at its real shape (1024px: latent 128x128, text width 2048, pooled branch):
+    the first seven units (first convolution, three ResBlocks, the strided convolution and a depth-2 transformer
+    over 4096 tokens) against the oracle on the same seeded inputs."""
+    from oracle.unet import build_units, run_units
+    d = CONFIGS["sdxl_1024"]
+    ocfg = UNetConfig(**d)
+    units = build_units(ocfg)
+    last = 6
+    assert [u.kind for u in units[:last + 1]] == ["conv_in", "res", "res", "down", "res", "tfm", "res"]
+    wts = SI.make_weights(weight_manifest(ocfg), bf16_exact=True)
+    prefixes = tuple(units[i].name + "." for i in range(last + 1)) + ("time.", "pool.")
+    sub = {k: np.asarray(v, np.float64) for k, v in wts.items() if k.startswith(prefixes)}
+    noise = SI.make_latent(d["latent_channels"], d["height"], d["width"])
+    text = quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), B.AD_BF16)
+    pooled = SI.make_pooled(d["batch"], d["pooled_dim"])
+    taus = __import__("oracle.sampler", fromlist=["timesteps"]).timesteps(50)
+    x = np.broadcast_to(noise.astype(np.float64), (d["batch"],) + noise.shape).copy()
+    ref = run_units(ocfg, units, 0, last, sub, {-1: x}, taus[0], text.astype(np.float64), pooled)
+
+    m = ad.AsyncDiff(d, 4, 3, 2, B.AD_BF16, cuts=[last + 1, 15, 27])
+    m.allocate(DEV)
+    m.load_weights(wts)
+    m.reset(50, sampler=B.AD_EULER)
+    ins, outs = m.component_io(1)
+    assert ins == [-1] and sorted(ref.keys()) == sorted(outs)
+    hout = []
+    for u in outs:
+        (b, h, w, c), _ = m.tensor_shape(u)
+        hout.append(torch.full((b, h, w, c), float("nan"), device=DEV, dtype=torch.bfloat16))
+    m.component_forward(1, [dev_f32(noise)], 0, dev(text, B.AD_BF16), hout, torch.cuda.current_stream(), pooled=dev_f32(pooled))
+    torch.cuda.synchronize()
+    for u, t in zip(outs, hout):
+        err = rel_l2(nhwc_to_nchw(host(t)), ref[u])
+        assert err < 2e-2, f"unit {u}: rel L2 {err:.3e}"
+    m.close()
