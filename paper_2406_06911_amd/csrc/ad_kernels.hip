@@ -49,7 +49,20 @@ template <> __device__ __forceinline__ bf16 from_f<bf16>(float v) { return (bf16
 template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
-__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
+// Exact-erf GELU x Phi(x) with erf from the rational approximation 7.1.26 of Abramowitz and Stegun,
+// erf(z) = 1 - (a1 t + ... + a5 t^5) exp(-z^2), t = 1 / (1 + p z), |error| <= 1.5e-7: a dozen vector instructions
+// instead of the ~25 of the library erff, which made up a third of the busy time of the GEGLU projections.
+__device__ __forceinline__ float gelu_f(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __frcp_rn(fmaf(0.3275911f, z, 1.f));
+  const float e = __builtin_amdgcn_exp2f(-1.44269504088896341f * z * z);
+  float p = fmaf(t, 1.061405429f, -1.453152027f);
+  p = fmaf(t, p, 1.421413741f);
+  p = fmaf(t, p, -0.284496736f);
+  p = fmaf(t, p, 0.254829592f);
+  const float erf_abs = fmaf(-p * t, e, 1.f);
+  return 0.5f * x * (1.f + copysignf(erf_abs, x));
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
