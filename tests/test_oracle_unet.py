@@ -5,6 +5,7 @@ What fixes the UNet here is public knowledge about the SD-shaped networks the pa
 """
 import itertools
 import json
+import math
 import os
 
 import numpy as np
@@ -204,3 +205,77 @@ def test_blocks_against_torch_modules(tiny):
                                TF.conv2d(torch.from_numpy(h[:, :32]), T("d0.ds.conv.w"), T("d0.ds.conv.b"), stride=2, padding=1).numpy(), rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(run_unit(cfg, units, 9, wts, h, None, temb_np, ctx),
                                TF.conv2d(TF.interpolate(xt, scale_factor=2, mode="nearest"), T("u1.us.conv.w"), T("u1.us.conv.b"), padding=1).numpy(), rtol=1e-10, atol=1e-12)
+
+
+def _silu_scalar(v):
+    return v / (1.0 + np.exp(-v))
+
+
+@pytest.mark.parametrize("pooled_dim", [0, 6])
+def test_time_embedding_against_explicit_loops_and_torch(pooled_dim):
+    """Pins oracle.unet.time_embedding (the time MLP and the pooled branch of the SDXL-shaped model) against
+    (a) scalar loops over every output feature and (b) torch.nn.functional, on tiny widths with batch 2 and two
+    different pooled rows; then plants the plausible mistakes and checks that they are told apart."""
+    import torch
+    import torch.nn.functional as TF
+    from oracle.unet import time_embedding
+    cfg = UNetConfig(latent_channels=4, height=4, width=4, batch=2, channels=[8, 16], layers_per_block=1,
+                     transformer_depth=[0, 0], mid_depth=0, head_dim=8, gn_groups=4, ctx_len=2, ctx_dim=8, pooled_dim=pooled_dim)
+    c0, td = 8, 32
+    assert cfg.temb_dim == td
+    rng = np.random.default_rng(91)
+    W = {"time.lin1.w": rng.standard_normal((td, c0)), "time.lin1.b": rng.standard_normal(td),
+         "time.lin2.w": rng.standard_normal((td, td)) * 0.3, "time.lin2.b": rng.standard_normal(td)}
+    pooled = None
+    if pooled_dim:
+        W.update({"pool.lin1.w": rng.standard_normal((td, pooled_dim)), "pool.lin1.b": rng.standard_normal(td),
+                  "pool.lin2.w": rng.standard_normal((td, td)) * 0.3, "pool.lin2.b": rng.standard_normal(td)})
+        pooled = rng.standard_normal((2, pooled_dim))
+    tau = 637
+    got = time_embedding(cfg, W, tau, pooled)
+    assert got.shape == (2, td)
+
+    # (a) scalar loops; the sinusoid is written out too: [cos | sin], f_k = 10^(-4 k / half)
+    half = c0 // 2
+    e = [math.cos(tau * 10.0 ** (-4.0 * k / half)) for k in range(half)] + [math.sin(tau * 10.0 ** (-4.0 * k / half)) for k in range(half)]
+    hid = [_silu_scalar(W["time.lin1.b"][o] + sum(W["time.lin1.w"][o, i] * e[i] for i in range(c0))) for o in range(td)]
+    ref = np.zeros((2, td))
+    for b in range(2):
+        for o in range(td):
+            ref[b, o] = W["time.lin2.b"][o] + sum(W["time.lin2.w"][o, i] * hid[i] for i in range(td))
+        if pooled_dim:
+            ph = [_silu_scalar(W["pool.lin1.b"][o] + sum(W["pool.lin1.w"][o, i] * pooled[b, i] for i in range(pooled_dim))) for o in range(td)]
+            for o in range(td):
+                ref[b, o] += W["pool.lin2.b"][o] + sum(W["pool.lin2.w"][o, i] * ph[i] for i in range(td))
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-12)
+
+    # (b) library routines
+    T = lambda k: torch.from_numpy(np.ascontiguousarray(W[k]))
+    te = torch.tensor(e, dtype=torch.float64)[None]
+    tref = TF.linear(TF.silu(TF.linear(te, T("time.lin1.w"), T("time.lin1.b"))), T("time.lin2.w"), T("time.lin2.b")).expand(2, td)
+    if pooled_dim:
+        tref = tref + TF.linear(TF.silu(TF.linear(torch.from_numpy(pooled), T("pool.lin1.w"), T("pool.lin1.b"))), T("pool.lin2.w"), T("pool.lin2.b"))
+    np.testing.assert_allclose(got, tref.numpy(), rtol=1e-12, atol=1e-12)
+
+    # planted mistakes (CPU only): each must be far outside the tolerance above
+    lin = lambda x, w, b: x @ W[w].T + W[b]
+    ev = np.asarray(e)[None]
+    wrong = [
+        _silu_scalar(lin(lin(ev, "time.lin1.w", "time.lin1.b"), "time.lin2.w", "time.lin2.b")),          # SiLU after Lin2
+        lin(lin(_silu_scalar(ev), "time.lin1.w", "time.lin1.b"), "time.lin2.w", "time.lin2.b"),          # SiLU before Lin1
+        lin(lin(ev, "time.lin1.w", "time.lin1.b"), "time.lin2.w", "time.lin2.b"),                        # no SiLU
+    ]
+    if pooled_dim:
+        base = lin(_silu_scalar(lin(ev, "time.lin1.w", "time.lin1.b")), "time.lin2.w", "time.lin2.b")
+        ph = _silu_scalar(lin(pooled, "pool.lin1.w", "pool.lin1.b"))
+        wrong += [
+            lin(_silu_scalar(lin(ev, "time.lin1.w", "time.lin1.b")) + ph, "time.lin2.w", "time.lin2.b"),  # pooled term added before Lin2
+            base + lin(ph[::-1], "pool.lin2.w", "pool.lin2.b"),                                           # batch rows swapped
+            base + lin(lin(pooled, "pool.lin1.w", "pool.lin1.b"), "pool.lin2.w", "pool.lin2.b"),          # pooled SiLU dropped
+            np.broadcast_to(base, (2, td)),                                                               # pooled branch dropped
+        ]
+        assert np.abs(got[0] - got[1]).max() > 1e-3          # rows differ only through the pooled branch
+    else:
+        np.testing.assert_array_equal(got[0], got[1])        # every batch row shares the timestep
+    for wv in wrong:
+        assert np.abs(np.broadcast_to(wv, got.shape) - got).max() > 1e-3
