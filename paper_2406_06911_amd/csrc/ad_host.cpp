@@ -538,6 +538,7 @@ static ad_status validate(const ad_unet_cfg& g, int n, int warmup, int stride) {
   if (g.pooled_dim < 0 || g.pooled_dim % 8) AD_FAIL(AD_ERR_INVALID, "pooled_dim must be a non-negative multiple of 8");
   if (g.frames < 0 || g.frames > 16) AD_FAIL(AD_ERR_INVALID, "frames must be 0 (image model) or 1..16");
   if (g.frames > 0 && g.batch != g.frames) AD_FAIL(AD_ERR_INVALID, "a video model has batch == frames");
+  if (g.frames == 0 && g.batch > 2) AD_FAIL(AD_ERR_INVALID, "an image model has batch 1 (no guidance) or 2 (guidance pair)");
   if (g.frames > 0 && g.pooled_dim > 0) AD_FAIL(AD_ERR_INVALID, "the pooled-embedding branch is not defined for the video model");
   if (g.temporal_heads < 0 || (g.temporal_heads > 0 && g.frames == 0)) AD_FAIL(AD_ERR_INVALID, "temporal_heads needs frames > 0");
   if (g.temporal_heads > 0) {

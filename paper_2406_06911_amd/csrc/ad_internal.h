@@ -134,6 +134,7 @@ struct Ctx {
     const void* latent = nullptr; const void* text = nullptr; const void* pooled = nullptr;
     std::vector<hipStream_t> streams;
     float cfg_scale = 0.f;
+    std::vector<int> offsets;            // per row: component and (tau, latent, eps) step relative to the round's first step
   } round_graph[2];
 };
 

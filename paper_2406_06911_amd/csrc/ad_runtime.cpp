@@ -625,8 +625,19 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
     // an asynchronous full round depends on the step only through the device-side counter: capture it once
     // per slot parity (and per set of caller pointers), then replay
     Ctx::RoundGraph& g = c.round_graph[c.rows[r0].write_slot & 1];
+    // what a captured round bakes in besides the pointers: every row's step indices relative to the device counter
+    // (they differ between rounds when time shifting starts, or for the round right after a warm-up of zero steps)
+    std::vector<int> offsets;
+    for (size_t r = r0; r < r1; ++r) {
+      const ad_sched_row& row = c.rows[r];
+      offsets.push_back(row.comp);
+      offsets.push_back(row.tau_step - c.steps_done);
+      offsets.push_back(row.latent_step >= 0 ? row.latent_step - c.steps_done : INT32_MIN);
+      offsets.push_back(row.eps_step >= 0 ? row.eps_step - c.steps_done : INT32_MIN);
+      offsets.push_back(row.fresh_from);
+    }
     bool same = g.exec && g.latent == latent && g.text == text_emb && g.pooled == pooled_emb && g.cfg_scale == c.cfg_scale &&
-                (int)g.streams.size() == ns;
+                (int)g.streams.size() == ns && g.offsets == offsets;
     for (int k = 0; same && k < ns; ++k) same = g.streams[k] == (hipStream_t)streams[k];
     if (!same) {
       if (g.exec) AD_HIP(hipStreamSynchronize(s0));   // a replay of the old graph may still be running
@@ -641,6 +652,7 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
       AD_HIP(hipGraphInstantiate(&g.exec, g.graph, nullptr, nullptr, 0));
       g.latent = latent; g.text = text_emb; g.pooled = pooled_emb; g.cfg_scale = c.cfg_scale;
       g.streams.assign((const hipStream_t*)streams, (const hipStream_t*)streams + ns);
+      g.offsets = offsets;
     } else {
       for (size_t r = r0; r < r1; ++r)
         if (c.rows[r].eps_step >= 0) done.push_back(c.rows[r].eps_step);

@@ -59,4 +59,23 @@ def stream_ptr(s=None):
     return C.c_void_p(s.cuda_stream)
 
 
-TOL = {B.AD_F32: 1e-4, B.AD_BF16: 2e-2}
+TOL = {B.AD_F32: 1e-4, B.AD_BF16: 2e-2}      # per-component budget (whole unit ranges)
+KTOL = {B.AD_F32: 2e-5, B.AD_BF16: 5e-3}     # one kernel: a single rounding of the result to the storage type
+ULP = {B.AD_F32: 1e-5, B.AD_BF16: 2.0 ** -8}
+
+
+def assert_kernel_close(got, ref, dtype, c=2.0, rel=None):
+    """Single-kernel bar: relative L2 within KTOL and, element by element, |got - ref| <= c * ulp * (|ref| + rms(ref)).
+    One rounding to bf16 is at most 2^-9 |ref|; the rms term covers results that cancel to near zero.  A single
+    wrong element (a pad column read as data, a lost tap) is off by about rms(ref), i.e. a hundred times the bound."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.isfinite(got).all()
+    scale = float(np.sqrt(np.mean(ref * ref)))
+    bound = c * ULP[dtype] * (np.abs(ref) + scale)
+    excess = np.abs(got - ref) - bound
+    worst = int(np.argmax(excess))
+    assert excess.flat[worst] <= 0, (f"element {np.unravel_index(worst, ref.shape)}: got {got.flat[worst]!r} ref {ref.flat[worst]!r} "
+                                      f"bound {bound.flat[worst]:.3e}")
+    err = rel_l2(got, ref)
+    assert err < (KTOL[dtype] if rel is None else rel), err

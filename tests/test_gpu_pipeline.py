@@ -219,6 +219,10 @@ def test_concurrent_streams_equal_serial_order_bitwise():
 @pytest.mark.parametrize("name,dtype,N,w,S,T,sampler,shift", [
     ("tiny", B.AD_F32, 3, 1, 2, 14, "ddim", False),
     ("tiny", B.AD_F32, 2, 2, 1, 9, "euler", True),
+    # no warm-up, one component, time shifting: the first round's timestep offset differs from every later round's,
+    # so a graph captured in round 0 must not be replayed for round 2
+    ("tiny", B.AD_F32, 1, 0, 1, 7, "ddim", True),
+    ("tiny", B.AD_F32, 1, 0, 2, 9, "ddim", True),
     ("sd21_narrow", B.AD_BF16, 4, 1, 1, 8, "ddim", False),
 ])
 def test_graph_replay_equals_direct_launch_bitwise(name, dtype, N, w, S, T, sampler, shift):
