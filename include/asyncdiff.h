@@ -298,6 +298,15 @@ size_t ad_groupnorm_scratch_bytes(int batch, int hw, int c);
 ad_status ad_groupnorm_forward(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw,
                                int groups, const float* gamma, const float* beta, float eps, int silu,
                                void* out, void* scratch, ad_stream stream);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): ad_groupnorm_forward with the partial sums kept in a fixed 512 KiB device array of the
+ * library instead of a caller-supplied scratch buffer.  Same kernels, same results bit for bit.  Calls no
+ * hipMalloc / hipFree.  Limit: 2 * batch * min(64, max(1, hw / 8)) * groups * 8 bytes <= 512 KiB (e.g. batch 16 with
+ * 32 groups), else AD_ERR_NOMEM.  Every call on a GPU shares that GPU's array: calls that overlap on one GPU
+ * (different streams, or threads) race; calls on one stream are ordered and need no clearing in between. */
+ad_status ad_groupnorm_forward_static(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw,
+                                      int groups, const float* gamma, const float* beta, float eps, int silu,
+                                      void* out, ad_stream stream);
 ad_status ad_layernorm_forward(int dtype, const void* src, int rows, int c, const float* gamma, const float* beta,
                                float eps, void* out, ad_stream stream);
 /* Multi-head attention out[b][l][h*d+j] = softmax(q k^T / sqrt(d)) v, heads = c / head_dim.

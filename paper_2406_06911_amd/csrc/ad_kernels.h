@@ -55,6 +55,9 @@ size_t conv_workspace_bytes(int dtype, long long m, int n, int k, int out_mode);
 ad_status launch_groupnorm(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw, int groups,
                            const float* gamma, const float* beta, float eps, int silu, void* out, void* scratch,
                            size_t scratch_bytes, hipStream_t s);
+// the same with the partial sums in the library's fixed device array (no caller scratch, no allocation)
+ad_status launch_groupnorm_static(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw, int groups,
+                                  const float* gamma, const float* beta, float eps, int silu, void* out, hipStream_t s);
 ad_status launch_layernorm(int dtype, const void* src, int rows, int c, const float* gamma, const float* beta, float eps,
                            void* out, hipStream_t s);
 ad_status launch_attention(int dtype, const void* q, const void* k, const void* v, int v_t, int batch, int l, int lk, int c,

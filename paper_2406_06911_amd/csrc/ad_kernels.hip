@@ -13,6 +13,7 @@
 #include "ad_kernels.h"
 
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 namespace ad {
@@ -1831,6 +1832,11 @@ static ad_status run_groupnorm(const void* src0, const void* src1, int c0, int c
   return AD_OK;
 }
 
+// bytes of partial sums the two-pass path writes: [2 sources][batch][chunks][groups][sum, sum of squares]
+static size_t gn_partial_bytes(int batch, int hw, int groups) {
+  return (size_t)2 * batch * gn_chunks(hw) * groups * 2 * sizeof(float);
+}
+
 ad_status launch_groupnorm(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw, int groups,
                            const float* gamma, const float* beta, float eps, int silu, void* out, void* scratch,
                            size_t scratch_bytes, hipStream_t s) {
@@ -1838,10 +1844,50 @@ ad_status launch_groupnorm(int dtype, const void* src0, const void* src1, int c0
   const int vn = dtype == AD_BF16 ? 8 : 4;
   if (batch < 1 || hw < 1 || c0 < vn || c0 % vn || c1 < 0 || c1 % vn || groups < 1 || (c0 + c1) % groups)
     AD_FAIL(AD_ERR_INVALID, "groupnorm: bad shape");
-  if (scratch_bytes < ad_groupnorm_scratch_bytes(batch, hw, c0 + c1)) AD_FAIL(AD_ERR_NOMEM, "groupnorm: scratch too small");
+  if (scratch_bytes < gn_partial_bytes(batch, hw, groups)) AD_FAIL(AD_ERR_NOMEM, "groupnorm: scratch too small");
   if (dtype == AD_BF16) return run_groupnorm<bf16>(src0, src1, c0, c1, batch, hw, groups, gamma, beta, eps, silu, out, scratch, s);
   if (dtype == AD_F32) return run_groupnorm<float>(src0, src1, c0, c1, batch, hw, groups, gamma, beta, eps, silu, out, scratch, s);
   AD_FAIL(AD_ERR_INVALID, "groupnorm: bad dtype");
+}
+
+// -------------------------------------------------------------------------------------------------
+// GroupNorm for callers that cannot allocate: the partial sums live in a fixed device array of this library
+// instead of a caller-supplied scratch buffer.  Host code never uses the array's name as an address: the device
+// address is looked up once per device (hipGetSymbolAddress, with that device current) and kept.
+// -------------------------------------------------------------------------------------------------
+constexpr size_t kStaticGnBytes = 512 * 1024;      // e.g. batch 16, 64 pixel chunks, 32 groups, two sources
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticGnBytes];
+static void* g_scratch_ptr[kMaxDevices] = {nullptr};
+static std::mutex g_scratch_mutex;
+
+static ad_status static_scratch(void** out) {
+  int dev = -1;
+  AD_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) AD_FAIL(AD_ERR_INVALID, "groupnorm (static scratch): device %d out of range", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    AD_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) AD_FAIL(AD_ERR_HIP, "groupnorm (static scratch): no device address");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return AD_OK;
+}
+
+ad_status launch_groupnorm_static(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw, int groups,
+                                  const float* gamma, const float* beta, float eps, int silu, void* out, hipStream_t s) {
+  if (batch < 1 || hw < 1 || groups < 1) AD_FAIL(AD_ERR_INVALID, "groupnorm: bad shape");
+  const size_t need = gn_partial_bytes(batch, hw, groups);
+  if (need > kStaticGnBytes)
+    AD_FAIL(AD_ERR_NOMEM, "groupnorm (static scratch): batch %d x %d chunks x %d groups needs %zu bytes, the fixed buffer holds %zu",
+            batch, gn_chunks(hw), groups, need, kStaticGnBytes);
+  void* ptr = nullptr;
+  ad_status st = static_scratch(&ptr);
+  if (st != AD_OK) return st;
+  // every partial sum the second pass reads is written by the first pass of the same call: nothing to clear
+  return launch_groupnorm(dtype, src0, src1, c0, c1, batch, hw, groups, gamma, beta, eps, silu, out, ptr, kStaticGnBytes, s);
 }
 
 // LayerNorm: one wavefront per row, the row stays in registers between the two statistics passes.
@@ -2078,6 +2124,12 @@ ad_status ad_groupnorm_forward(int dtype, const void* src0, const void* src1, in
                                void* scratch, ad_stream stream) {
   return launch_groupnorm(dtype, src0, src1, c0, c1, batch, hw, groups, gamma, beta, eps, silu, out, scratch,
                           ad_groupnorm_scratch_bytes(batch, hw, c0 + c1), (hipStream_t)stream);
+}
+
+ad_status ad_groupnorm_forward_static(int dtype, const void* src0, const void* src1, int c0, int c1, int batch, int hw,
+                                      int groups, const float* gamma, const float* beta, float eps, int silu, void* out,
+                                      ad_stream stream) {
+  return launch_groupnorm_static(dtype, src0, src1, c0, c1, batch, hw, groups, gamma, beta, eps, silu, out, (hipStream_t)stream);
 }
 
 ad_status ad_layernorm_forward(int dtype, const void* src, int rows, int c, const float* gamma, const float* beta,
