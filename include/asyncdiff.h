@@ -289,6 +289,10 @@ ad_status ad_tune_conv_tile(int tile);
  * column tiles (the activations are fetched into every L2); -1: automatic, the default (the smaller operand is
  * the one fetched everywhere).  Results are bit-identical. */
 ad_status ad_tune_conv_order(int order);
+/* Tuning knob for measurements and tests (process-global, not thread-safe): which MFMA attention kernel serves bf16,
+ * head_dim 64, transposed v.  0: 32 queries per wavefront, register-staged tiles; 1 / 2: tiles filled by the load
+ * unit, lazy maximum, 32 / 64 queries per wavefront; -1: automatic, the default.  Same results up to rounding. */
+ad_status ad_tune_attention(int variant);
 /* Packs HOST fp32 weights [n_out][c_in][k][k] into the kernel layout (HOST out, dtype elements).
  * Returns the packed size in bytes through *bytes when out == NULL. */
 ad_status ad_pack_conv_weight(int dtype, const float* w, int n_out, int c_in, int ksize, int geglu, void* out, size_t* bytes);

@@ -78,7 +78,7 @@ EXPORTS = [
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
     "ad_conv_forward", "ad_conv_workspace_bytes", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
     "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode", "ad_create_with_cuts", "ad_balance_cuts", "ad_tune_conv_order", "ad_create_wrapped", "ad_num_segments",
-    "ad_attention_frames_forward", "ad_groupnorm_forward_static",
+    "ad_attention_frames_forward", "ad_groupnorm_forward_static", "ad_tune_attention",
 ]
 
 
@@ -128,6 +128,7 @@ def _load():
     L.ad_attention_forward.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
     L.ad_attention_frames_forward.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp]
     L.ad_tune_conv_tile.argtypes = [ci]
+    L.ad_tune_attention.argtypes = [ci]
     L.ad_precompute_text.argtypes = [vp, vp, vp]
     L.ad_set_graph_mode.argtypes = [vp, ci]
     L.ad_profile_enable.argtypes = [vp, ci]

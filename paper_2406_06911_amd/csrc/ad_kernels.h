@@ -48,6 +48,7 @@ enum { OUT_ROWMAJOR = 0, OUT_GEGLU = 1, OUT_TRANSPOSED = 2, OUT_TRANSPOSED_F32 =
 
 ad_status launch_conv(const ConvArgs& a, hipStream_t s);
 void set_tile_override(int tile);     // -1 = choose automatically
+void set_attn_variant(int variant);   // -1 automatic, 0 first-generation kernel, 1 / 2 second generation with 32 / 64 queries per wavefront
 void set_order_override(int order);   // -1 automatic, 0 row-tile-major, 1 column-tile-major workgroup order
 // scratch a convolution of this shape wants for split-K (0 = it will not split); k = taps * channels
 size_t conv_workspace_bytes(int dtype, long long m, int n, int k, int out_mode);

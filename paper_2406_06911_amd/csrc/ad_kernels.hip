@@ -36,6 +36,7 @@ ProfLaunch::~ProfLaunch() {
 typedef __bf16 bf16;
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -495,6 +496,13 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// Swizzle of the dense 128-byte LDS rows the load unit fills: row r keeps its 16-byte chunk c at position
+// c ^ lds_swizzle(r).  A ds_read_b128 serves 16 lanes (256 bytes, the width of the bank window) per cycle; the
+// fragment reads take the same chunk of 16 consecutive rows, which (r >> 1) & 7 spreads over the 16 positions of
+// the window (two rows share a window).  With r & 7 rows r and r + 8 collide: every read takes twice as long
+// (counter SQ_LDS_BANK_CONFLICT: half of the LDS cycles).
+__device__ __forceinline__ int lds_swizzle(int row) { return (row >> 1) & 7; }
+
 template <typename T, int MODE, int NSTAGE>
 __global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
   typedef typename Vec<T>::type V;
@@ -516,7 +524,7 @@ __global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
 
   // lane -> (row of the wavefront's 8-row group, swizzled 16-byte column it fetches)
   const int drow = wave * 8 + (lane >> 3);
-  const int scol = (lane & 7) ^ (lane >> 3);
+  const int scol = (lane & 7) ^ ((drow >> 1) & 7);      // see lds_swizzle()
   int a_iy0[AV], a_ix0[AV], a_b[AV];
 #pragma unroll
   for (int i = 0; i < AV; ++i) {
@@ -582,9 +590,9 @@ __global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
 #pragma unroll
   for (int t = 0; t < NSTAGE - 1; ++t)
     if (t < nkt) issue(t);
-  // fragment reads: row * 128 + ((chunk ^ (row & 7)) * 16), chunk = 2 ks + half
+  // fragment reads: row * 128 + ((chunk ^ lds_swizzle(row)) * 16), chunk = 2 ks + half
   const int a_row = (wave_m * WTM + l32) * kRowBytes, b_row = (BM + wave_n * WTN + l32) * kRowBytes;
-  const int x7 = l32 & 7;
+  const int x7 = lds_swizzle(l32);
   int stage = 0;
   for (int kt = 0; kt < nkt; ++kt) {
     // tiles issued after kt that may still be in flight: min(NSTAGE - 2, nkt - 1 - kt)
@@ -650,7 +658,7 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
   const u32x4 rsw = make_rsrc_words(p.w, p.bytes_w);
 
   // load i of a k-tile covers rows (4 i + wave) * 8 .. + 7 of the A tile (i < AG) or of the B tile
-  const int r8 = lane >> 3, scol = (lane & 7) ^ r8;
+  const int r8 = lane >> 3, scol = (lane & 7) ^ (((wave * 8 + r8) >> 1) & 7);      // see lds_swizzle(); rows (4 i + wave) * 8 + r8
   const int kt_begin = tid3.split * p.kt_per_split;
   const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
@@ -734,9 +742,9 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
       for (int i = 0; i < AG; ++i) issue_one(t, i);      // the B part of these tiles is already on its way
       end_tile();
     }
-  // fragment reads: row * 128 + ((chunk ^ (row & 7)) * 16), chunk = 2 ks + half
+  // fragment reads: row * 128 + ((chunk ^ lds_swizzle(row)) * 16), chunk = 2 ks + half
   const int a_row = (wave_m * WTM + l32) * kRowBytes, b_row = (BM + wave_n * WTN + l32) * kRowBytes;
-  const int x7 = l32 & 7;
+  const int x7 = lds_swizzle(l32);
   int sw[kRowBytes / 32];
 #pragma unroll
   for (int ks = 0; ks < kRowBytes / 32; ++ks) sw[ks] = ((ks * 2 + half) ^ x7) << 4;
@@ -1308,6 +1316,259 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(256) voi
   }
 }
 
+// =================================================================================================
+// Fused attention, second generation (bf16, head_dim 64).  What changed against k_attn_mfma and why:
+//  * a wavefront owns 32 * QSETS queries (QSETS = 2: 64), so every K and V^T fragment read from LDS feeds QSETS
+//    MFMAs: at 32 queries per wavefront the fragment reads alone need the LDS port's full rate at full MFMA rate;
+//  * K and V^T tiles are written into LDS by the load unit (buffer_load ... lds, three stages, dense 128-byte rows
+//    with the XOR swizzle of the GEMM kernels): no staging registers, no ds_write;
+//  * the vector work per score is the exponential, half a conversion and half an add.  q is multiplied by
+//    log2(e) / sqrt(d) once, when it is loaded.  The reference value m that is subtracted before the exponential
+//    enters the score MFMA as its C operand (a 16-register block holding -m), so the scores leave the matrix pipe
+//    as s - m.  m need not be the running maximum: the result is exact for any m, and fp32 / bf16 hold
+//    2^(s - m) as long as s - m stays below about 100, so m is the exact maximum of the first 32 keys and is
+//    raised (with the usual rescaling of what has been accumulated) only when a row sum of a 32-key block
+//    reaches 2^100 - this is tested on the sum, which is needed anyway, so the steady state computes no
+//    maximum at all.  m never exceeds the running maximum, hence the largest term of a row is at least 1 and
+//    nothing underflows.  The row sums are taken from the bf16 probabilities, two per instruction;
+//  * the keys of a tile are placed in LDS rows so that the 8 score registers a lane holds per 16-key block are 8
+//    consecutive keys (LDS row 16 b + 8 a + 4 h + e holds key 16 b + 8 h + 4 a + e): the probabilities are the B
+//    operand of the PV product as they stand and V^T is read in its natural order;
+//  * an accumulator is used by MFMAs that follow each other directly (the result is forwarded) or are at least
+//    four apart: two alternating accumulation chains run at 58 instead of 33 cycles per MFMA on this chip.
+// Scores are computed transposed (S^T = K Q^T, a lane owns one query) as in the first kernel.
+// =================================================================================================
+constexpr int kAttn2Stage = 2 * 64 * kRowBytes;   // one K tile and one V^T tile of 64 keys: 16 KiB
+constexpr int kAttn2Stages = 3;
+constexpr float kAttnBig = 1.2676506e30f;
+#ifndef PRIO
+#define PRIO 2
+#endif         // 2^100: a 32-key row sum at or above it moves the reference
+
+template <int QSETS, bool RAGGED>
+__global__ __attribute__((amdgpu_waves_per_eu(QSETS == 1 ? 3 : 2, QSETS == 1 ? 3 : 2))) __launch_bounds__(256) void k_attn_mfma2(
+    const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ Vt, bf16* __restrict__ O, int L, int Lk, int C,
+    int ldq, int ldk, int ldv, int ldo, float scale_log2, int qblocks) {
+  __shared__ __attribute__((aligned(128))) char lds[kAttn2Stages * kAttn2Stage];
+  constexpr int QW = 32 * QSETS;                  // queries per wavefront
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool low = half == 0;
+  const int vid = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = vid / qblocks, heads = C / 64;
+  const int b = bh / heads, h = bh - b * heads;
+  const int q0 = (vid - bh * qblocks) * (4 * QW) + wave * QW + l32;
+  const int ntiles = (Lk + 63) / 64;
+
+  // ---- tile loads: per 64-key tile a wavefront issues two 8-row groups of K and two of V^T
+  const bf16* kbase = K + (size_t)b * Lk * ldk + h * 64;
+  const bf16* vbase = Vt + ((size_t)b * C + h * 64) * ldv;
+  const u32x4 rsk = make_rsrc_words(kbase, (unsigned)(((size_t)(Lk - 1) * ldk + 64) * 2));
+  const u32x4 rsv = make_rsrc_words(vbase, (unsigned)((size_t)64 * ldv * 2));
+  // LDS row r keeps its 16-byte chunk c at position c ^ ((r >> 1) & 7): the 16 rows that one quarter of a wavefront
+  // reads in a cycle (same chunk, consecutive rows) then fall on 16 different 16-byte bank groups of the 256-byte
+  // bank window (rows r and r + 8 collide with the plain r & 7 swizzle)
+  const int r8 = lane >> 3;
+  unsigned koff[2], voff[2];
+  int krow[2], scol[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int g = wave * 2 + i;                                              // 8-row group of the tile
+    scol[i] = (lane & 7) ^ (((g * 8 + r8) >> 1) & 7);                        // chunk this lane fetches for its row
+    krow[i] = 16 * (g >> 1) + 8 * (r8 >> 2) + 4 * (g & 1) + (r8 & 3);        // key held by LDS row 8 g + r8
+    koff[i] = (unsigned)(krow[i] * ldk + scol[i] * 8) * 2;
+    voff[i] = (unsigned)((g * 8 + r8) * ldv + scol[i] * 8) * 2;
+  }
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
+  const unsigned kstep = 64u * (unsigned)ldk * 2u;
+  auto issue = [&](int t, int stage) {
+    const unsigned st = lds_base + stage * kAttn2Stage + (unsigned)wave * 2048u;
+    const bool last = RAGGED && t == ntiles - 1;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      // keys past the end read zeros (their scores are masked, but the pad must not hold NaNs)
+      const unsigned ko = (last && t * 64 + krow[i] >= Lk) ? kOob : koff[i];
+      dma_load16(rsk, ko, (unsigned)t * kstep, st + i * 1024);
+    }
+    if (!last) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) dma_load16(rsv, voff[i], (unsigned)t * 128u, st + 8192 + i * 1024);
+    } else {
+      // the last, partial tile of V^T goes through registers: values of keys past the end are cleared, whatever the pad holds
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int g = wave * 2 + i;
+        bf16x8 v = *(const bf16x8*)(vbase + (size_t)(g * 8 + r8) * ldv + t * 64 + scol[i] * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (t * 64 + scol[i] * 8 + e >= Lk) v[e] = (bf16)0.f;
+        *(bf16x8*)(lds + stage * kAttn2Stage + 8192 + wave * 2048 + i * 1024 + lane * 16) = v;
+      }
+    }
+  };
+  issue(0, 0);
+  if (ntiles > 1) issue(1, 1);
+
+  // ---- queries: B operand of the score product, pre-multiplied by log2(e) / sqrt(d)
+  bf16x8 qf[QSETS][4];
+#pragma unroll
+  for (int s = 0; s < QSETS; ++s)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[s][ks][e] = (bf16)0.f;
+      if (q0 + 32 * s < L) {
+        const bf16x8 raw = *(const bf16x8*)(Q + ((size_t)b * L + q0 + 32 * s) * ldq + h * 64 + ks * 16 + half * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[s][ks][e] = (bf16)((float)raw[e] * scale_log2);
+      }
+    }
+  f32x16 o[QSETS][2], negm[QSETS];
+  float m_ref[QSETS], l_run[QSETS];
+#pragma unroll
+  for (int s = 0; s < QSETS; ++s) {
+    m_ref[s] = 0.f; l_run[s] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { o[s][0][r] = 0.f; o[s][1][r] = 0.f; negm[s][r] = 0.f; }
+  }
+  const int x7 = lds_swizzle(l32);
+  const int frag_row = l32 * kRowBytes;
+  const bf16x2 ones = {(bf16)1.f, (bf16)1.f};
+  auto mask_tail = [&](f32x16 (&sc)[QSETS], int t, int j) {
+    const int key0 = t * 64 + j * 32 + 8 * half;          // register r: key key0 + 16 (r / 8) + r % 8
+#pragma unroll
+    for (int s = 0; s < QSETS; ++s)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (key0 + 16 * (r >> 3) + (r & 7) >= Lk) sc[s][r] = -INFINITY;
+  };
+  // p = 2^(s - m) in bf16 for both 16-key halves of a block, and their row sums
+  auto probs = [&](const f32x16 (&sc)[QSETS], bf16x8 (&dst)[QSETS][2], float (&psum)[QSETS]) {
+#pragma unroll
+    for (int s = 0; s < QSETS; ++s) {
+      psum[s] = 0.f;
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const bf16x2 pp = {(bf16)__builtin_amdgcn_exp2f(sc[s][8 * s2 + e]), (bf16)__builtin_amdgcn_exp2f(sc[s][8 * s2 + e + 1])};
+          dst[s][s2][e] = pp[0]; dst[s][s2][e + 1] = pp[1];
+          psum[s] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum[s], false);
+        }
+    }
+  };
+  // One 32-key block: scores, probabilities, PV.  `first`: the block that fixes the reference (exact maximum).
+  auto block = [&](const char* Ks, int t, int j, bool first) {
+    const char* Vs = Ks + 8192;
+    bf16x8 kf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) kf[ks] = *(const bf16x8*)(Ks + j * 32 * kRowBytes + frag_row + (((ks * 2 + half) ^ x7) << 4));
+    f32x16 sc[QSETS];
+#pragma unroll
+    for (int s = 0; s < QSETS; ++s) {
+      sc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[s][0], negm[s], 0, 0, 0);
+#pragma unroll
+      for (int ks = 1; ks < 4; ++ks) sc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[s][ks], sc[s], 0, 0, 0);
+    }
+    // the V^T fragments are requested before the exponentials so that they have arrived when the PV products start
+    bf16x8 vf[2][2];
+#pragma unroll
+    for (int d = 0; d < 2; ++d)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+        vf[d][s2] = *(const bf16x8*)(Vs + d * 32 * kRowBytes + frag_row + (((j * 4 + s2 * 2 + half) ^ x7) << 4));
+    if (RAGGED && t == ntiles - 1) mask_tail(sc, t, j);
+    bf16x8 pb[QSETS][2];
+    float psum[QSETS];
+    probs(sc, pb, psum);
+    bool redo = first;
+#pragma unroll
+    for (int s = 0; s < QSETS; ++s) redo |= !(psum[s] < kAttnBig);
+    // the score MFMAs keep their program order: each chain of four runs back to back
+#pragma unroll
+    for (int i = 0; i < 4 * QSETS; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (__builtin_amdgcn_ballot_w64(redo) != 0) {
+      // rare: the reference is too far below some score of this block (or this is the first block).  Take the exact
+      // maximum of the block, move the reference there, rescale what has been accumulated, and redo the block.
+#pragma unroll
+      for (int s = 0; s < QSETS; ++s) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc[s][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const bf16x8 kk = *(const bf16x8*)(Ks + j * 32 * kRowBytes + frag_row + (((ks * 2 + half) ^ x7) << 4));
+          sc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk, qf[s][ks], sc[s], 0, 0, 0);
+        }
+      }
+      if (RAGGED && t == ntiles - 1) mask_tail(sc, t, j);
+#pragma unroll
+      for (int s = 0; s < QSETS; ++s) {
+        float a = fmaxf(fmaxf(sc[s][0], sc[s][1]), sc[s][2]);
+#pragma unroll
+        for (int r = 3; r + 1 < 16; r += 2) a = fmaxf(fmaxf(a, sc[s][r]), sc[s][r + 1]);
+        a = fmaxf(a, sc[s][15]);
+        a = fmaxf(a, other_half(a, low));
+        const float m_new = first ? a : fmaxf(m_ref[s], a);
+        const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(m_ref[s] - m_new);
+        m_ref[s] = m_new;
+        l_run[s] *= alpha;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          o[s][0][r] *= alpha; o[s][1][r] *= alpha;
+          sc[s][r] -= m_new;
+          negm[s][r] = -m_new;
+        }
+      }
+      probs(sc, pb, psum);
+    }
+#pragma unroll
+    for (int s = 0; s < QSETS; ++s) {
+      l_run[s] += psum[s];
+      // O^T += V^T P^T; the two MFMAs of an accumulator follow each other directly (the result is forwarded)
+#pragma unroll
+      for (int d = 0; d < 2; ++d)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) o[s][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[d][s2], pb[s][s2], o[s][d], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4 * QSETS; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+  };
+
+  int stage = 0;
+  for (int t = 0; t < ntiles; ++t) {
+    // tile t has landed once at most the loads of tile t + 1 are outstanding (a partial last tile waits by itself)
+    if (t + 1 < ntiles && !(RAGGED && t + 2 == ntiles)) wait_vmcnt<4>(); else wait_vmcnt<0>();
+    __syncthreads();       // tile t is complete for every wavefront, and everybody is done with tile t - 1
+    if (t + 2 < ntiles) {
+      int target = stage + 2;
+      if (target >= kAttn2Stages) target -= kAttn2Stages;
+      issue(t + 2, target);
+    }
+    const char* Ks = lds + stage * kAttn2Stage;
+    block(Ks, t, 0, t == 0);
+    block(Ks, t, 1, false);
+    if (++stage == kAttn2Stages) stage = 0;
+  }
+#pragma unroll
+  for (int s = 0; s < QSETS; ++s) {
+    const float l_tot = l_run[s] + other_half(l_run[s], low);
+    const int query = q0 + 32 * s;
+    if (query < L) {
+      const float inv = 1.f / l_tot;
+      bf16* orow = O + ((size_t)b * L + query) * ldo + h * 64;
+#pragma unroll
+      for (int d = 0; d < 2; ++d)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[s][d][4 * g + e] * inv);
+          *(bf16x4*)(orow + d * 32 + 8 * g + 4 * half) = v;
+        }
+    }
+  }
+}
+
 // Generic attention: one wavefront per query, keys in chunks of 64 (one per lane), online softmax.
 template <typename T>
 __global__ __launch_bounds__(256) void k_attn_simple(const T* __restrict__ Q, const T* __restrict__ K,
@@ -1358,6 +1619,18 @@ __global__ __launch_bounds__(256) void k_attn_simple(const T* __restrict__ Q, co
   }
 }
 
+// which MFMA attention kernel: 0 = first generation (32 queries per wavefront, register-staged tiles), 1 / 2 = second
+// generation with 32 / 64 queries per wavefront; -1 = automatic
+static int g_attn_variant = -1;
+void set_attn_variant(int v) { g_attn_variant = v; }
+static int attn_auto_variant(int bh, int l, int lk) {
+  // measured on the self-attention shapes of the SD-sized models: the second-generation kernel with 32 queries per
+  // wavefront is 8-20 % faster from a few hundred keys on; with one or two key tiles (cross-attention to the text,
+  // the deepest level) its longer prologue loses, and 64 queries per wavefront (two wavefronts per SIMD) never won
+  (void)bh; (void)l;
+  return lk > 256 ? 1 : 0;
+}
+
 ad_status launch_attention(int dtype, const void* q, const void* k, const void* v, int v_t, int batch, int l, int lk, int c,
                            int head_dim, int ldq, int ldk, int ldv, int ldo, void* out, hipStream_t s) {
   if (!q || !k || !v || !out) AD_FAIL(AD_ERR_INVALID, "attention: null pointer");
@@ -1371,6 +1644,24 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
     // the kernel walks K and V^T with 32-bit element offsets from the (sample, head) base
     if ((long long)(lk + 64) * ldk >= (1LL << 32) || 64LL * ldv + lk >= (1LL << 32)) AD_FAIL(AD_ERR_INVALID, "attention: key tensor too large");
     ProfLaunch pl("attn_mfma_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s, batch * l, lk, c);
+    int variant = g_attn_variant;
+    if (variant < 0) variant = attn_auto_variant(batch * heads, l, lk);
+    if (variant > 0) {
+      // the tile loads address K and V^T through 32-bit byte offsets from the (sample, head) base
+      if (((long long)(lk + 64) * ldk + 64) * 2 >= (1LL << 31) || (64LL * ldv + lk + 64) * 2 >= (1LL << 31))
+        AD_FAIL(AD_ERR_INVALID, "attention: key tensor too large");
+      if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) != 0) AD_FAIL(AD_ERR_INVALID, "attention: pointers must be 16-byte aligned");
+      const int qw = variant == 2 ? 256 : 128, qb = (l + qw - 1) / qw;
+      const dim3 grid(qb * heads * batch);
+      const float sl2 = scale * 1.44269504088896341f;
+#define AD_ATTN2(QS, RG) hipLaunchKernelGGL((k_attn_mfma2<QS, RG>), grid, dim3(256), 0, s, (const bf16*)q, (const bf16*)k, (const bf16*)v, \
+                                            (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, sl2, qb)
+      if (variant == 2) { if (lk & 63) AD_ATTN2(2, true); else AD_ATTN2(2, false); }
+      else { if (lk & 63) AD_ATTN2(1, true); else AD_ATTN2(1, false); }
+#undef AD_ATTN2
+      AD_HIP(hipGetLastError());
+      return AD_OK;
+    }
     const int qblocks = (l + 127) / 128;
     if (lk & 63)
       hipLaunchKernelGGL(k_attn_mfma<true>, dim3(qblocks * heads * batch), dim3(256), 0, s, (const bf16*)q, (const bf16*)k,
@@ -2155,6 +2446,12 @@ size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n
 ad_status ad_tune_conv_tile(int tile) {
   if (tile != -1 && tile != 1 && tile != 3 && (tile < 4 || tile > 7)) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1, 3, 4, 5, 6 or 7");
   set_tile_override(tile);
+  return AD_OK;
+}
+
+ad_status ad_tune_attention(int variant) {
+  if (variant < -1 || variant > 2) AD_FAIL(AD_ERR_INVALID, "variant must be -1, 0, 1 or 2");
+  set_attn_variant(variant);
   return AD_OK;
 }
 

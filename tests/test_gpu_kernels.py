@@ -243,6 +243,22 @@ def test_layernorm(dtype, rows, c):
 
 
 # ---------------------------------------------------------------------------------------------------
+LOG2E_F32 = np.float32(1.4426950408889634)
+
+
+def mfma2_contract(q, d, variant, dtype, transposed, lk):
+    """The second-generation MFMA attention kernels feed the matrix cores q * (log2(e) / sqrt(d)) rounded to bf16 (one
+    more rounding than the first kernel, which scales the fp32 scores).  That operand rounding is part of the kernel's
+    contract like the bf16 storage of q itself, so the oracle is given the same operand: returns the q (fp64) whose
+    plain softmax(q k^T / sqrt(d)) equals 2^(q' k^T) for the rounded q'.  Other kernels: q unchanged."""
+    second = variant in (1, 2) or (variant == -1 and lk > 256)
+    if not (second and dtype == B.AD_BF16 and d == 64 and transposed):
+        return q
+    c32 = np.float32(1.0) / np.sqrt(np.float32(d)) * LOG2E_F32
+    qp = SI.round_to_bf16(q.astype(np.float32) * c32)
+    return qp.astype(np.float64) * (math.log(2.0) * math.sqrt(d))
+
+
 def run_attention(dtype, q, k, v, heads, transposed):
     bsz, l, c = q.shape
     lk = k.shape[1]
@@ -271,17 +287,37 @@ ATT_CASES = [
 ]
 
 
+@pytest.fixture(params=[-1, 0, 1, 2], ids=["auto", "gen1", "gen2_q32", "gen2_q64"])
+def attn_variant(request):
+    """Forces one of the MFMA attention kernels (applies to bf16, head width 64, transposed v; other calls are unaffected)."""
+    B.check(lib.ad_tune_attention(request.param))
+    yield request.param
+    B.check(lib.ad_tune_attention(-1))
+
+
+ATT_CASES += [
+    # several 256-query blocks with a ragged tail, several key tiles with a ragged tail
+    (B.AD_BF16, 2, 600, 333, 2, 64, True), (B.AD_BF16, 1, 257, 64, 1, 64, True), (B.AD_BF16, 1, 31, 65, 2, 64, True),
+    (B.AD_BF16, 1, 1024, 1024, 1, 64, True), (B.AD_BF16, 2, 96, 128, 1, 64, True),
+]
+
+
 @pytest.mark.parametrize("case", ATT_CASES, ids=[f"{'bf16' if c[0] else 'f32'}_l{c[2]}_lk{c[3]}_h{c[4]}_d{c[5]}_{'vt' if c[6] else 'v'}" for c in ATT_CASES])
-def test_attention(case):
+def test_attention(case, attn_variant):
     dtype, bsz, l, lk, heads, d, tr = case
+    if attn_variant >= 0 and not (dtype == B.AD_BF16 and d == 64 and tr):
+        pytest.skip("the knob only selects among the bf16 MFMA kernels")
     c = heads * d
     q, k, v = (quantize(SI.make_array(s, sd), dtype) for s, sd in (((bsz, l, c), 61), ((bsz, lk, c), 62), ((bsz, lk, c), 63)))
     got = run_attention(dtype, q, k, v, heads, tr)
-    assert_kernel_close(got, P.attention(q, k, v, heads), dtype)
+    q = mfma2_contract(q, d, attn_variant, dtype, tr, lk)
+    # the probabilities are rounded to bf16 and the result is an average of v rows: its rms is well below that of the
+    # v entries the errors are proportional to
+    assert_kernel_close(got, P.attention(q, k, v, heads), dtype, c=4.0)
 
 
 @pytest.mark.parametrize("dtype,tr", [(B.AD_F32, False), (B.AD_BF16, True)])
-def test_attention_peaky_softmax(dtype, tr):
+def test_attention_peaky_softmax(dtype, tr, attn_variant):
     """Scores far from uniform (scaled q, k) so that a mistake in the running max / rescaling shows."""
     bsz, l, lk, heads, d = 1, 96, 200, 2, 64
     c = heads * d
@@ -291,10 +327,34 @@ def test_attention_peaky_softmax(dtype, tr):
     # put the dominant key of some queries in the last tile so that the maximum moves late
     k[0, lk - 1] = q[0, 5] * 0.5
     got = run_attention(dtype, q, k, v, heads, tr)
-    ref = P.attention(q, k, v, heads)
-    assert_kernel_close(got, ref, dtype)
+    ref = P.attention(mfma2_contract(q, d, attn_variant, dtype, tr, lk), k, v, heads)
+    assert_kernel_close(got, ref, dtype, c=4.0)
     pmax = P.softmax_rows(q[0, :, :d] @ k[0, :, :d].T / math.sqrt(d)).max(axis=1)
     assert np.median(pmax) > 0.5
+
+
+@pytest.mark.parametrize("lk", [640, 700])
+def test_attention_rising_and_falling_maximum(lk, attn_variant):
+    """Scores that keep growing from key tile to key tile (the reference maximum has to move again and again, by
+    more and by less than the slack the lazy maximum allows), then collapse far below it; one query row is all zeros."""
+    dtype, l, d = B.AD_BF16, 300, 64
+    rng = np.random.default_rng(77)
+    base = rng.standard_normal((l, d)).astype(np.float32)
+    q = quantize(base[None] * 2.0, dtype)
+    q[0, 7] = 0.0
+    k = rng.standard_normal((1, lk, d)).astype(np.float32) * 0.3
+    ramp = np.concatenate([np.linspace(0.0, 3.0, lk // 2), np.linspace(3.0, -3.0, lk - lk // 2)]).astype(np.float32)
+    k[0] += ramp[:, None] * np.sign(base[rng.integers(0, l, lk)])          # every key lines up with some query, more and more
+    k = quantize(k, dtype)
+    v = quantize(SI.make_array((1, lk, d), 75), dtype)
+    got = run_attention(dtype, q, k, v, 1, True)
+    ref = P.attention(mfma2_contract(q, d, attn_variant, dtype, True, lk), k, v, 1)
+    assert_kernel_close(got, ref, dtype, c=4.0)
+    sc = q[0] @ k[0].T / math.sqrt(d) * math.log2(math.e)
+    tile_max = np.stack([sc[:, t:t + 32].max(axis=1) for t in range(0, lk, 32)], 1)
+    run_max = np.maximum.accumulate(tile_max, axis=1)
+    jumps = np.diff(run_max, axis=1)
+    assert (jumps > 8).any() and ((jumps > 0) & (jumps < 8)).any()          # both kinds of moves occur
 
 
 # ---------------------------------------------------------------------------------------------------
