@@ -31,6 +31,9 @@ MEASURED_TRAFFIC = {"sd21_768": {
     "linear_rows": 5868024, "gn_small": 3070976}}
 
 
+TRAFFIC_SOURCE = "not measured in this run: FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this file, profiles/bench_sd21_768_all_kernels.md"
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -53,8 +56,12 @@ def main():
     ap.add_argument("--refine", type=int, default=1, help="with --cuts auto: refine the time-balanced split by timing whole rounds of neighbouring splits")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams for the timed region (0 = one per concurrent evaluation)")
     ap.add_argument("--graphs", type=int, default=1, help="1 (default): replay full asynchronous rounds from HIP graphs; 0: launch every kernel directly")
-    ap.add_argument("--cuts", default="auto", help="partition of the units into components: 'auto' (default: balanced by unit times measured on this GPU "
-                    "before the timed region), 'flops' (FLOP-balanced, the library default) or N-1 comma-separated first units of components 2..N")
+    ap.add_argument("--cuts", default="flops", help="partition of the units into components for the headline value: 'flops' (default: FLOP-balanced, the "
+                    "library default and what the metric configuration names), 'auto' (balanced by unit times measured on this GPU before the "
+                    "timed region) or N-1 comma-separated first units of components 2..N")
+    ap.add_argument("--tuned", type=int, default=1, help="1 (default, with --cuts flops): after the headline measurement also time the partition balanced by "
+                    "measured unit times and refined by whole-round timings, and report it as tuned_partition")
+    ap.add_argument("--repeats", type=int, default=10, help="the timed region of --steps rounds is repeated this many times; value is the median")
     ap.add_argument("--wrap", type=int, default=0, help="1: wrapped segmentation (first and last segment in one component; stride 1, FLOP-balanced cuts)")
     ap.add_argument("--tile", type=int, default=-1, help="GEMM kernel family override for measurements (ad_tune_conv_tile); -1 = automatic")
     ap.add_argument("--order", type=int, default=-1, help="GEMM workgroup order override for measurements (ad_tune_conv_order); -1 = automatic")
@@ -107,7 +114,6 @@ def main():
     m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts, wrap=bool(args.wrap))
     m.allocate(dev)
     m.load_weights(wts)
-    del wts
     log(f"model ready in {time.time() - t0:.1f}s; arenas {[round(b / 2**20) for b in m.device_bytes()]} MiB")
     tdt = torch.bfloat16 if dtype == ad.AD_BF16 else torch.float32
     frames = d.get("frames", 0)     # video model: one latent per frame, one text embedding for all frames, no guidance
@@ -119,48 +125,55 @@ def main():
     units = m.units()
     flops_step = float(sum(u.flops for u in units))
     sampler = ad.AD_DDIM if r["sampler"] == "ddim" else ad.AD_EULER
-    # rounds: w sequential warm-up steps of the method, then W untimed and K timed asynchronous rounds
-    rounds_needed = w + (W + K)
-    T = w + max(W + K, min(K, 10) + 2) * S
-    if T > 1000:
-        raise SystemExit("steps too large for one schedule (T <= 1000)")
-
-    def fresh(n_streams):
-        m.reset(T, sampler=sampler, cfg_scale=r["cfg_scale"])
-        lat = noise.clone()
-        ss = [torch.cuda.Stream(device=dev) for _ in range(n_streams)]
-        torch.cuda.synchronize()
-        return lat, ss
-
     n_par = N + S - 1
     n_streams = args.streams if args.streams > 0 else n_par
+    R = max(1, args.repeats)
+    T = w + max(W + K * R, min(K, 10) + 2) * S
+    if T > 1000:
+        R = max(1, (1000 // S - w - W) // K)
+        T = w + max(W + K * R, min(K, 10) + 2) * S
+        log(f"repeats reduced to {R} so that one schedule (T <= 1000) holds every timed round")
+
+    def timed_rounds(model, graphs, streams, k, reps):
+        """w warm-up rounds of the method and W untimed rounds, then reps x (exactly k rounds bracketed by device synchronisation).
+        Returns the list of seconds per repetition and the host enqueue time of the first one."""
+        model.set_graph_mode(bool(graphs))
+        model.reset(T, sampler=sampler, cfg_scale=r["cfg_scale"])
+        lat = noise.clone()
+        ss = [torch.cuda.Stream(device=dev) for _ in range(streams)]
+        torch.cuda.synchronize()
+        run_rounds(model, lat, text, ss, w + W)
+        secs, host = [], None
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            run_rounds(model, lat, text, ss, k)
+            th = time.perf_counter() - t1
+            torch.cuda.synchronize()
+            secs.append(time.perf_counter() - t1)
+            host = th if host is None else host
+        assert bool(torch.isfinite(lat).all()), "latent is not finite"
+        return secs, host, lat, ss
+
     # ---- timed region: concurrent components -----------------------------------------------------
-    m.set_graph_mode(bool(args.graphs))
-    lat, ss = fresh(n_streams)
-    run_rounds(m, lat, text, ss, w + W)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    run_rounds(m, lat, text, ss, K)
-    t_host = time.perf_counter() - t1          # time the host needed to enqueue the K rounds
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    sec = t2 - t1
+    secs, t_host, lat, ss = timed_rounds(m, args.graphs, n_streams, K, R)
+    sec = float(np.median(secs))
     steps_per_s = K * S / sec
     ms_per_step = sec / (K * S) * 1e3
-    assert bool(torch.isfinite(lat).all()), "latent is not finite"
-    log(f"concurrent ({n_streams} streams): {steps_per_s:.2f} steps/s, {ms_per_step:.3f} ms/step")
-    # ---- the same rounds on one stream (sequential UNet with the same kernels) ---------------------
+    spread = dict(repeats=R, timed_seconds=round(float(sum(secs)), 3), ms_per_step_min=round(min(secs) / (K * S) * 1e3, 4),
+                  ms_per_step_max=round(max(secs) / (K * S) * 1e3, 4))
+    log(f"concurrent ({n_streams} streams): {steps_per_s:.2f} steps/s, {ms_per_step:.3f} ms/step (median of {R} x {K} rounds, "
+        f"{spread['ms_per_step_min']:.3f} .. {spread['ms_per_step_max']:.3f})")
+    # ---- the same rounds on one stream (sequential UNet with the same kernels): graph replay and direct launches ----
     K2 = min(K, 10)
+    R2 = min(R, 5)
+    seq = {}
+    for mode, graphs in (("graph_replay", 1), ("direct_launches", 0)):
+        secs2, _, lat, ss = timed_rounds(m, graphs, 1, K2, R2)
+        seq[mode] = K2 * S / float(np.median(secs2))
+    seq_steps_per_s = max(seq.values())
+    log("one stream: " + ", ".join(f"{k} {v:.2f} steps/s" for k, v in seq.items()))
     m.set_graph_mode(False)
-    lat, ss = fresh(1)
-    run_rounds(m, lat, text, ss, w + 1)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    run_rounds(m, lat, text, ss, K2)
-    torch.cuda.synchronize()
-    seq_sec = time.perf_counter() - t1
-    seq_steps_per_s = K2 * S / seq_sec
-    log(f"one stream: {seq_steps_per_s:.2f} steps/s")
     # ---- per-kernel durations: HIP events around every launch of one more round, one stream ----------
     m.profile(True)
     run_rounds(m, lat, text, ss, 1)
@@ -195,14 +208,16 @@ def main():
     if da["flops"] > 0:
         ach = da["flops"] / (da["ms"] * 1e-3) / 1e12
         roofline = dict(kernel=dname, bound="mfma", achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=MEASURED_TRAFFIC.get(args.config, {}).get(dname), launches=da["calls"],
+                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=MEASURED_TRAFFIC.get(args.config, {}).get(dname), traffic_source=TRAFFIC_SOURCE,
+                        launches=da["calls"],
                         avg_launch_us=round(da["ms"] / da["calls"] * 1e3, 2),
                         flops_per_launch=round(da["flops"] / da["calls"]),
                         algorithmic_bytes_per_launch=round(da["bytes"] / da["calls"]))
     else:
         ach = da["bytes"] / (da["ms"] * 1e-3) / 1e9
         roofline = dict(kernel=dname, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=MEASURED_TRAFFIC.get(args.config, {}).get(dname), launches=da["calls"],
+                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=MEASURED_TRAFFIC.get(args.config, {}).get(dname), traffic_source=TRAFFIC_SOURCE,
+                        launches=da["calls"],
                         avg_launch_us=round(da["ms"] / da["calls"] * 1e3, 2),
                         bytes_per_launch=round(da["bytes"] / da["calls"]))
     # ---- the sampler kernel at a bandwidth-bound size (same kernel, synthetic size) ---------------------
@@ -222,6 +237,23 @@ def main():
     samp_ms = ev[0].elapsed_time(ev[1]) / 2
     samp_gbs = n_big * 16 / (samp_ms * 1e-3) / 1e9
     del xb, eb
+    # ---- GroupNorm + SiLU (statistics pass + apply pass) at a bandwidth-bound size: 2^26 bf16 elements ----------
+    gb, ghw, gc = 2, 512 * 256, 256
+    gx = torch.randn(gb, ghw, gc, device=dev).to(torch.bfloat16)
+    gy = torch.empty_like(gx)
+    gg, gbt = torch.ones(gc, device=dev), torch.zeros(gc, device=dev)
+    gscr = torch.zeros(ad.lib.ad_groupnorm_scratch_bytes(gb, ghw, gc), dtype=torch.uint8, device=dev)
+    vp = lambda t: C.c_void_p(t.data_ptr())
+    for it in range(3):
+        if it == 1:
+            ev[0].record(s0)
+        ad.binding.check(ad.lib.ad_groupnorm_forward(ad.AD_BF16, vp(gx), None, gc, 0, gb, ghw, 32, vp(gg), vp(gbt), 1e-5, 1, vp(gy), vp(gscr),
+                                                     C.c_void_p(s0.cuda_stream)))
+    ev[1].record(s0)
+    torch.cuda.synchronize()
+    gn_ms = ev[0].elapsed_time(ev[1]) / 2
+    gn_gbs = gx.numel() * 4 / (gn_ms * 1e-3) / 1e9
+    del gx, gy, gscr
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -252,10 +284,38 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count()
-        cpu = dict(value=round(1.0 / (cpu_sec * flops_step / sample_flops), 6), unit="steps/s", cores=int(cores), kind="oracle",
+        cpu = dict(value=round(1.0 / (cpu_sec * flops_step / sample_flops), 6), unit="steps/s", cores=int(cores),
+                   kind=f"oracle: NumPy fp64, its matmul steps run in the BLAS library on {int(cores)} threads; a quarter of a step timed, scaled by FLOPs",
                    sample=f"units {ounits[0].name}..{ounits[last].name} of one UNet forward ({sample_flops / 1e9:.0f} of "
                           f"{flops_step / 1e9:.0f} GFLOP) in {cpu_sec:.1f}s, scaled by FLOPs to a full step",
                    sample_seconds=round(cpu_sec, 2))
+    # ---- the same measurement with the partition balanced by measured unit times (profile-guided; a study, not the headline) ----
+    tuned = None
+    if args.tuned and args.cuts == "flops" and not args.wrap and N > 1:
+        from paper_2406_06911_amd.tuning import refine_cuts, time_balanced_cuts
+        headline_cuts = [a for a, _ in m.partition()]
+        m.close()
+        torch.cuda.empty_cache()
+        t1 = time.time()
+        tcuts, unit_us = time_balanced_cuts(d, N, dtype, wts, dev)
+        if args.refine:
+            tcuts, _, tried = refine_cuts(d, N, w, S, dtype, wts, tcuts, dev)
+        tune_s = time.time() - t1
+        m2 = ad.AsyncDiff(d, N, w, S, dtype, cuts=tcuts)
+        m2.allocate(dev)
+        m2.load_weights(wts)
+        secs_t, _, _, _ = timed_rounds(m2, args.graphs, n_streams, K, R)
+        sec_t = float(np.median(secs_t))
+        tuned = dict(component_first_units=[a for a, _ in m2.partition()], steps_per_s=round(K * S / sec_t, 3),
+                     ms_per_step=round(sec_t / (K * S) * 1e3, 4), over_flops_partition=round(sec / sec_t, 4),
+                     tuning_seconds=round(tune_s, 1),
+                     note="units timed alone on this GPU, split by the library's rule, refined by timing whole rounds of neighbouring splits")
+        log(f"tuned partition {tuned['component_first_units']} (found in {tune_s:.0f}s): {tuned['steps_per_s']:.2f} steps/s vs {steps_per_s:.2f} with FLOP cuts {headline_cuts}")
+        part_units = headline_cuts
+        m2.close()
+    else:
+        part_units = [a for a, _ in m.partition()]
+    del wts
     out = {
         "metric": "UNet denoising steps/sec, 768px SD2.1-shape N=4, 1 GPU; % bf16 MFMA peak" if args.config == "sd21_768" and not args.wrap
                   else f"UNet denoising steps/sec, {args.config}, N={N}{' wrapped' if args.wrap else ''}, 1 GPU",
@@ -265,16 +325,21 @@ def main():
         "config": {"workload": f"{args.config}: latent {d['latent_channels']}x{d['height']}x{d['width']}, batch {d['batch']} ({'frames' if frames else 'guidance'}), "
                                f"N={N} components on {n_streams} HIP streams, warm-up {w}, stride {S}, {r['sampler']}",
                    "n_components": N, "stride": S, "streams": n_streams, "hip_graphs": bool(args.graphs), "partition": ("wrapped, " if args.wrap else "") + (("flops" if args.wrap else args.cuts) if args.cuts in ("auto", "flops") else "given"),
-                   "component_first_units": [a for a, _ in m.partition()], "flops_per_step": flops_step},
+                   "component_first_units": part_units, "flops_per_step": flops_step},
+        "timing": spread,
         "component_evals_per_s": round(steps_per_s / S * n_par, 2),
         "sequential_steps_per_s": round(seq_steps_per_s, 3),
+        "sequential_one_stream": {k: round(v, 3) for k, v in seq.items()},
         "concurrent_over_sequential": round(steps_per_s / seq_steps_per_s, 4),
+        "tuned_partition": tuned,
         "host_enqueue_ms_per_step": round(t_host / (K * S) * 1e3, 3),
         "mfma_frac_whole_step": round(flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline,
         "kernels": kernels,
         "sampler_large": {"n": n_big, "gbs": round(samp_gbs, 1), "frac_hbm_peak": round(samp_gbs / PEAK_HBM_GBS, 4),
                           "note": "same kernel on 2^26 latent elements (synthetic size); 16 bytes per element"},
+        "gn_large": {"elements": gb * ghw * gc, "gbs": round(gn_gbs, 1), "frac_hbm_peak": round(gn_gbs / PEAK_HBM_GBS, 4), "us": round(gn_ms * 1e3, 1),
+                     "note": "GroupNorm(32)+SiLU, statistics pass + apply pass, bf16 [2][131072][256] (synthetic size); 4 bytes per element"},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

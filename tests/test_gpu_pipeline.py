@@ -17,11 +17,11 @@ pytestmark = pytest.mark.gpu
 class Case:
     """A model instance on the GPU plus the oracle pipeline over the same seeded inputs."""
 
-    def __init__(self, name, dtype, N, w, S, T, sampler="ddim", cfg_scale=1.0, std=0.02, time_shift=False, cuts=None, wrap=False):
+    def __init__(self, name, dtype, N, w, S, T, sampler="ddim", cfg_scale=1.0, std=0.02, time_shift=False, cuts=None, wrap=False, wts=None):
         d = CONFIGS[name]
         self.d, self.dtype, self.N, self.S, self.T = d, dtype, N, S, T
         ocfg = UNetConfig(**d)
-        self.wts = SI.make_weights(weight_manifest(ocfg), std=std, bf16_exact=(dtype == B.AD_BF16))
+        self.wts = wts if wts is not None else SI.make_weights(weight_manifest(ocfg), std=std, bf16_exact=(dtype == B.AD_BF16))
         frames = d.get("frames", 0)
         # video model: one latent per frame, one text embedding for all frames
         self.noise = (SI.make_video_latent(frames, d["latent_channels"], d["height"], d["width"]) if frames
@@ -712,3 +712,94 @@ def test_full_size_sdxl_first_units_match_oracle():
         err = rel_l2(nhwc_to_nchw(host(t)), ref[u])
         assert err < 2e-2, f"unit {u}: rel L2 {err:.3e}"
     m.close()
+
+
+# ---------------------------------------------------------------------------------------------------
+# Asynchronous rounds and the deep / wide units at full size against the oracle
+# ---------------------------------------------------------------------------------------------------
+def test_full_size_async_round_components_match_oracle(full_size_weights):
+    """The metric configuration at its real shape with the FLOP-balanced partition of four components: the last
+    warm-up step and the first asynchronous round, every component evaluation against the oracle's evaluation of the
+    same schedule row.  Each evaluation is fed the oracle's stored tensors of the round before (rounded to bf16), so
+    the asynchronous round runs on genuinely stale inputs of real size: 2 x 4 component evaluations, two UNet
+    forwards in fp64 on the oracle side.  (One warm-up step instead of the configuration's three: the warm-up steps
+    are the same computation, and step w - 1 is the one that seeds the asynchronous phase.)"""
+    case = Case("sd21_768", B.AD_BF16, 4, 1, 1, 2, cfg_scale=7.5, wts=full_size_weights)
+    assert [a for a, _ in case.m.partition()] == [0, 10, 31, 40]          # conv_in.. | d1.ds.. | u2.us.. | u0.0.tfm..out
+    log = []
+    print("oracle: two steps of four components", flush=True)
+    worst = run_components_isolated(case, log)
+    rounds = sorted({r for r, _, _, _ in log})
+    assert rounds == [0, 1] and sorted({c for _, c, _, _ in log}) == [1, 2, 3, 4]
+    print(f"full-size warm-up step and first asynchronous round: worst per-tensor rel L2 {worst:.3e}", flush=True)
+    for r in rounds:
+        print("  round", r, " ".join(f"c{c}/u{u}:{e:.1e}" for rr, c, u, e in log if rr == r), flush=True)
+    case.m.close()
+
+
+def _single_unit_against_oracle(name, unit, N, cuts, comp, T, sampler, seed):
+    """One unit of a full-size model as a component of its own: seeded N(0,1) hidden state in, oracle's run_units on the
+    same (bf16-rounded) input and the weights of that unit."""
+    from oracle.unet import build_units, run_units
+    d = CONFIGS[name]
+    ocfg = UNetConfig(**d)
+    units = build_units(ocfg)
+    u = units[unit]
+    print("drawing weights", flush=True)
+    wts = SI.make_weights(weight_manifest(ocfg), bf16_exact=True)
+    prefixes = (u.name + ".", "time.", "pool.")
+    sub = {k: np.asarray(v, np.float64) for k, v in wts.items() if k.startswith(prefixes)}
+    frames = d.get("frames", 0)
+    text = quantize(SI.make_text(1 if frames else d["batch"], d["ctx_len"], d["ctx_dim"]), B.AD_BF16)
+    pooled = SI.make_pooled(d["batch"], d["pooled_dim"]) if d["pooled_dim"] else None
+    x = quantize(SI.make_array((d["batch"], u.c_in, u.h_in, u.w_in), seed), B.AD_BF16)
+    taus = __import__("oracle.sampler", fromlist=["timesteps"]).timesteps(T)
+    step = 3
+    print(f"oracle: unit {u.name}", flush=True)
+    ref = run_units(ocfg, units, unit, unit, sub, {unit - 1: x.astype(np.float64)}, taus[step], text.astype(np.float64), pooled)[unit]
+    print("gpu", flush=True)
+    m = ad.AsyncDiff(d, N, 1, 1, B.AD_BF16, cuts=cuts)
+    m.allocate(DEV)
+    m.load_weights(wts)
+    del wts
+    m.reset(T, sampler=sampler)
+    assert m.partition()[comp - 1] == (unit, unit)
+    ins, outs = m.component_io(comp)
+    assert ins == [unit - 1] and outs == [unit]
+    (b, h, w, c), _ = m.tensor_shape(unit)
+    out = torch.full((b, h, w, c), float("nan"), device=DEV, dtype=torch.bfloat16)
+    m.component_forward(comp, [dev(nchw_to_nhwc(x), B.AD_BF16)], step, dev(text, B.AD_BF16), [out], torch.cuda.current_stream(),
+                        pooled=dev_f32(pooled) if pooled is not None else None)
+    torch.cuda.synchronize()
+    got = nhwc_to_nchw(host(out))
+    m.close()
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    err = rel_l2(got, ref)
+    # the residual path passes x through unchanged: also compare what the unit adds
+    err_delta = rel_l2(got - x, ref - x)
+    print(f"{name} unit {u.name}: rel L2 {err:.3e}, of the unit's own contribution {err_delta:.3e}", flush=True)
+    assert err < 2e-2
+    return err, err_delta
+
+
+def test_full_size_sdxl_depth10_transformer_matches_oracle():
+    """The deepest transformer of the SDXL-shaped model at its real width: 1280 channels, 32x32 = 1024 tokens, 20 heads,
+    ten layers (self-attention, cross-attention to the 77x2048 text embedding, GEGLU feed-forward each)."""
+    from oracle.unet import build_units
+    units = build_units(UNetConfig(**CONFIGS["sdxl_1024"]))
+    unit = 10
+    assert (units[unit].name, units[unit].depth, units[unit].c_in, units[unit].h_in) == ("d2.0.tfm", 10, 1280, 32)
+    err, err_delta = _single_unit_against_oracle("sdxl_1024", unit, 3, [unit, unit + 1], 2, 50, B.AD_EULER, 9100)
+    assert err_delta < 5e-2          # ten layers of three residual branches each, every one rounded to bf16
+
+
+def test_full_size_video_level1_transformer_and_temporal_layer_match_oracle():
+    """The level-1 transformer of the video model at full width and its temporal layer: 16 frames of 32x32 tokens,
+    640 channels; spatial self / cross attention per frame, then attention over the 16 frames at each of the 1024
+    positions - every output element against the oracle."""
+    from oracle.unet import build_units
+    units = build_units(UNetConfig(**CONFIGS["video_16f"]))
+    unit = 7
+    assert (units[unit].name, units[unit].c_in, units[unit].h_in) == ("d1.0.tfm", 640, 32)
+    err, err_delta = _single_unit_against_oracle("video_16f", unit, 3, [unit, unit + 1], 2, 25, B.AD_DDIM, 9200)
+    assert err_delta < 3e-2
