@@ -281,8 +281,10 @@ ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0,
 /* Tuning knob for measurements: forces the block tile of ad_conv_forward and of every convolution / linear
  * layer of the process (1: 128x128 register-staged tiles, 3: 64x64 register-staged tiles, 4: 128x128 two-stage
  * LDS-DMA, 5: 128x128 three-stage LDS-DMA, 6: 256x128 three-stage LDS-DMA, 7: 64x64 three-stage LDS-DMA,
- * -1: automatic choice, the default).  4 to 7 apply to bf16 GEMMs with a row-major, GEGLU or fused q/k/v output; other calls keep the automatic
- * choice.  Results are the same up to rounding order. */
+ * 8 / 9: as 5 / 6, with 3x3 stride-1 convolutions on the halo-staged kernel (128 / 256 output positions per workgroup),
+ * -1: automatic choice, the default (3x3 convolutions on the per-tap kernels 5 / 6: measured faster than 8 / 9 on the SD-sized models)).
+ * 4 to 9 apply to bf16 GEMMs with a row-major, GEGLU or fused q/k/v output; other calls keep the automatic
+ * choice.  Results are the same up to rounding order.  Process-global, not thread-safe: for tests and measurements. */
 ad_status ad_tune_conv_tile(int tile);
 /* Tuning knob for measurements: order in which the workgroups of a GEMM walk its output tiles.  0: an XCD owns a
  * run of row tiles and every column tile of them (the weights are fetched into every L2); 1: an XCD owns a run of

@@ -831,6 +831,217 @@ static ad_status run_igemm_p3(const IgemmParams& p0, const char* name, hipStream
   return AD_OK;
 }
 
+// =================================================================================================
+// 3x3 convolution (stride 1) with the input staged in LDS as a halo tile, bf16.
+//
+// The implicit-GEMM kernels above fetch the A tile (BM output positions x 64 channels) once per tap: nine times the
+// same pixels, shifted, through the L2 -> LDS path that already limits them.  Here a workgroup stages, per chunk of
+// 64 input channels, every input pixel its BM output positions touch - the BM positions themselves plus one image
+// row and one pixel on either side, (BM + 2 W + 2) rows of 128 bytes - once, and runs the nine taps out of that
+// tile: tap (dy, dx) of output position m reads LDS row m - m0 + (W + 1) + dy W + dx.  Positions are linear over
+// the whole batch, so a tile may straddle image rows and samples; what a shifted index would pick up from the
+// neighbouring row or sample (or from beyond the tensor) is replaced by zeros by pointing the lane's fragment
+// address at a 128-byte zero block - one select per (lane, row block, tap), no work per element.  With a nearest-2x
+// upsampled input the staged pixels are the stored (half-resolution) ones and the row is computed from
+// ((y + dy) >> 1, (x + dx) >> 1).  Weights: one 128 x 64 tile per (tap, chunk) through a ring of NB stages.
+// The halo tile is double-buffered; the next chunk's tile is requested in eight slices, one per tap.
+// LDS traffic from L2 per k-tile: 16 KiB of weights + a ninth of the halo (about 6.4 KiB for BM = 256, W = 96)
+// instead of 16 + 32 KiB.
+// =================================================================================================
+struct HaloParams {
+  int hr;            // rows of the halo tile: BM + 2 Ws + 2 (+ slack of the upsampled mapping), rounded up to 32
+  int chunk_begin_stride;   // chunks per split (split-K over channel chunks), or all of them
+  FastDiv div_hw, div_w;    // output position -> (sample, y, x)
+};
+
+template <int BM, int NB, int MODE>
+__global__ __launch_bounds__(256) void k_conv3_halo(IgemmParams p, HaloParams hp) {
+  typedef bf16 T;
+  typedef bf16x8 V;
+  constexpr int BN = 128, WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
+  constexpr int BSTAGE = BN * kRowBytes, BG = BN / 32;          // weight tile, loads per wavefront and tile
+  constexpr int ASL = BM / 128;                                 // halo loads per wavefront and tap slice (8 slices cover the tile)
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wave_m = wave >> 1, wave_n = wave & 1;
+  const TileId tid3 = tile_of(p);
+  const int m0 = tid3.m_tile * BM, n0 = tid3.n_tile * BN;
+  const u32x4 rs0 = make_rsrc_words(p.src0, p.bytes0), rs1 = make_rsrc_words(p.src1, p.bytes1);
+  const u32x4 rsw = make_rsrc_words(p.w, p.bytes_w);
+  // LDS: [halo 0][halo 1][weights x NB][zero block]
+  const int abytes = hp.hr * kRowBytes;
+  char* const bbase = lds + 2 * abytes;
+  char* const zero = bbase + NB * BSTAGE;
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
+  if (tid < 8) *(V*)(zero + tid * 16) = V{};
+  const int nchunks = p.ctot / 64;
+  const int c_begin = tid3.split * hp.chunk_begin_stride;
+  const int c_end = min(nchunks, c_begin + hp.chunk_begin_stride);
+  const int nkt = (c_end - c_begin) * 9;
+  const int up = p.up, Ws = p.ws, W = p.win, H = p.hin;        // stored width, logical (convolved) size
+
+  // ---- which stored pixel heads the halo tile: the one tap (-1, -1) of the tile's first output position maps to
+  //      (clamped into the sample; everything before it in the same sample is not needed), minus nothing.
+  //      Stored linear index of logical (b, yy, xx): b Hs Ws + (yy >> up) Ws + (xx >> up).
+  int g_base;
+  {
+    const int b = (int)fast_div((unsigned)m0, hp.div_hw), r = m0 - b * p.hw_out;
+    const int y = (int)fast_div((unsigned)r, hp.div_w), x = r - y * W;
+    // plain input: tap (-1, -1) of the first position, m0 - W - 1 (no later position reaches further back).  Upsampled input:
+    // later positions of the tile may sit in the next logical row, which shares the stored row, at smaller x: start one
+    // pixel before the stored row of (y - 1) >> 1 (arithmetic shift: row -1 of the sample for y = 0)
+    g_base = b * p.hs * Ws + (up ? ((y - 1) >> 1) * Ws - 1 : (y - 1) * Ws + x - 1);
+  }
+  const int total_pix = p.M / p.hw_out * p.hs * Ws;                        // stored pixels of a source
+  // ---- loads: halo row group G = wave + 4 j covers rows 8 G .. 8 G + 7; this lane's row r8, chunk position lane & 7
+  const int r8 = lane >> 3;
+  const int scol = (lane & 7) ^ lds_swizzle(wave * 8 + r8);
+  const int na = hp.hr / 32;                                               // loads per wavefront and halo tile
+  auto issue_halo = [&](int chunk, int buf, int j0, int j1) {
+    const bool second = chunk * 64 >= p.c0;
+    u32x4 rs = second ? rs1 : rs0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) rs[e] = __builtin_amdgcn_readfirstlane(rs[e]);      // workgroup-uniform by construction
+    const unsigned cs = (unsigned)(second ? p.c1 : p.c0) * 2u;             // bytes per pixel of that source
+    const unsigned soff = __builtin_amdgcn_readfirstlane((unsigned)((second ? chunk * 64 - p.c0 : chunk * 64) * 2));
+    for (int j = j0; j < j1 && j < na; ++j) {
+      const int g = g_base + (wave + 4 * j) * 8 + r8;
+      const unsigned vo = (g >= 0 && g < total_pix) ? (unsigned)g * cs + (unsigned)scol * 16u : kOob;
+      dma_load16(rs, vo, soff, __builtin_amdgcn_readfirstlane(lds_base + buf * abytes + (wave + 4 * j) * 1024));
+    }
+  };
+  unsigned b_off[BG];
+#pragma unroll
+  for (int i = 0; i < BG; ++i) b_off[i] = (unsigned)((n0 + (4 * i + wave) * 8 + r8) * p.Kp + scol * 8) * 2;
+  auto issue_b = [&](int chunk, int tap, int stage) {
+    const unsigned soff = __builtin_amdgcn_readfirstlane((unsigned)((tap * p.ctot + chunk * 64) * 2));
+#pragma unroll
+    for (int i = 0; i < BG; ++i)
+      dma_load16(rsw, b_off[i], soff, __builtin_amdgcn_readfirstlane(lds_base + 2 * abytes + stage * BSTAGE + (4 * i + wave) * 1024));
+  };
+
+  // ---- this lane's output positions (one per 32-row block of the wavefront's tile): sample base, y, x
+  int pb_[TM], py[TM], px[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + wave_m * WTM + i * 32 + l32;
+    if (m < p.M) {
+      const int b = (int)fast_div((unsigned)m, hp.div_hw), r = m - b * p.hw_out;
+      py[i] = (int)fast_div((unsigned)r, hp.div_w);
+      px[i] = r - py[i] * W;
+      pb_[i] = b * p.hs * Ws - g_base;
+    } else {
+      py[i] = -4; px[i] = -4; pb_[i] = 0;          // every tap is out of the image
+    }
+  }
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // prologue: the first halo tile, then the first NB - 1 weight tiles
+  if (nkt > 0) issue_halo(c_begin, 0, 0, na);
+#pragma unroll
+  for (int t = 0; t < NB - 1; ++t)
+    if (t < nkt) issue_b(c_begin + t / 9, t % 9, t);
+
+  const int b_row = (wave_n * WTN + l32) * kRowBytes;
+  const int x7 = lds_swizzle(l32);
+  const char* const zero_rd = zero + half * 16;
+  int kt = 0, bstage = 0;
+  for (int chunk = c_begin; chunk < c_end; ++chunk) {
+    const int abuf = (chunk - c_begin) & 1;
+    const char* const As = lds + abuf * abytes;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap, ++kt) {
+      // weight tile kt has landed once at most the NB - 2 tiles requested after it are outstanding; the halo slice
+      // requested one tap ago is older than those and is waited for with it
+      if (NB == 3 && kt + 1 < nkt) wait_vmcnt<BG>(); else wait_vmcnt<0>();
+      __syncthreads();       // tile kt (and at tap 0 the chunk's halo) is complete for everybody; everybody is done with tile kt - 1
+      if (tap < 8 && chunk + 1 < c_end) issue_halo(chunk + 1, abuf ^ 1, tap * ASL * 2, (tap + 1) * ASL * 2);
+      if (kt + NB - 1 < nkt) {
+        const int t2 = kt + NB - 1;
+        int st = bstage + NB - 1;
+        if (st >= NB) st -= NB;
+        issue_b(c_begin + t2 / 9, t2 % 9, st);
+      }
+      // fragment addresses of this tap: halo row of (y + dy, x + dx), or the zero block
+      const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+      const char* a_rd[TM];
+      int a_sw[TM];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int yy = py[i] + dy, xx = px[i] + dx;
+        const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
+        const int row = pb_[i] + (yy >> up) * Ws + (xx >> up);
+        a_rd[i] = ok ? As + row * kRowBytes + ((half ^ (lds_swizzle(row) & 1)) << 4) : zero_rd;
+        a_sw[i] = ok ? (lds_swizzle(row) & 6) : 0;
+      }
+      const char* const Bs = bbase + bstage * BSTAGE + b_row;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        V af[TM], bf[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[i] = *(const V*)(a_rd[i] + (((2 * ks) ^ a_sw[i]) << 4));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bf[j] = *(const V*)(Bs + j * 32 * kRowBytes + (((ks * 2 + half) ^ x7) << 4));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+      }
+      if (++bstage == NB) bstage = 0;
+    }
+  }
+  wait_vmcnt<0>();
+  __syncthreads();     // every wavefront is done reading the tiles: LDS can be reused by the epilogue
+  igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch), tid3.split);
+}
+
+// Rows of the halo tile for a BM-position tile: the stored pixels between the one tap (-1, -1) of the first position
+// maps to and the one tap (+1, +1) of the last position maps to, at most; rounded up to whole 32-row load rounds.
+static int halo_rows(int bm, int ws, int up) {
+  if (!up) return round_up(bm + 2 * ws + 2, 32);
+  // upsampled: bm consecutive logical positions touch at most d + 1 logical rows, d = (bm + W - 2) / W, hence with the
+  // taps logical rows l0 - 1 .. l0 + d + 1, whose stored rows (l >> 1) number at most (d + 3) / 2 + 1; plus the pixel before
+  const int w = 2 * ws, d = (bm + w - 2) / w;
+  return round_up(((d + 3) / 2 + 1) * ws + 1, 32);
+}
+static size_t halo_lds_bytes(int bm, int nb, int ws, int up) {
+  return (size_t)2 * halo_rows(bm, ws, up) * kRowBytes + (size_t)nb * 128 * kRowBytes + 128;
+}
+constexpr size_t kLdsLimit = 160 * 1024;
+
+template <int BM, int NB, int MODE>
+static ad_status run_conv3_halo(const IgemmParams& p0, int splits, const char* name, hipStream_t s) {
+  IgemmParams p = p0;
+  p.tiles_n = (p.N + 127) / 128;
+  p.tiles_m = (p.M + BM - 1) / BM;
+  HaloParams hp;
+  hp.hr = halo_rows(BM, p.ws, p.up);
+  const int nchunks = p.ctot / 64;
+  hp.chunk_begin_stride = splits > 1 ? (nchunks + splits - 1) / splits : nchunks;
+  hp.div_hw = p.div_hw; hp.div_w = p.div_w;
+  const int real_splits = (nchunks + hp.chunk_begin_stride - 1) / hp.chunk_begin_stride;
+  const size_t lds_bytes = std::max(halo_lds_bytes(BM, NB, p.ws, p.up), (size_t)4 * (BM / 2) * kPitch);
+  if (lds_bytes > kLdsLimit || hp.hr / 32 > 16 * (BM / 128)) AD_FAIL(AD_ERR_INVALID, "conv (halo): tile does not fit");
+  static bool attr_set = false;
+  if (!attr_set) {
+    AD_HIP(hipFuncSetAttribute((const void*)k_conv3_halo<BM, NB, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit));
+    attr_set = true;
+  }
+  const double in_bytes = (double)p.M * p.ctot * 2 / (p.up ? 4 : 1);
+  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * 2 + (double)p.M * p.N * 2, s, p.M, p.N, p.Kp);
+  hipLaunchKernelGGL((k_conv3_halo<BM, NB, MODE>), dim3(p.tiles_n * p.tiles_m, real_splits), dim3(256), lds_bytes, s, p, hp);
+  AD_HIP(hipGetLastError());
+  return AD_OK;
+}
+
 template <typename T, int MODE, int NSTAGE>
 static ad_status run_igemm_dma(const IgemmParams& p0, const char* name, hipStream_t s) {
   IgemmParams p = p0;
@@ -912,7 +1123,7 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
 // Tile shapes.  The register-staged kernels (64x64, 128x128) serve fp32 and the transposed epilogues; bf16
 // GEMMs with a row-major, GEGLU, fused q/k/v or split-K epilogue take the three-stage LDS-DMA kernel with a
 // 128x128 or a 256x128 tile.
-enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_DMA2_128 = 4, TILE_P3_128 = 5, TILE_P3_256 = 6, TILE_P3_64 = 7, TILE_AUTO = -1 };
+enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_DMA2_128 = 4, TILE_P3_128 = 5, TILE_P3_256 = 6, TILE_P3_64 = 7, TILE_HALO_128 = 8, TILE_HALO_256 = 9, TILE_AUTO = -1 };
 static int g_tile_override = TILE_AUTO;
 static int g_order_override = -1;
 
@@ -954,6 +1165,8 @@ static ConvPlan choose_plan(int dtype, long long m, int n, int ktiles, int out_m
   const bool geglu = out_mode == OUT_GEGLU;   // needs a value and a gate tile in the same wavefront
   const bool dma = dma_capable(dtype, out_mode);
   int forced = g_tile_override;
+  if (forced == TILE_HALO_128) forced = TILE_P3_128;      // the halo kernels share the tile shapes (and the split-K planning) of these
+  if (forced == TILE_HALO_256) forced = TILE_P3_256;
   if (forced == TILE_P3_128 || forced == TILE_P3_256 || forced == TILE_DMA2_128 || forced == TILE_P3_64) {
     if (!dma || (forced == TILE_P3_64 && geglu)) forced = TILE_AUTO;
   }
@@ -1073,7 +1286,33 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
     case OUT_PARTIAL: st = run_igemm_p3<bf16, BM_, 128, OUT_PARTIAL>(p, "igemm_bf16_" #BM_ "x128_p3_splitk", s); break; \
     default: break;                                                                                                   \
   }
-  if (tile == TILE_P3_128) {
+  // 3x3, stride 1: the halo-staged kernel, on request (TILE_HALO_*) and when its tiles fit into LDS.  It moves less than
+  // half the bytes from L2 into LDS per k-tile, but on the convolutions of the SD-sized models it runs at 0.70-0.85 of the
+  // per-tap three-stage kernel (its k-loop has neither that kernel's fragment prefetch across the barrier nor its third
+  // weight stage at 256 positions): the automatic choice keeps the per-tap kernels.
+  int halo_bm = 0;
+  if (h16 && a.ksize == 3 && a.stride == 1 && (mode == OUT_ROWMAJOR || mode == OUT_PARTIAL) && (tile == TILE_P3_128 || tile == TILE_P3_256) &&
+      (g_tile_override == TILE_HALO_128 || g_tile_override == TILE_HALO_256)) {
+    const bool want256 = tile == TILE_P3_256 && g_tile_override != TILE_HALO_128;
+    if (want256 && halo_lds_bytes(256, 2, a.ws, a.up) <= kLdsLimit && halo_rows(256, a.ws, a.up) / 32 <= 32) halo_bm = 256;
+    else if (halo_lds_bytes(128, 3, a.ws, a.up) <= kLdsLimit && halo_rows(128, a.ws, a.up) / 32 <= 16) halo_bm = 128;
+  }
+  if (halo_bm) {
+    const int nchunks = p.ctot / 64;
+    if (splits > 1) {
+      const int per = (nchunks + splits - 1) / splits;
+      splits = (nchunks + per - 1) / per;              // split-K over channel chunks: never more splits than chunks
+      if (splits <= 1) { splits = 1; p.partial = nullptr; }
+    }
+    const int hmode = splits > 1 ? OUT_PARTIAL : a.out_mode;
+    if (halo_bm == 256) {
+      if (hmode == OUT_ROWMAJOR) st = run_conv3_halo<256, 2, OUT_ROWMAJOR>(p, splits, "conv3_halo_bf16_256x128", s);
+      else st = run_conv3_halo<256, 2, OUT_PARTIAL>(p, splits, "conv3_halo_bf16_256x128_splitk", s);
+    } else {
+      if (hmode == OUT_ROWMAJOR) st = run_conv3_halo<128, 3, OUT_ROWMAJOR>(p, splits, "conv3_halo_bf16_128x128", s);
+      else st = run_conv3_halo<128, 3, OUT_PARTIAL>(p, splits, "conv3_halo_bf16_128x128_splitk", s);
+    }
+  } else if (tile == TILE_P3_128) {
     AD_P3(128)
   } else if (tile == TILE_P3_256) {
     AD_P3(256)
@@ -2444,7 +2683,7 @@ size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n
 }
 
 ad_status ad_tune_conv_tile(int tile) {
-  if (tile != -1 && tile != 1 && tile != 3 && (tile < 4 || tile > 7)) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1, 3, 4, 5, 6 or 7");
+  if (tile != -1 && tile != 1 && tile != 3 && (tile < 4 || tile > 9)) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1, 3 or 4..9");
   set_tile_override(tile);
   return AD_OK;
 }

@@ -123,7 +123,7 @@ def test_conv_epilogues(dtype):
         assert_kernel_close(got[:, :, :ho * wo], ref, dtype)
 
 
-@pytest.fixture(params=[1, 3, 4, 5, 6, 7], ids=["reg128", "reg64", "dma2_128", "dma3_128", "dma3_256", "dma3_64"])
+@pytest.fixture(params=[1, 3, 4, 5, 6, 7, 8, 9], ids=["reg128", "reg64", "dma2_128", "dma3_128", "dma3_256", "dma3_64", "halo_128", "halo_256"])
 def force_big_tiles(request):
     """Forces one GEMM kernel family on every shape (the LDS-DMA ones apply to bf16 only; fp32 keeps the automatic choice)."""
     B.check(lib.ad_tune_conv_tile(request.param))
