@@ -282,6 +282,7 @@ ad_status ad_conv_forward(int dtype, const void* src0, const void* src1, int c0,
  * layer of the process (1: 128x128 register-staged tiles, 3: 64x64 register-staged tiles, 4: 128x128 two-stage
  * LDS-DMA, 5: 128x128 three-stage LDS-DMA, 6: 256x128 three-stage LDS-DMA, 7: 64x64 three-stage LDS-DMA,
  * 8 / 9: as 5 / 6, with 3x3 stride-1 convolutions on the halo-staged kernel (128 / 256 output positions per workgroup),
+ * 10 / 11: as 6 / 5 with four wavefronts per workgroup instead of eight, 12: as 6 with sixteen,
  * -1: automatic choice, the default (3x3 convolutions on the per-tap kernels 5 / 6: measured faster than 8 / 9 on the SD-sized models)).
  * 4 to 9 apply to bf16 GEMMs with a row-major, GEGLU or fused q/k/v output; other calls keep the automatic
  * choice.  Results are the same up to rounding order.  Process-global, not thread-safe: for tests and measurements. */

@@ -637,13 +637,17 @@ __global__ __launch_bounds__(256) void k_igemm_dma(IgemmParams p) {
 // k-step and the stage of tile kt can be refilled in the next iteration.  One workgroup per CU
 // (96 KiB for 128x128, 144 KiB for 256x128), 4 wavefronts in a 2 x 2 grid.
 // =================================================================================================
-template <typename T, int BM, int BN, int MODE>
-__global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
+// WM: wavefronts along M (2: four wavefronts, one per SIMD; 4: eight wavefronts, two per SIMD, each with half the tile rows -
+// while one of a SIMD's two wavefronts waits at the barrier or for its fragments the other one has MFMAs to issue).
+template <typename T, int BM, int BN, int MODE, int WM = 2>
+__global__ __launch_bounds__(128 * WM) void k_igemm_p3(IgemmParams p) {
   typedef typename Vec<T>::type V;
-  constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
+  constexpr int NW = 2 * WM;                                   // wavefronts: WM x 2
+  constexpr int WTM = BM / WM, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
   constexpr int ES = (int)sizeof(T), VN = Vec<T>::N, BK = kRowBytes / ES;
   constexpr int STAGE = (BM + BN) * kRowBytes, NSTAGE = 3;
-  constexpr int AG = BM / 32, BG = BN / 32, OPS = AG + BG;     // 8-row groups (= loads) per wavefront and k-tile
+  constexpr int AG = BM / (8 * NW), BG = BN / (8 * NW), OPS = AG + BG;     // 8-row groups (= loads) per wavefront and k-tile
+  constexpr int RND = 8 * NW;                                  // rows one round of loads (one per wavefront) covers
   constexpr int NG = TM * TN;                                  // MFMA groups per k-step; loads go out during the first three k-steps
   static_assert(OPS < 32, "vmcnt range");
   extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -657,27 +661,27 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
   const u32x4 rs0 = make_rsrc_words(p.src0, p.bytes0), rs1 = make_rsrc_words(p.src1, p.bytes1);
   const u32x4 rsw = make_rsrc_words(p.w, p.bytes_w);
 
-  // load i of a k-tile covers rows (4 i + wave) * 8 .. + 7 of the A tile (i < AG) or of the B tile
-  const int r8 = lane >> 3, scol = (lane & 7) ^ (((wave * 8 + r8) >> 1) & 7);      // see lds_swizzle(); rows (4 i + wave) * 8 + r8
+  // load i of a k-tile covers rows (NW i + wave) * 8 .. + 7 of the A tile (i < AG) or of the B tile
+  const int r8 = lane >> 3, scol = (lane & 7) ^ (((wave * 8 + r8) >> 1) & 7);      // see lds_swizzle(); rows (NW i + wave) * 8 + r8
   const int kt_begin = tid3.split * p.kt_per_split;
   const int nkt = min(p.ktiles - kt_begin, p.kt_per_split);
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
   const unsigned grp = (unsigned)wave * 8 * kRowBytes;
   unsigned b_off[BG];
 #pragma unroll
-  for (int i = 0; i < BG; ++i) b_off[i] = (unsigned)((n0 + (4 * i + wave) * 8 + r8) * p.Kp + scol * VN) * ES;
+  for (int i = 0; i < BG; ++i) b_off[i] = (unsigned)((n0 + (NW * i + wave) * 8 + r8) * p.Kp + scol * VN) * ES;
   // the weight tiles of the first two k-tiles go out before the row arithmetic below, which they do not need
 #pragma unroll
   for (int t = 0; t < NSTAGE - 1; ++t)
     if (t < nkt) {
 #pragma unroll
       for (int i = 0; i < BG; ++i)
-        dma_load16(rsw, b_off[i], (unsigned)((kt_begin + t) * BK * ES), lds_base + t * STAGE + grp + (BM + i * 32) * kRowBytes);
+        dma_load16(rsw, b_off[i], (unsigned)((kt_begin + t) * BK * ES), lds_base + t * STAGE + grp + (BM + i * RND) * kRowBytes);
     }
   int a_iy0[AG], a_ix0[AG], a_b[AG];
 #pragma unroll
   for (int i = 0; i < AG; ++i) {
-    const int m = m0 + (4 * i + wave) * 8 + r8;
+    const int m = m0 + (NW * i + wave) * 8 + r8;
     if (m < p.M) {
       const int b = (int)fast_div((unsigned)m, p.div_hw), r = m - b * p.hw_out;
       const int oy = (int)fast_div((unsigned)r, p.div_w), ox = r - oy * p.wout;
@@ -713,8 +717,8 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
   };
   auto issue_one = [&](int stage, int i) {
     const unsigned st = lds_base + stage * STAGE + grp;
-    if (i < AG) dma_load16(rsa, second ? a_off1[i] : a_off0[i], soff_a, st + i * 32 * kRowBytes);
-    else dma_load16(rsw, b_off[i - AG], soff_b, st + (BM + (i - AG) * 32) * kRowBytes);
+    if (i < AG) dma_load16(rsa, second ? a_off1[i] : a_off0[i], soff_a, st + i * RND * kRowBytes);
+    else dma_load16(rsw, b_off[i - AG], soff_b, st + (BM + (i - AG) * RND) * kRowBytes);
   };
   auto end_tile = [&]() {
     f_k0 += BK;
@@ -809,24 +813,24 @@ __global__ __launch_bounds__(256) void k_igemm_p3(IgemmParams p) {
   igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch), tid3.split);
 }
 
-template <typename T, int BM, int BN, int MODE>
+template <typename T, int BM, int BN, int MODE, int WM = 2>
 static ad_status run_igemm_p3(const IgemmParams& p0, const char* name, hipStream_t s) {
   IgemmParams p = p0;
   p.tiles_n = (p.N + BN - 1) / BN;
   const int tiles_m = (p.M + BM - 1) / BM;
   p.tiles_m = tiles_m;
   constexpr int lds_bytes = 3 * (BM + BN) * kRowBytes;
-  static_assert(lds_bytes >= 4 * (BM / 2) * kPitch, "epilogue staging fits");
+  static_assert(lds_bytes >= 2 * WM * (BM / WM) * kPitch, "epilogue staging fits");
   static bool attr_set = false;
   if (!attr_set) {
-    AD_HIP(hipFuncSetAttribute((const void*)k_igemm_p3<T, BM, BN, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    AD_HIP(hipFuncSetAttribute((const void*)k_igemm_p3<T, BM, BN, MODE, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     attr_set = true;
   }
   const double in_bytes = (double)p.M * p.ctot * sizeof(T) * (p.stride == 2 ? 4 : 1) / (p.up ? 4 : 1);
   const double out_cols = p.out_mode == OUT_GEGLU ? p.N / 2 : p.N;
   ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
   const int splits = (p.ktiles + p.kt_per_split - 1) / p.kt_per_split;
-  hipLaunchKernelGGL((k_igemm_p3<T, BM, BN, MODE>), dim3(p.tiles_n * tiles_m, splits), dim3(256), lds_bytes, s, p);
+  hipLaunchKernelGGL((k_igemm_p3<T, BM, BN, MODE, WM>), dim3(p.tiles_n * tiles_m, splits), dim3(128 * WM), lds_bytes, s, p);
   AD_HIP(hipGetLastError());
   return AD_OK;
 }
@@ -1123,7 +1127,7 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
 // Tile shapes.  The register-staged kernels (64x64, 128x128) serve fp32 and the transposed epilogues; bf16
 // GEMMs with a row-major, GEGLU, fused q/k/v or split-K epilogue take the three-stage LDS-DMA kernel with a
 // 128x128 or a 256x128 tile.
-enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_DMA2_128 = 4, TILE_P3_128 = 5, TILE_P3_256 = 6, TILE_P3_64 = 7, TILE_HALO_128 = 8, TILE_HALO_256 = 9, TILE_AUTO = -1 };
+enum { TILE_128x128 = 1, TILE_64x64 = 3, TILE_DMA2_128 = 4, TILE_P3_128 = 5, TILE_P3_256 = 6, TILE_P3_64 = 7, TILE_HALO_128 = 8, TILE_HALO_256 = 9, TILE_P3_256_W4 = 10, TILE_P3_128_W4 = 11, TILE_P3_256_W16 = 12, TILE_AUTO = -1 };
 static int g_tile_override = TILE_AUTO;
 static int g_order_override = -1;
 
@@ -1165,6 +1169,8 @@ static ConvPlan choose_plan(int dtype, long long m, int n, int ktiles, int out_m
   const bool geglu = out_mode == OUT_GEGLU;   // needs a value and a gate tile in the same wavefront
   const bool dma = dma_capable(dtype, out_mode);
   int forced = g_tile_override;
+  if (forced == TILE_P3_128_W4) forced = TILE_P3_128;     // variants with other wavefront counts: same tiles, same planning
+  if (forced == TILE_P3_256_W4 || forced == TILE_P3_256_W16) forced = TILE_P3_256;
   if (forced == TILE_HALO_128) forced = TILE_P3_128;      // the halo kernels share the tile shapes (and the split-K planning) of these
   if (forced == TILE_HALO_256) forced = TILE_P3_256;
   if (forced == TILE_P3_128 || forced == TILE_P3_256 || forced == TILE_DMA2_128 || forced == TILE_P3_64) {
@@ -1278,14 +1284,6 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
     case OUT_PARTIAL: AD_RUN(TT, BM_, OUT_PARTIAL); break;             \
     default: break;                                                    \
   }
-#define AD_P3(BM_)                                                                                                    \
-  switch (mode) {                                                                                                     \
-    case OUT_ROWMAJOR: st = run_igemm_p3<bf16, BM_, 128, OUT_ROWMAJOR>(p, "igemm_bf16_" #BM_ "x128_p3", s); break;    \
-    case OUT_GEGLU: st = run_igemm_p3<bf16, BM_, 128, OUT_GEGLU>(p, "igemm_bf16_" #BM_ "x128_p3", s); break;          \
-    case OUT_QKV: st = run_igemm_p3<bf16, BM_, 128, OUT_QKV>(p, "igemm_bf16_" #BM_ "x128_p3", s); break;              \
-    case OUT_PARTIAL: st = run_igemm_p3<bf16, BM_, 128, OUT_PARTIAL>(p, "igemm_bf16_" #BM_ "x128_p3_splitk", s); break; \
-    default: break;                                                                                                   \
-  }
   // 3x3, stride 1: the halo-staged kernel, on request (TILE_HALO_*) and when its tiles fit into LDS.  It moves less than
   // half the bytes from L2 into LDS per k-tile, but on the convolutions of the SD-sized models it runs at 0.70-0.85 of the
   // per-tap three-stage kernel (its k-loop has neither that kernel's fragment prefetch across the barrier nor its third
@@ -1312,10 +1310,24 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
       if (hmode == OUT_ROWMAJOR) st = run_conv3_halo<128, 3, OUT_ROWMAJOR>(p, splits, "conv3_halo_bf16_128x128", s);
       else st = run_conv3_halo<128, 3, OUT_PARTIAL>(p, splits, "conv3_halo_bf16_128x128_splitk", s);
     }
-  } else if (tile == TILE_P3_128) {
-    AD_P3(128)
-  } else if (tile == TILE_P3_256) {
-    AD_P3(256)
+  } else if (tile == TILE_P3_128 || tile == TILE_P3_256) {
+    // eight wavefronts (two per SIMD) by default: 3-20 % faster than four on the layers of the SD-sized models; the
+    // four- and sixteen-wavefront variants stay selectable for measurements
+    const int wm = g_tile_override == TILE_P3_256_W4 || g_tile_override == TILE_P3_128_W4 ? 2 : (g_tile_override == TILE_P3_256_W16 && tile == TILE_P3_256 ? 8 : 4);
+#define AD_P3W(BM_, WM_, TAG)                                                                                                          \
+  switch (mode) {                                                                                                                      \
+    case OUT_ROWMAJOR: st = run_igemm_p3<bf16, BM_, 128, OUT_ROWMAJOR, WM_>(p, "igemm_bf16_" #BM_ "x128_p3" TAG, s); break;            \
+    case OUT_GEGLU: st = run_igemm_p3<bf16, BM_, 128, OUT_GEGLU, WM_>(p, "igemm_bf16_" #BM_ "x128_p3" TAG, s); break;                  \
+    case OUT_QKV: st = run_igemm_p3<bf16, BM_, 128, OUT_QKV, WM_>(p, "igemm_bf16_" #BM_ "x128_p3" TAG, s); break;                      \
+    case OUT_PARTIAL: st = run_igemm_p3<bf16, BM_, 128, OUT_PARTIAL, WM_>(p, "igemm_bf16_" #BM_ "x128_p3" TAG "_splitk", s); break;    \
+    default: break;                                                                                                                    \
+  }
+    if (tile == TILE_P3_256) {
+      if (wm == 2) { AD_P3W(256, 2, "w4") } else if (wm == 8) { AD_P3W(256, 8, "w16") } else { AD_P3W(256, 4, "") }
+    } else {
+      if (wm == 2) { AD_P3W(128, 2, "w4") } else { AD_P3W(128, 4, "") }
+    }
+#undef AD_P3W
   } else if (tile == TILE_P3_64) {
     switch (mode) {
       case OUT_ROWMAJOR: st = run_igemm_p3<bf16, 64, 64, OUT_ROWMAJOR>(p, "igemm_bf16_64x64_p3", s); break;
@@ -1336,7 +1348,6 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   } else {
     if (big) { AD_MODES(float, 128) } else { AD_MODES(float, 64) }
   }
-#undef AD_P3
 #undef AD_MODES
 #undef AD_RUN
   if (st != AD_OK || splits <= 1) return st;
@@ -2683,7 +2694,7 @@ size_t ad_conv_workspace_bytes(int dtype, int batch, int h_out, int w_out, int n
 }
 
 ad_status ad_tune_conv_tile(int tile) {
-  if (tile != -1 && tile != 1 && tile != 3 && (tile < 4 || tile > 9)) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1, 3 or 4..9");
+  if (tile != -1 && tile != 1 && tile != 3 && (tile < 4 || tile > 12)) AD_FAIL(AD_ERR_INVALID, "tile must be -1, 1, 3 or 4..12");
   set_tile_override(tile);
   return AD_OK;
 }

@@ -123,7 +123,7 @@ def test_conv_epilogues(dtype):
         assert_kernel_close(got[:, :, :ho * wo], ref, dtype)
 
 
-@pytest.fixture(params=[1, 3, 4, 5, 6, 7, 8, 9], ids=["reg128", "reg64", "dma2_128", "dma3_128", "dma3_256", "dma3_64", "halo_128", "halo_256"])
+@pytest.fixture(params=[1, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12], ids=["reg128", "reg64", "dma2_128", "dma3_128", "dma3_256", "dma3_64", "halo_128", "halo_256", "dma3_256_w4", "dma3_128_w4", "dma3_256_w16"])
 def force_big_tiles(request):
     """Forces one GEMM kernel family on every shape (the LDS-DMA ones apply to bf16 only; fp32 keeps the automatic choice)."""
     B.check(lib.ad_tune_conv_tile(request.param))
@@ -141,7 +141,7 @@ def test_conv_big_tile_kernels(dtype, case, force_big_tiles):
 
 
 @pytest.mark.parametrize("dtype", DT)
-@pytest.mark.parametrize("big", [0, 1, 4, 5, 6, 7])
+@pytest.mark.parametrize("big", [0, 1, 4, 5, 6, 7, 10, 11, 12])
 @pytest.mark.parametrize("vt", [False, True])
 def test_fused_qkv_projection(dtype, big, vt):
     """One GEMM for q, k, v: thirds of the output columns go to three tensors, the last optionally transposed."""
