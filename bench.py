@@ -47,6 +47,47 @@ def run_rounds(m, latent, text, streams, n):
             raise RuntimeError("schedule exhausted")
 
 
+def study_saturation(ad, torch, d, r, dtype, wts, dev, cuts, K):
+    """One context (N streams, graph replay) against two independent contexts enqueued alternately on 2N streams.  The second
+    context's kernels are free to fill whatever the first leaves idle, at round boundaries in particular, so
+    (time of a pair of rounds) / 2 is a lower bound for the round time any cross-round overlap within one context can reach."""
+    import synthetic_inputs as SI
+    N, w, S = r["N"], r["w"], r["S"]
+    sampler = ad.AD_DDIM if r["sampler"] == "ddim" else ad.AD_EULER
+    tdt = torch.bfloat16 if dtype == ad.AD_BF16 else torch.float32
+
+    def make(seed):
+        m = ad.AsyncDiff(d, N, w, S, dtype, cuts=cuts)
+        m.allocate(dev); m.load_weights(wts); m.set_graph_mode(True)
+        m.reset(w + 8 + 3 * K * S, sampler=sampler, cfg_scale=r["cfg_scale"])
+        lat = torch.from_numpy(SI.make_latent(d["latent_channels"], d["height"], d["width"], seed=seed)).to(dev)
+        text = torch.from_numpy(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"], seed=seed + 1)).to(dev).to(tdt)
+        return m, lat, text, [torch.cuda.Stream(device=dev) for _ in range(N + S - 1)]
+
+    A, B2 = make(2000), make(2100)
+    for m, lat, text, ss in (A, B2):
+        run_rounds(m, lat, text, ss, w + 4)
+    torch.cuda.synchronize()
+
+    def timed(ctxs):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            for m, lat, text, ss in ctxs:
+                run_rounds(m, lat, text, ss, 1)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / K * 1e3
+
+    one = min(timed([A]), timed([A]))
+    two = timed([A, B2])
+    out = {"metric": "round time, one context vs two independent contexts side by side (saturation study)", "unit": "ms",
+           "config": {"workload": "sd21_768" if d["height"] == 96 else "other", "component_first_units": [a for a, _ in A[0].partition()]},
+           "one_context_ms_per_round": round(one, 4), "two_contexts_ms_per_pair": round(two, 4),
+           "lower_bound_ms_per_round_with_overlap": round(two / 2, 4), "headroom": round(one / (two / 2), 4)}
+    log(f"one context {one:.3f} ms per round; two contexts side by side {two:.3f} ms per pair = {two / 2:.3f} per round; headroom x{one / (two / 2):.3f}")
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +108,9 @@ def main():
     ap.add_argument("--order", type=int, default=-1, help="GEMM workgroup order override for measurements (ad_tune_conv_order); -1 = automatic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--shapes", action="store_true", help="print the per-shape GEMM/attention timings of the instrumented round to stderr")
+    ap.add_argument("--study", default="", help="'saturation': instead of the benchmark, time one context against two independent contexts run side by side "
+                    "(twice the streams): what the second context's rounds gain is an upper bound on what any overlap of consecutive rounds of one "
+                    "context (per-edge events instead of the round barrier) could gain")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the N components on ONE GPU (separate HIP streams); --gpus must be 1", file=sys.stderr)
@@ -94,6 +138,11 @@ def main():
     probe = ad.AsyncDiff(d, 1, 0, 1, dtype)
     wts = SI.make_weights(probe.weight_manifest(), bf16_exact=(dtype == ad.AD_BF16))
     probe.close()
+    if args.study == "saturation":
+        study_saturation(ad, torch, d, r, dtype, wts, dev, None if args.cuts in ("flops", "auto") else [int(x) for x in args.cuts.split(",")], K)
+        return
+    if args.study:
+        raise SystemExit("unknown --study")
     unit_us = None
     if args.wrap:
         cuts = None if args.cuts in ("auto", "flops") else [int(x) for x in args.cuts.split(",")]

@@ -1197,7 +1197,7 @@ static ConvPlan choose_plan(int dtype, long long m, int n, int ktiles, int out_m
   // measured 1.1-1.3x there, slower everywhere else
   const long long tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
   if (forced == TILE_P3_64) return ConvPlan{TILE_P3_64, splits_by_tiles(m, n, ktiles, out_mode, 64)};
-  if (forced == TILE_AUTO && !geglu && tiles128 <= 192 && ktiles <= 32) return ConvPlan{TILE_P3_64, 1};
+  if (forced == TILE_AUTO && !geglu && tiles128 <= 128 && ktiles <= 32) return ConvPlan{TILE_P3_64, 1};
   for (int tile : {TILE_P3_128, TILE_P3_256}) {
     if (forced != TILE_AUTO && tile != forced) continue;
     for (int sp = 1; sp <= max_splits; ++sp) {
@@ -1589,17 +1589,17 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(256) voi
 // Scores are computed transposed (S^T = K Q^T, a lane owns one query) as in the first kernel.
 // =================================================================================================
 constexpr int kAttn2Stage = 2 * 64 * kRowBytes;   // one K tile and one V^T tile of 64 keys: 16 KiB
-constexpr int kAttn2Stages = 3;
 constexpr float kAttnBig = 1.2676506e30f;
 #ifndef PRIO
 #define PRIO 2
 #endif         // 2^100: a 32-key row sum at or above it moves the reference
 
-template <int QSETS, bool RAGGED>
-__global__ __attribute__((amdgpu_waves_per_eu(QSETS == 1 ? 3 : 2, QSETS == 1 ? 3 : 2))) __launch_bounds__(256) void k_attn_mfma2(
+// NSTG: LDS stages (tiles requested NSTG - 1 ahead); OCC: wavefronts per SIMD the register budget is set for
+template <int QSETS, bool RAGGED, int NSTG = 3, int OCC = (QSETS == 1 ? 3 : 2)>
+__global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256) void k_attn_mfma2(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ Vt, bf16* __restrict__ O, int L, int Lk, int C,
     int ldq, int ldk, int ldv, int ldo, float scale_log2, int qblocks) {
-  __shared__ __attribute__((aligned(128))) char lds[kAttn2Stages * kAttn2Stage];
+  __shared__ __attribute__((aligned(128))) char lds[NSTG * kAttn2Stage];
   constexpr int QW = 32 * QSETS;                  // queries per wavefront
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1657,7 +1657,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(QSETS == 1 ? 3 : 2, QSETS == 1 ? 3
     }
   };
   issue(0, 0);
-  if (ntiles > 1) issue(1, 1);
+  if (NSTG > 2 && ntiles > 1) issue(1, 1);
 
   // ---- queries: B operand of the score product, pre-multiplied by log2(e) / sqrt(d)
   bf16x8 qf[QSETS][4];
@@ -1787,17 +1787,17 @@ __global__ __attribute__((amdgpu_waves_per_eu(QSETS == 1 ? 3 : 2, QSETS == 1 ? 3
   int stage = 0;
   for (int t = 0; t < ntiles; ++t) {
     // tile t has landed once at most the loads of tile t + 1 are outstanding (a partial last tile waits by itself)
-    if (t + 1 < ntiles && !(RAGGED && t + 2 == ntiles)) wait_vmcnt<4>(); else wait_vmcnt<0>();
+    if (NSTG > 2 && t + 1 < ntiles && !(RAGGED && t + 2 == ntiles)) wait_vmcnt<4>(); else wait_vmcnt<0>();
     __syncthreads();       // tile t is complete for every wavefront, and everybody is done with tile t - 1
-    if (t + 2 < ntiles) {
-      int target = stage + 2;
-      if (target >= kAttn2Stages) target -= kAttn2Stages;
-      issue(t + 2, target);
+    if (t + NSTG - 1 < ntiles) {
+      int target = stage + NSTG - 1;
+      if (target >= NSTG) target -= NSTG;
+      issue(t + NSTG - 1, target);
     }
     const char* Ks = lds + stage * kAttn2Stage;
     block(Ks, t, 0, t == 0);
     block(Ks, t, 1, false);
-    if (++stage == kAttn2Stages) stage = 0;
+    if (++stage == NSTG) stage = 0;
   }
 #pragma unroll
   for (int s = 0; s < QSETS; ++s) {
