@@ -1197,7 +1197,7 @@ static ConvPlan choose_plan(int dtype, long long m, int n, int ktiles, int out_m
   // measured 1.1-1.3x there, slower everywhere else
   const long long tiles128 = ((m + 127) / 128) * ((n + 127) / 128);
   if (forced == TILE_P3_64) return ConvPlan{TILE_P3_64, splits_by_tiles(m, n, ktiles, out_mode, 64)};
-  if (forced == TILE_AUTO && !geglu && tiles128 <= 128 && ktiles <= 32) return ConvPlan{TILE_P3_64, 1};
+  if (forced == TILE_AUTO && !geglu && tiles128 <= 192 && ktiles <= 32) return ConvPlan{TILE_P3_64, 1};
   for (int tile : {TILE_P3_128, TILE_P3_256}) {
     if (forced != TILE_AUTO && tile != forced) continue;
     for (int sp = 1; sp <= max_splits; ++sp) {
