@@ -294,7 +294,9 @@ ad_status ad_tune_conv_tile(int tile);
 ad_status ad_tune_conv_order(int order);
 /* Tuning knob for measurements and tests (process-global, not thread-safe): which MFMA attention kernel serves bf16,
  * head_dim 64, transposed v.  0: 32 queries per wavefront, register-staged tiles; 1 / 2: tiles filled by the load
- * unit, lazy maximum, 32 / 64 queries per wavefront; -1: automatic, the default.  Same results up to rounding. */
+ * unit, lazy maximum, 32 / 64 queries per wavefront; 3: as 1 with the scores of the next 32 keys computed while the
+ * exponentials of the current ones run (two workgroups per CU; 4-10 % faster than 1 alone on the GPU, no faster inside the
+ * concurrent schedule); -1: automatic, the default (1 beyond 256 keys, else 0).  Same results up to rounding. */
 ad_status ad_tune_attention(int variant);
 /* Packs HOST fp32 weights [n_out][c_in][k][k] into the kernel layout (HOST out, dtype elements).
  * Returns the packed size in bytes through *bytes when out == NULL. */

@@ -42,6 +42,7 @@ struct ConvArgs {
   void* splitk_ws = nullptr;            // fp32 scratch for split-K partial sums (optional)
   size_t splitk_bytes = 0;
   void* out2 = nullptr; void* out3 = nullptr;   // OUT_QKV: columns [n/3, 2n/3) and [2n/3, n)
+  int k_real = 0;                       // > 0: K without zero padding, for the profiler's FLOP count (the im2col'ed first convolution)
 };
 // OUT_QKV: n_out = 3c; thirds go to out [m][c], out2 [m][c] and out3 ([batch][c][ld_t] when ld_t > 0, else [m][c])
 enum { OUT_ROWMAJOR = 0, OUT_GEGLU = 1, OUT_TRANSPOSED = 2, OUT_TRANSPOSED_F32 = 3, OUT_QKV = 4 };

@@ -13,6 +13,7 @@
 #include "ad_kernels.h"
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <type_traits>
 
@@ -129,6 +130,7 @@ struct IgemmParams {
   void* out2; void* out3;             // OUT_QKV
   FastDiv div_hw, div_w;              // by hw_out and by wout (row index -> sample, output row, output column)
   int tiles_m;                        // row tiles
+  int k_prof;                         // K the profiler counts (the real one where the operand is zero-padded), else Kp
   int n_major;                        // workgroup order: 0 = an XCD owns a run of row tiles (all column tiles of each),
                                       // 1 = an XCD owns a run of column tiles (all row tiles of each); see tile_of()
 };
@@ -821,14 +823,14 @@ static ad_status run_igemm_p3(const IgemmParams& p0, const char* name, hipStream
   p.tiles_m = tiles_m;
   constexpr int lds_bytes = 3 * (BM + BN) * kRowBytes;
   static_assert(lds_bytes >= 2 * WM * (BM / WM) * kPitch, "epilogue staging fits");
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};
   if (!attr_set) {
     AD_HIP(hipFuncSetAttribute((const void*)k_igemm_p3<T, BM, BN, MODE, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     attr_set = true;
   }
   const double in_bytes = (double)p.M * p.ctot * sizeof(T) * (p.stride == 2 ? 4 : 1) / (p.up ? 4 : 1);
   const double out_cols = p.out_mode == OUT_GEGLU ? p.N / 2 : p.N;
-  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
+  ProfLaunch pl(name, 2.0 * p.M * p.N * p.k_prof, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
   const int splits = (p.ktiles + p.kt_per_split - 1) / p.kt_per_split;
   hipLaunchKernelGGL((k_igemm_p3<T, BM, BN, MODE, WM>), dim3(p.tiles_n * tiles_m, splits), dim3(128 * WM), lds_bytes, s, p);
   AD_HIP(hipGetLastError());
@@ -1034,13 +1036,13 @@ static ad_status run_conv3_halo(const IgemmParams& p0, int splits, const char* n
   const int real_splits = (nchunks + hp.chunk_begin_stride - 1) / hp.chunk_begin_stride;
   const size_t lds_bytes = std::max(halo_lds_bytes(BM, NB, p.ws, p.up), (size_t)4 * (BM / 2) * kPitch);
   if (lds_bytes > kLdsLimit || hp.hr / 32 > 16 * (BM / 128)) AD_FAIL(AD_ERR_INVALID, "conv (halo): tile does not fit");
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};
   if (!attr_set) {
     AD_HIP(hipFuncSetAttribute((const void*)k_conv3_halo<BM, NB, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit));
     attr_set = true;
   }
   const double in_bytes = (double)p.M * p.ctot * 2 / (p.up ? 4 : 1);
-  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * 2 + (double)p.M * p.N * 2, s, p.M, p.N, p.Kp);
+  ProfLaunch pl(name, 2.0 * p.M * p.N * p.k_prof, in_bytes + (double)p.N * p.Kp * 2 + (double)p.M * p.N * 2, s, p.M, p.N, p.Kp);
   hipLaunchKernelGGL((k_conv3_halo<BM, NB, MODE>), dim3(p.tiles_n * p.tiles_m, real_splits), dim3(256), lds_bytes, s, p, hp);
   AD_HIP(hipGetLastError());
   return AD_OK;
@@ -1053,14 +1055,14 @@ static ad_status run_igemm_dma(const IgemmParams& p0, const char* name, hipStrea
   const int tiles_m = (p.M + 127) / 128;
   p.tiles_m = tiles_m;
   constexpr int lds_bytes = NSTAGE * 256 * kRowBytes;
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};
   if (!attr_set) {
     AD_HIP(hipFuncSetAttribute((const void*)k_igemm_dma<T, MODE, NSTAGE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     attr_set = true;
   }
   const double in_bytes = (double)p.M * p.ctot * sizeof(T) * (p.stride == 2 ? 4 : 1) / (p.up ? 4 : 1);
   const double out_cols = p.out_mode == OUT_GEGLU ? p.N / 2 : p.N;
-  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
+  ProfLaunch pl(name, 2.0 * p.M * p.N * p.k_prof, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
   const int splits = (p.ktiles + p.kt_per_split - 1) / p.kt_per_split;
   hipLaunchKernelGGL((k_igemm_dma<T, MODE, NSTAGE>), dim3(p.tiles_n * tiles_m, splits), dim3(256), lds_bytes, s, p);
   AD_HIP(hipGetLastError());
@@ -1074,14 +1076,14 @@ static ad_status run_igemm(const IgemmParams& p0, const char* name, hipStream_t 
   const int tiles_m = (p.M + BM - 1) / BM;
   p.tiles_m = tiles_m;
   constexpr int lds_bytes = 2 * (BM + BN) * kPitch;
-  static bool attr_set = false;     // LDS above 64 KiB has to be requested once per kernel
+  static std::atomic<bool> attr_set{false};     // LDS above 64 KiB has to be requested once per kernel
   if (!attr_set) {
     AD_HIP(hipFuncSetAttribute((const void*)k_igemm<T, BM, BN, WGM, WGN, NSET, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     attr_set = true;
   }
   const double in_bytes = (double)p.M * p.ctot * sizeof(T) * (p.stride == 2 ? 4 : 1) / (p.up ? 4 : 1);
   const double out_cols = p.out_mode == OUT_GEGLU ? p.N / 2 : p.N;
-  ProfLaunch pl(name, 2.0 * p.M * p.N * p.Kp, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
+  ProfLaunch pl(name, 2.0 * p.M * p.N * p.k_prof, in_bytes + (double)p.N * p.Kp * sizeof(T) + (double)p.M * out_cols * sizeof(T), s, p.M, p.N, p.Kp);
   const int splits = (p.ktiles + p.kt_per_split - 1) / p.kt_per_split;
   hipLaunchKernelGGL((k_igemm<T, BM, BN, WGM, WGN, NSET, MODE>), dim3(p.tiles_n * tiles_m, splits), dim3(256), lds_bytes, s, p);
   AD_HIP(hipGetLastError());
@@ -1241,6 +1243,7 @@ ad_status launch_conv(const ConvArgs& a, hipStream_t s) {
   p.M = (int)m; p.N = a.n_out;
   p.Kp = a.ksize * a.ksize * p.ctot;      // a multiple of the k-tile because ctot is
   p.ktiles = p.Kp / bk;
+  p.k_prof = a.k_real > 0 ? a.k_real : p.Kp;
   p.w = a.w; p.bias = a.bias; p.rowvec = a.rowvec; p.residual = a.residual;
   p.out = a.out; p.out_mode = a.out_mode; p.ld_t = a.ld_t; p.rowvec_ld = a.rowvec_ld > 0 ? a.rowvec_ld : (a.rowvec_ld < 0 ? 0 : a.n_out);
   p.out2 = a.out2; p.out3 = a.out3;
@@ -1589,13 +1592,21 @@ __global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(256) voi
 // Scores are computed transposed (S^T = K Q^T, a lane owns one query) as in the first kernel.
 // =================================================================================================
 constexpr int kAttn2Stage = 2 * 64 * kRowBytes;   // one K tile and one V^T tile of 64 keys: 16 KiB
-constexpr float kAttnBig = 1.2676506e30f;
-#ifndef PRIO
-#define PRIO 2
-#endif         // 2^100: a 32-key row sum at or above it moves the reference
+constexpr float kAttnBig = 1.2676506e30f;         // 2^100: a 32-key row sum at or above it moves the reference
 
-// NSTG: LDS stages (tiles requested NSTG - 1 ahead); OCC: wavefronts per SIMD the register budget is set for
-template <int QSETS, bool RAGGED, int NSTG = 3, int OCC = (QSETS == 1 ? 3 : 2)>
+// NSTG: LDS stages (tiles requested two ahead from three stages on); OCC: wavefronts per SIMD the register budget is set for.
+// PIPE (one query set): the software-pipelined path.  Measured on this chip: a wavefront that issues four plain vector
+// instructions between two of its own MFMAs pays nothing for them (32 -> 34 cycles per MFMA), an exponential costs about
+// 4.5 cycles, whereas vector work of ANOTHER wavefront of the SIMD overlaps an MFMA stream poorly (1.25-1.45x instead of 2x).
+// So the vector work has to sit between the MFMAs of the same wavefront: a step issues the score MFMAs of block u + 1,
+// the exponentials / conversions / row sums of block u (whose scores the previous step left in registers) and the PV MFMAs of
+// block u in one straight line, with the order pinned (one MFMA, five vector instructions, ...).  The steady state has no
+// branch: the reference is the exact maximum of the first 32 keys, and whether some later score left the window
+// (row sum >= 2^100 or not finite) is tested once, at the end; if so - it takes a score more than 69 nats above every
+// one of the first 32 - the workgroup repeats its work with the checked block-by-block loop below.  The K fragments of a
+// step are fetched from LDS one step ahead, so a tile is opened (waited for, barrier) one block before its first scores:
+// three tiles are in use across that barrier plus one in flight, hence four stages (64 KiB, two workgroups per CU).
+template <int QSETS, bool RAGGED, int NSTG = 3, int OCC = (QSETS == 1 ? 3 : 2), bool PIPE = false>
 __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256) void k_attn_mfma2(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ Vt, bf16* __restrict__ O, int L, int Lk, int C,
     int ldq, int ldk, int ldv, int ldo, float scale_log2, int qblocks) {
@@ -1784,21 +1795,139 @@ __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256)
     for (int i = 0; i < 4 * QSETS; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
   };
 
+  // Waits for tile t and lets a free stage be refilled.  Tile t has landed once at most the loads of tile t + 1 are outstanding
+  // (a partial last tile waits by itself); after the barrier tile t is complete for every wavefront and everybody is done with
+  // tile t - 1 (the pipelined path, which opens a tile one block early, is then done with tile t - 2: hence its fourth stage).
+  auto open_tile = [&](int t, int stage) {
+    if (NSTG > 2 && t + 1 < ntiles && !(RAGGED && t + 2 == ntiles)) wait_vmcnt<4>(); else wait_vmcnt<0>();
+    __syncthreads();
+    constexpr int AHEAD = NSTG > 2 ? 2 : 1;      // tiles requested ahead (a fourth stage is slack for the pipelined path)
+    if (t + AHEAD < ntiles) {
+      int target = stage + AHEAD;
+      if (target >= NSTG) target -= NSTG;
+      issue(t + AHEAD, target);
+    }
+  };
+  if constexpr (PIPE) {
+    static_assert(QSETS == 1 && NSTG == 4, "the pipelined path is written for one query set and four stages");
+    __shared__ int s_redo;
+    const int nfull = RAGGED ? ntiles - 1 : ntiles;     // tiles without a ragged tail
+    auto stage_of = [&](int t) { return lds + (t & (NSTG - 1)) * kAttn2Stage; };
+    open_tile(0, 0);
+    block(lds, 0, 0, true);                              // fixes the reference: exact maximum of the first 32 keys
+    if (nfull == 0) {
+      block(lds, 0, 1, false);
+    } else {
+      auto k_frags = [&](const char* Ks, int j, bf16x8 (&kf)[4]) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) kf[ks] = *(const bf16x8*)(Ks + j * 32 * kRowBytes + frag_row + (((ks * 2 + half) ^ x7) << 4));
+      };
+      auto v_frags = [&](const char* Ks, int j, bf16x8 (&vf)[2][2]) {
+#pragma unroll
+        for (int d = 0; d < 2; ++d)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2)
+            vf[d][s2] = *(const bf16x8*)(Ks + 8192 + d * 32 * kRowBytes + frag_row + (((j * 4 + s2 * 2 + half) ^ x7) << 4));
+      };
+      auto score_chain = [&](const bf16x8 (&kf)[4]) {
+        f32x16 sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0][0], negm[0], 0, 0, 0);
+#pragma unroll
+        for (int ks = 1; ks < 4; ++ks) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[0][ks], sc, 0, 0, 0);
+        return sc;
+      };
+      // exponentials, conversion and row sum of a block whose (s - m) are in sc, then its PV products
+      auto finish_block = [&](const f32x16& sc, const bf16x8 (&vf)[2][2]) {
+        bf16x8 pb[2];
+        float psum = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const bf16x2 pp = {(bf16)__builtin_amdgcn_exp2f(sc[8 * s2 + e]), (bf16)__builtin_amdgcn_exp2f(sc[8 * s2 + e + 1])};
+            pb[s2][e] = pp[0]; pb[s2][e + 1] = pp[1];
+            psum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum, false);
+          }
+        l_run[0] += psum;
+#pragma unroll
+        for (int d = 0; d < 2; ++d)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) o[0][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[d][s2], pb[s2], o[0][d], 0, 0, 0);
+      };
+      // One step: the scores of the next block from the K fragments the previous step fetched (kf_c), the exponentials,
+      // row sum and PV products of the current block (scores in sc_c), and the fetch of the K fragments for the step after
+      // (kf_n, from block (Kf, jf); Kf == nullptr: none).  open >= 0: that block opens tile `open`, which is waited for first.
+      auto pipe_step = [&](const f32x16& sc_c, f32x16& sc_n, const bf16x8 (&kf_c)[4], bf16x8 (&kf_n)[4], const char* Kc, int jc,
+                           const char* Kf, int jf, int open) {
+        bf16x8 vf[2][2];
+        v_frags(Kc, jc, vf);
+        if (open >= 0) open_tile(open, open & (NSTG - 1));
+        if (Kf) k_frags(Kf, jf, kf_n);
+        sc_n = score_chain(kf_c);
+        finish_block(sc_c, vf);
+        // order: score MFMAs with the exponentials of the current block between them, then the PV MFMAs with what is left of the
+        // conversions and row sums (transcendentals form a scheduling class of their own)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
+          if (i > 0) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        }
+      };
+      f32x16 sc_a, sc_b;
+      bf16x8 kf_a[4], kf_b[4];
+      k_frags(lds, 1, kf_b);
+      if (ntiles > 1) open_tile(1, 1);
+      if (nfull > 1) k_frags(stage_of(1), 0, kf_a);
+      sc_a = score_chain(kf_b);
+      for (int t = 1; t < nfull; ++t) {
+        // (t - 1, 1) is finished while (t, 0) is scored; then (t, 0) is finished while (t, 1) is scored and tile t + 1 opened
+        pipe_step(sc_a, sc_b, kf_a, kf_b, stage_of(t - 1), 1, stage_of(t), 1, -1);
+        const bool more = t + 1 < nfull;
+        pipe_step(sc_b, sc_a, kf_b, kf_a, stage_of(t), 0, more ? stage_of(t + 1) : nullptr, 0, t + 1 < ntiles ? t + 1 : -1);
+      }
+      {   // the last full block has no successor to compute scores for
+        bf16x8 vf[2][2];
+        v_frags(stage_of(nfull - 1), 1, vf);
+        finish_block(sc_a, vf);
+      }
+      if (RAGGED) {
+        block(stage_of(ntiles - 1), ntiles - 1, 0, false);
+        block(stage_of(ntiles - 1), ntiles - 1, 1, false);
+      }
+    }
+    // did some score leave the window above the reference?  Then every wavefront of the workgroup starts over, checked.
+    const float l_chk = l_run[0] + other_half(l_run[0], low);
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (tid == 0) s_redo = 0;
+    __syncthreads();
+    if (__builtin_amdgcn_ballot_w64(!(l_chk < kAttnBig)) != 0 && lane == 0) s_redo = 1;
+    __syncthreads();
+    if (s_redo != 0) {
+      m_ref[0] = 0.f; l_run[0] = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { o[0][0][r] = 0.f; o[0][1][r] = 0.f; negm[0][r] = 0.f; }
+      issue(0, 0);
+      if (ntiles > 1) issue(1, 1);
+    }
+    if (s_redo == 0) goto finished;
+  }
+  {
   int stage = 0;
   for (int t = 0; t < ntiles; ++t) {
-    // tile t has landed once at most the loads of tile t + 1 are outstanding (a partial last tile waits by itself)
-    if (NSTG > 2 && t + 1 < ntiles && !(RAGGED && t + 2 == ntiles)) wait_vmcnt<4>(); else wait_vmcnt<0>();
-    __syncthreads();       // tile t is complete for every wavefront, and everybody is done with tile t - 1
-    if (t + NSTG - 1 < ntiles) {
-      int target = stage + NSTG - 1;
-      if (target >= NSTG) target -= NSTG;
-      issue(t + NSTG - 1, target);
-    }
+    open_tile(t, stage);
     const char* Ks = lds + stage * kAttn2Stage;
     block(Ks, t, 0, t == 0);
     block(Ks, t, 1, false);
     if (++stage == NSTG) stage = 0;
   }
+  }
+finished:
 #pragma unroll
   for (int s = 0; s < QSETS; ++s) {
     const float l_tot = l_run[s] + other_half(l_run[s], low);
@@ -1876,7 +2005,9 @@ void set_attn_variant(int v) { g_attn_variant = v; }
 static int attn_auto_variant(int bh, int l, int lk) {
   // measured on the self-attention shapes of the SD-sized models: the second-generation kernel with 32 queries per
   // wavefront is 8-20 % faster from a few hundred keys on; with one or two key tiles (cross-attention to the text,
-  // the deepest level) its longer prologue loses, and 64 queries per wavefront (two wavefronts per SIMD) never won
+  // the deepest level) its longer prologue loses, and 64 queries per wavefront (two wavefronts per SIMD) never won.
+  // The pipelined variant (3) is 4-10 % faster launched alone and 1 % slower inside the concurrent schedule (its 64 KiB of
+  // LDS and two wavefronts per SIMD leave less room for the other streams' workgroups), so it stays a selectable variant.
   (void)bh; (void)l;
   return lk > 256 ? 1 : 0;
 }
@@ -1906,7 +2037,10 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
       const float sl2 = scale * 1.44269504088896341f;
 #define AD_ATTN2(QS, RG) hipLaunchKernelGGL((k_attn_mfma2<QS, RG>), grid, dim3(256), 0, s, (const bf16*)q, (const bf16*)k, (const bf16*)v, \
                                             (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, sl2, qb)
-      if (variant == 2) { if (lk & 63) AD_ATTN2(2, true); else AD_ATTN2(2, false); }
+      if (variant == 3) {
+        if (lk & 63) hipLaunchKernelGGL((k_attn_mfma2<1, true, 4, 2, true>), grid, dim3(256), 0, s, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, sl2, qb);
+        else hipLaunchKernelGGL((k_attn_mfma2<1, false, 4, 2, true>), grid, dim3(256), 0, s, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, sl2, qb);
+      } else if (variant == 2) { if (lk & 63) AD_ATTN2(2, true); else AD_ATTN2(2, false); }
       else { if (lk & 63) AD_ATTN2(1, true); else AD_ATTN2(1, false); }
 #undef AD_ATTN2
       AD_HIP(hipGetLastError());
@@ -2700,7 +2834,7 @@ ad_status ad_tune_conv_tile(int tile) {
 }
 
 ad_status ad_tune_attention(int variant) {
-  if (variant < -1 || variant > 2) AD_FAIL(AD_ERR_INVALID, "variant must be -1, 0, 1 or 2");
+  if (variant < -1 || variant > 3) AD_FAIL(AD_ERR_INVALID, "variant must be -1 .. 3");
   set_attn_variant(variant);
   return AD_OK;
 }

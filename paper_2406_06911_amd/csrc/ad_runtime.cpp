@@ -219,7 +219,13 @@ static ad_status run_component(Ctx& c, int comp, int lane, const void* const* in
         if (!latent) AD_FAIL(AD_ERR_STATE, "conv_in: missing latent");
         AD_TRY(launch_pack_latent(e.dt, (const float*)latent, g.frames > 0, latent_scale, scale_ref, g.latent_channels, g.height, g.width, g.batch, e.temp(0), s));
         if (latent_consumed) AD_HIP(hipEventRecord(latent_consumed, s));
-        AD_TRY(e.conv(e.temp(0), nullptr, kConvInK, 0, g.height, g.width, 0, 1, 1, u.w_first, u.w_first + 1, nullptr, nullptr, e.tensor_out(ui)));
+        {   // a 1x1 GEMM over the im2col'ed latent: K = 9 latent channels zero-padded to kConvInK
+          WView wv{c};
+          ConvArgs a{e.dt, e.temp(0), nullptr, kConvInK, 0, g.batch, g.height, g.width, 0, 1, 1, wv.at(u.w_first), c.weights[u.w_first].info.shape[0],
+                     wv.f32(u.w_first + 1), nullptr, 0, nullptr, e.tensor_out(ui), OUT_ROWMAJOR, 0, e.temp(9), e.ws.temp_bytes[9]};
+          a.k_real = 9 * g.latent_channels;
+          AD_TRY(launch_conv(a, s));
+        }
         break;
       }
       case AD_UNIT_RES: {

@@ -251,7 +251,7 @@ def mfma2_contract(q, d, variant, dtype, transposed, lk):
     more rounding than the first kernel, which scales the fp32 scores).  That operand rounding is part of the kernel's
     contract like the bf16 storage of q itself, so the oracle is given the same operand: returns the q (fp64) whose
     plain softmax(q k^T / sqrt(d)) equals 2^(q' k^T) for the rounded q'.  Other kernels: q unchanged."""
-    second = variant in (1, 2) or (variant == -1 and lk > 256)
+    second = variant in (1, 2, 3) or (variant == -1 and lk > 256)
     if not (second and dtype == B.AD_BF16 and d == 64 and transposed):
         return q
     c32 = np.float32(1.0) / np.sqrt(np.float32(d)) * LOG2E_F32
@@ -287,7 +287,7 @@ ATT_CASES = [
 ]
 
 
-@pytest.fixture(params=[-1, 0, 1, 2], ids=["auto", "gen1", "gen2_q32", "gen2_q64"])
+@pytest.fixture(params=[-1, 0, 1, 2, 3], ids=["auto", "gen1", "gen2_q32", "gen2_q64", "gen2_pipelined"])
 def attn_variant(request):
     """Forces one of the MFMA attention kernels (applies to bf16, head width 64, transposed v; other calls are unaffected)."""
     B.check(lib.ad_tune_attention(request.param))
