@@ -24,11 +24,11 @@ PEAK_HBM_GBS = 8000.0
 # `rocprofv3 --pmc` runs of this file (FETCH_SIZE, WRITE_SIZE; KiB per dispatch scaled by the factors 2.00 and 1.00 that the
 # same counters show for the 2^26-element sampler launch).  Commands and tables: profiles/bench_sd21_768_all_kernels.md.
 MEASURED_TRAFFIC = {"sd21_768": {
-    "igemm_bf16_128x128_p3": 92210413, "igemm_bf16_128x128_dma": 56103632, "igemm_bf16_256x128_p3": 76244019,
-    "igemm_bf16_64x64_p3": 25199724, "igemm_bf16_128x128_p3_splitk": 52933017,
-    "igemm_bf16_256x128_p3_splitk": 119020846, "splitk_reduce": 17823279, "attn_mfma_bf16": 22606982,
-    "gn_apply": 17511113, "gn_partial": 7280061, "layernorm": 13111232, "igemm_bf16_64x64_splitk": 31000200,
-    "linear_rows": 5868024, "gn_small": 3070976}}
+    "igemm_bf16_128x128_p3": 91963135, "igemm_bf16_128x128_dma": 56108535, "igemm_bf16_256x128_p3": 75786808,
+    "igemm_bf16_64x64_p3": 25692599, "igemm_bf16_128x128_p3_splitk": 52864068,
+    "igemm_bf16_256x128_p3_splitk": 119037697, "splitk_reduce": 18418274, "attn_mfma_bf16": 23346674,
+    "gn_apply": 17512630, "gn_partial": 7287290, "layernorm": 13111232, "igemm_bf16_64x64_splitk": 51743432,
+    "linear_rows": 5601074, "gn_small": 3033907}}
 
 
 TRAFFIC_SOURCE = "not measured in this run: FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this file, profiles/bench_sd21_768_all_kernels.md"
