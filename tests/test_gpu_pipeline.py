@@ -10,6 +10,7 @@ from gpu_util import DEV, dev, dev_f32, host, nchw_to_nhwc, nhwc_to_nchw, quanti
 from oracle.asyncdiff import Pipeline
 from oracle.unet import UNetConfig, weight_manifest
 from paper_2406_06911_amd import binding as B
+from progress import progress
 
 pytestmark = pytest.mark.gpu
 
@@ -369,6 +370,7 @@ def test_state_errors():
 @pytest.fixture(scope="module")
 def full_size_weights():
     d = CONFIGS["sd21_768"]
+    progress("drawing the weights of sd21_768")
     return SI.make_weights(weight_manifest(UNetConfig(**d)), bf16_exact=True)
 
 
@@ -388,8 +390,10 @@ def test_full_size_first_units_match_oracle(full_size_weights):
     text = quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), B.AD_BF16)
     taus = __import__("oracle.sampler", fromlist=["timesteps"]).timesteps(50)
     x = np.broadcast_to(noise.astype(np.float64), (d["batch"],) + noise.shape).copy()
+    progress("oracle: first three units of sd21_768")
     ref = run_units(ocfg, units, 0, last, sub, {-1: x}, taus[0], text.astype(np.float64), None)
 
+    progress("gpu: loading the weights")
     m = ad.AsyncDiff(d, 4, 3, 1, B.AD_BF16, cuts=[last + 1, 28, 39])
     m.allocate(DEV)
     m.load_weights(full_size_weights)
@@ -419,6 +423,7 @@ def test_full_size_bench_configuration_properties(full_size_weights):
     d_text = dev(quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), B.AD_BF16), B.AD_BF16)
 
     def trajectory(n, cuts, warm, streams, graphs, rounds=None):
+        progress(f"gpu: trajectory with {n} component(s) on {streams} stream(s), graphs {graphs}")
         m = ad.AsyncDiff(d, n, warm, 1, B.AD_BF16, cuts=cuts)
         m.allocate(DEV)
         m.load_weights(full_size_weights)
@@ -540,7 +545,7 @@ def test_video_full_size_first_units_and_properties():
     units = build_units(ocfg)
     last = 2
     assert units[last].kind == "tfm"
-    print("drawing weights", flush=True)
+    progress("drawing weights")
     wts = SI.make_weights(weight_manifest(ocfg), bf16_exact=True)
     off = dict(wts)
     tname = units[last].name
@@ -551,16 +556,16 @@ def test_video_full_size_first_units_and_properties():
     noise = SI.make_video_latent(d["frames"], d["latent_channels"], d["height"], d["width"])
     text = quantize(SI.make_text(1, d["ctx_len"], d["ctx_dim"]), B.AD_BF16)
     taus = __import__("oracle.sampler", fromlist=["timesteps"]).timesteps(25)
-    print("oracle: first two units", flush=True)
+    progress("oracle: first two units")
     ref = run_units(ocfg, units, 0, 1, sub, {-1: noise.astype(np.float64)}, taus[0], text.astype(np.float64), None)
     # the temporal layer never mixes positions: its reference is evaluated on a sample of them (corners included)
-    print("oracle: temporal layer on sampled positions", flush=True)
+    progress("oracle: temporal layer on sampled positions")
     hw = d["height"] * d["width"]
     pos = np.unique(np.concatenate([[0, d["width"] - 1, hw - d["width"], hw - 1],
                                     np.random.default_rng(11).integers(0, hw, 252)]))
     z = ref[1].reshape(d["frames"], -1, hw)[:, :, pos][..., None]             # [frames, C, n, 1]
     ref_t = _temporal(ocfg, units[last], sub, z)[..., 0]                        # [frames, C, n]
-    print("gpu", flush=True)
+    progress("gpu")
 
     cuts = [last + 1, 28, 39]
     d_text = dev(text, B.AD_BF16)
@@ -650,11 +655,11 @@ def test_full_size_whole_unet_matches_oracle(full_size_weights, name):
     got = host(eps)
     m.close()
     torch.cuda.empty_cache()
-    print("oracle: whole UNet forward", flush=True)
+    progress("oracle: whole UNet forward")
     x = np.broadcast_to(noise.astype(np.float64), (d["batch"],) + noise.shape).copy()
     ref = unet_forward(ocfg, full_size_weights, x, taus[0], text.astype(np.float64))
     err = rel_l2(got, ref)
-    print(f"whole UNet at full size ({name}): rel L2 {err:.3e}", flush=True)
+    progress(f"whole UNet at full size ({name}): rel L2 {err:.3e}")
     assert got.shape == ref.shape and err < 2e-2
 
 
@@ -686,6 +691,7 @@ def test_full_size_sdxl_first_units_match_oracle():
     units = build_units(ocfg)
     last = 6
     assert [u.kind for u in units[:last + 1]] == ["conv_in", "res", "res", "down", "res", "tfm", "res"]
+    progress("drawing the weights of sdxl_1024")
     wts = SI.make_weights(weight_manifest(ocfg), bf16_exact=True)
     prefixes = tuple(units[i].name + "." for i in range(last + 1)) + ("time.", "pool.")
     sub = {k: np.asarray(v, np.float64) for k, v in wts.items() if k.startswith(prefixes)}
@@ -694,8 +700,10 @@ def test_full_size_sdxl_first_units_match_oracle():
     pooled = SI.make_pooled(d["batch"], d["pooled_dim"])
     taus = __import__("oracle.sampler", fromlist=["timesteps"]).timesteps(50)
     x = np.broadcast_to(noise.astype(np.float64), (d["batch"],) + noise.shape).copy()
+    progress("oracle: first seven units")
     ref = run_units(ocfg, units, 0, last, sub, {-1: x}, taus[0], text.astype(np.float64), pooled)
 
+    progress("gpu: loading the weights")
     m = ad.AsyncDiff(d, 4, 3, 2, B.AD_BF16, cuts=[last + 1, 15, 27])
     m.allocate(DEV)
     m.load_weights(wts)
@@ -727,13 +735,13 @@ def test_full_size_async_round_components_match_oracle(full_size_weights):
     case = Case("sd21_768", B.AD_BF16, 4, 1, 1, 2, cfg_scale=7.5, wts=full_size_weights)
     assert [a for a, _ in case.m.partition()] == [0, 10, 31, 40]          # conv_in.. | d1.ds.. | u2.us.. | u0.0.tfm..out
     log = []
-    print("oracle: two steps of four components", flush=True)
+    progress("oracle: two steps of four components")
     worst = run_components_isolated(case, log)
     rounds = sorted({r for r, _, _, _ in log})
     assert rounds == [0, 1] and sorted({c for _, c, _, _ in log}) == [1, 2, 3, 4]
-    print(f"full-size warm-up step and first asynchronous round: worst per-tensor rel L2 {worst:.3e}", flush=True)
+    progress(f"full-size warm-up step and first asynchronous round: worst per-tensor rel L2 {worst:.3e}")
     for r in rounds:
-        print("  round", r, " ".join(f"c{c}/u{u}:{e:.1e}" for rr, c, u, e in log if rr == r), flush=True)
+        progress(f"  round {r} " + " ".join(f"c{c}/u{u}:{e:.1e}" for rr, c, u, e in log if rr == r))
     case.m.close()
 
 
@@ -745,7 +753,7 @@ def _single_unit_against_oracle(name, unit, N, cuts, comp, T, sampler, seed):
     ocfg = UNetConfig(**d)
     units = build_units(ocfg)
     u = units[unit]
-    print("drawing weights", flush=True)
+    progress("drawing weights")
     wts = SI.make_weights(weight_manifest(ocfg), bf16_exact=True)
     prefixes = (u.name + ".", "time.", "pool.")
     sub = {k: np.asarray(v, np.float64) for k, v in wts.items() if k.startswith(prefixes)}
@@ -755,13 +763,14 @@ def _single_unit_against_oracle(name, unit, N, cuts, comp, T, sampler, seed):
     x = quantize(SI.make_array((d["batch"], u.c_in, u.h_in, u.w_in), seed), B.AD_BF16)
     taus = __import__("oracle.sampler", fromlist=["timesteps"]).timesteps(T)
     step = 3
-    print(f"oracle: unit {u.name}", flush=True)
+    progress(f"oracle: unit {u.name}")
     ref = run_units(ocfg, units, unit, unit, sub, {unit - 1: x.astype(np.float64)}, taus[step], text.astype(np.float64), pooled)[unit]
-    print("gpu", flush=True)
+    progress("gpu: loading the weights")
     m = ad.AsyncDiff(d, N, 1, 1, B.AD_BF16, cuts=cuts)
     m.allocate(DEV)
     m.load_weights(wts)
     del wts
+    progress("gpu: forward")
     m.reset(T, sampler=sampler)
     assert m.partition()[comp - 1] == (unit, unit)
     ins, outs = m.component_io(comp)
@@ -777,7 +786,7 @@ def _single_unit_against_oracle(name, unit, N, cuts, comp, T, sampler, seed):
     err = rel_l2(got, ref)
     # the residual path passes x through unchanged: also compare what the unit adds
     err_delta = rel_l2(got - x, ref - x)
-    print(f"{name} unit {u.name}: rel L2 {err:.3e}, of the unit's own contribution {err_delta:.3e}", flush=True)
+    progress(f"{name} unit {u.name}: rel L2 {err:.3e}, of the unit's own contribution {err_delta:.3e}")
     assert err < 2e-2
     return err, err_delta
 
