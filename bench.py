@@ -26,7 +26,8 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC = {"sd21_768": {
     "igemm_bf16_128x128_p3": 91963135, "igemm_bf16_128x128_dma": 56108535, "igemm_bf16_256x128_p3": 75786808,
     "igemm_bf16_64x64_p3": 25692599, "igemm_bf16_128x128_p3_splitk": 52864068,
-    "igemm_bf16_256x128_p3_splitk": 119037697, "splitk_reduce": 18418274, "attn_mfma_bf16": 23346674,
+    "igemm_bf16_256x128_p3_splitk": 119037697, "splitk_reduce": 18418274, "attn_mfma2_bf16": 33214464,
+    "attn_mfma_bf16": 14639820,
     "gn_apply": 17512630, "gn_partial": 7287290, "layernorm": 13111232, "igemm_bf16_64x64_splitk": 51743432,
     "linear_rows": 5601074, "gn_small": 3033907}}
 

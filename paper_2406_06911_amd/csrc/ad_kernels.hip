@@ -2024,9 +2024,11 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
     if (ldv < round_up(lk, 64) || (ldq | ldk | ldv | ldo) % 8) AD_FAIL(AD_ERR_INVALID, "attention: MFMA path needs padded, 8-aligned strides");
     // the kernel walks K and V^T with 32-bit element offsets from the (sample, head) base
     if ((long long)(lk + 64) * ldk >= (1LL << 32) || 64LL * ldv + lk >= (1LL << 32)) AD_FAIL(AD_ERR_INVALID, "attention: key tensor too large");
-    ProfLaunch pl("attn_mfma_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s, batch * l, lk, c);
     int variant = g_attn_variant;
     if (variant < 0) variant = attn_auto_variant(batch * heads, l, lk);
+    // the two kernel generations are separate classes for the per-launch timing, as they are separate kernels in a trace
+    ProfLaunch pl(variant > 0 ? "attn_mfma2_bf16" : "attn_mfma_bf16", 4.0 * batch * l * lk * c, 2.0 * batch * c * (2.0 * l + 2.0 * lk), s,
+                  batch * l, lk, c);
     if (variant > 0) {
       // the tile loads address K and V^T through 32-bit byte offsets from the (sample, head) base
       if (((long long)(lk + 64) * ldk + 64) * 2 >= (1LL << 31) || (64LL * ldv + lk + 64) * 2 >= (1LL << 31))
