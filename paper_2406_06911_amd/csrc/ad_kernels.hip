@@ -1606,7 +1606,7 @@ constexpr float kAttnBig = 1.2676506e30f;         // 2^100: a 32-key row sum at 
 // one of the first 32 - the workgroup repeats its work with the checked block-by-block loop below.  The K fragments of a
 // step are fetched from LDS one step ahead, so a tile is opened (waited for, barrier) one block before its first scores:
 // three tiles are in use across that barrier plus one in flight, hence four stages (64 KiB, two workgroups per CU).
-template <int QSETS, bool RAGGED, int NSTG = 3, int OCC = (QSETS == 1 ? 3 : 2), bool PIPE = false>
+template <int QSETS, bool RAGGED, int NSTG = 3, int OCC = (QSETS == 1 ? 3 : 2), int PIPE = 0>
 __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256) void k_attn_mfma2(
     const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ Vt, bf16* __restrict__ O, int L, int Lk, int C,
     int ldq, int ldk, int ldv, int ldo, float scale_log2, int qblocks) {
@@ -1629,41 +1629,38 @@ __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256)
   // LDS row r keeps its 16-byte chunk c at position c ^ ((r >> 1) & 7): the 16 rows that one quarter of a wavefront
   // reads in a cycle (same chunk, consecutive rows) then fall on 16 different 16-byte bank groups of the 256-byte
   // bank window (rows r and r + 8 collide with the plain r & 7 swizzle)
+  // A wavefront fills the 8-row groups g = wave and wave + 4 of the K tile and of the V^T tile: both have the same swizzle
+  // column, and their rows are 32 keys (32 rows of V^T) apart, so one lane offset serves both (the distance goes into the
+  // scalar offset of the load)
   const int r8 = lane >> 3;
-  unsigned koff[2], voff[2];
-  int krow[2], scol[2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int g = wave * 2 + i;                                              // 8-row group of the tile
-    scol[i] = (lane & 7) ^ (((g * 8 + r8) >> 1) & 7);                        // chunk this lane fetches for its row
-    krow[i] = 16 * (g >> 1) + 8 * (r8 >> 2) + 4 * (g & 1) + (r8 & 3);        // key held by LDS row 8 g + r8
-    koff[i] = (unsigned)(krow[i] * ldk + scol[i] * 8) * 2;
-    voff[i] = (unsigned)((g * 8 + r8) * ldv + scol[i] * 8) * 2;
-  }
+  const int scol = (lane & 7) ^ (((wave * 8 + r8) >> 1) & 7);                // chunk this lane fetches for its row
+  const int krow = 16 * (wave >> 1) + 8 * (r8 >> 2) + 4 * (wave & 1) + (r8 & 3);   // key held by LDS row 8 wave + r8 (+ 32: row + 32)
+  const unsigned koff = (unsigned)(krow * ldk + scol * 8) * 2;
+  const unsigned voff = (unsigned)((wave * 8 + r8) * ldv + scol * 8) * 2;
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
-  const unsigned kstep = 64u * (unsigned)ldk * 2u;
+  const unsigned kstep = 64u * (unsigned)ldk * 2u, khalf = 32u * (unsigned)ldk * 2u, vhalf = 32u * (unsigned)ldv * 2u;
   auto issue = [&](int t, int stage) {
-    const unsigned st = lds_base + stage * kAttn2Stage + (unsigned)wave * 2048u;
+    const unsigned st = lds_base + stage * kAttn2Stage + (unsigned)wave * 1024u;
     const bool last = RAGGED && t == ntiles - 1;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       // keys past the end read zeros (their scores are masked, but the pad must not hold NaNs)
-      const unsigned ko = (last && t * 64 + krow[i] >= Lk) ? kOob : koff[i];
-      dma_load16(rsk, ko, (unsigned)t * kstep, st + i * 1024);
+      const unsigned ko = (last && t * 64 + krow + 32 * i >= Lk) ? kOob : koff;
+      dma_load16(rsk, ko, (unsigned)t * kstep + i * khalf, st + i * 4096);
     }
     if (!last) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) dma_load16(rsv, voff[i], (unsigned)t * 128u, st + 8192 + i * 1024);
+      for (int i = 0; i < 2; ++i) dma_load16(rsv, voff, (unsigned)t * 128u + i * vhalf, st + 8192 + i * 4096);
     } else {
       // the last, partial tile of V^T goes through registers: values of keys past the end are cleared, whatever the pad holds
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int g = wave * 2 + i;
-        bf16x8 v = *(const bf16x8*)(vbase + (size_t)(g * 8 + r8) * ldv + t * 64 + scol[i] * 8);
+        const int g = wave + 4 * i;
+        bf16x8 v = *(const bf16x8*)(vbase + (size_t)(g * 8 + r8) * ldv + t * 64 + scol * 8);
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (t * 64 + scol[i] * 8 + e >= Lk) v[e] = (bf16)0.f;
-        *(bf16x8*)(lds + stage * kAttn2Stage + 8192 + wave * 2048 + i * 1024 + lane * 16) = v;
+          if (t * 64 + scol * 8 + e >= Lk) v[e] = (bf16)0.f;
+        *(bf16x8*)(lds + stage * kAttn2Stage + 8192 + g * 1024 + lane * 16) = v;
       }
     }
   };
@@ -1692,8 +1689,13 @@ __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { o[s][0][r] = 0.f; o[s][1][r] = 0.f; negm[s][r] = 0.f; }
   }
-  const int x7 = lds_swizzle(l32);
-  const int frag_row = l32 * kRowBytes;
+  // fragment offsets inside a tile: row l32, 16-byte chunk (2 c + half) at its swizzled place; K fragment ks uses c = ks,
+  // the V^T fragment of block j and 16-key half s2 uses c = 2 j + s2
+  // (c and c + 2 differ in bit 6 of the offset only)
+  int cofs[2];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) cofs[c] = l32 * kRowBytes + (((c * 2 + half) ^ lds_swizzle(l32)) << 4);
+  auto cof = [&](int c) -> int { return c < 2 ? cofs[c] : (cofs[c - 2] ^ 64); };
   const bf16x2 ones = {(bf16)1.f, (bf16)1.f};
   auto mask_tail = [&](f32x16 (&sc)[QSETS], int t, int j) {
     const int key0 = t * 64 + j * 32 + 8 * half;          // register r: key key0 + 16 (r / 8) + r % 8
@@ -1723,7 +1725,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256)
     const char* Vs = Ks + 8192;
     bf16x8 kf[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) kf[ks] = *(const bf16x8*)(Ks + j * 32 * kRowBytes + frag_row + (((ks * 2 + half) ^ x7) << 4));
+    for (int ks = 0; ks < 4; ++ks) kf[ks] = *(const bf16x8*)(Ks + j * 32 * kRowBytes + cof(ks));
     f32x16 sc[QSETS];
 #pragma unroll
     for (int s = 0; s < QSETS; ++s) {
@@ -1737,7 +1739,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256)
     for (int d = 0; d < 2; ++d)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2)
-        vf[d][s2] = *(const bf16x8*)(Vs + d * 32 * kRowBytes + frag_row + (((j * 4 + s2 * 2 + half) ^ x7) << 4));
+        vf[d][s2] = *(const bf16x8*)(Vs + d * 32 * kRowBytes + cof(2 * j + s2));
     if (RAGGED && t == ntiles - 1) mask_tail(sc, t, j);
     bf16x8 pb[QSETS][2];
     float psum[QSETS];
@@ -1757,7 +1759,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256)
         for (int r = 0; r < 16; ++r) sc[s][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          const bf16x8 kk = *(const bf16x8*)(Ks + j * 32 * kRowBytes + frag_row + (((ks * 2 + half) ^ x7) << 4));
+          const bf16x8 kk = *(const bf16x8*)(Ks + j * 32 * kRowBytes + cof(ks));
           sc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk, qf[s][ks], sc[s], 0, 0, 0);
         }
       }
@@ -1808,11 +1810,11 @@ __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256)
       issue(t + AHEAD, target);
     }
   };
-  if constexpr (PIPE) {
+  if constexpr (PIPE != 0) {
     static_assert(QSETS == 1 && NSTG == 4, "the pipelined path is written for one query set and four stages");
     __shared__ int s_redo;
     const int nfull = RAGGED ? ntiles - 1 : ntiles;     // tiles without a ragged tail
-    auto stage_of = [&](int t) { return lds + (t & (NSTG - 1)) * kAttn2Stage; };
+    auto stage_of = [&](int t) { return lds + (t % NSTG) * kAttn2Stage; };
     open_tile(0, 0);
     block(lds, 0, 0, true);                              // fixes the reference: exact maximum of the first 32 keys
     if (nfull == 0) {
@@ -1820,14 +1822,14 @@ __global__ __attribute__((amdgpu_waves_per_eu(OCC, OCC))) __launch_bounds__(256)
     } else {
       auto k_frags = [&](const char* Ks, int j, bf16x8 (&kf)[4]) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) kf[ks] = *(const bf16x8*)(Ks + j * 32 * kRowBytes + frag_row + (((ks * 2 + half) ^ x7) << 4));
+        for (int ks = 0; ks < 4; ++ks) kf[ks] = *(const bf16x8*)(Ks + j * 32 * kRowBytes + cof(ks));
       };
       auto v_frags = [&](const char* Ks, int j, bf16x8 (&vf)[2][2]) {
 #pragma unroll
         for (int d = 0; d < 2; ++d)
 #pragma unroll
           for (int s2 = 0; s2 < 2; ++s2)
-            vf[d][s2] = *(const bf16x8*)(Ks + 8192 + d * 32 * kRowBytes + frag_row + (((j * 4 + s2 * 2 + half) ^ x7) << 4));
+            vf[d][s2] = *(const bf16x8*)(Ks + 8192 + d * 32 * kRowBytes + cof(2 * j + s2));
       };
       auto score_chain = [&](const bf16x8 (&kf)[4]) {
         f32x16 sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0][0], negm[0], 0, 0, 0);
@@ -2040,8 +2042,8 @@ ad_status launch_attention(int dtype, const void* q, const void* k, const void* 
 #define AD_ATTN2(QS, RG) hipLaunchKernelGGL((k_attn_mfma2<QS, RG>), grid, dim3(256), 0, s, (const bf16*)q, (const bf16*)k, (const bf16*)v, \
                                             (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, sl2, qb)
       if (variant == 3) {
-        if (lk & 63) hipLaunchKernelGGL((k_attn_mfma2<1, true, 4, 2, true>), grid, dim3(256), 0, s, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, sl2, qb);
-        else hipLaunchKernelGGL((k_attn_mfma2<1, false, 4, 2, true>), grid, dim3(256), 0, s, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, sl2, qb);
+        if (lk & 63) hipLaunchKernelGGL((k_attn_mfma2<1, true, 4, 2, 1>), grid, dim3(256), 0, s, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, sl2, qb);
+        else hipLaunchKernelGGL((k_attn_mfma2<1, false, 4, 2, 1>), grid, dim3(256), 0, s, (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)out, l, lk, c, ldq, ldk, ldv, ldo, sl2, qb);
       } else if (variant == 2) { if (lk & 63) AD_ATTN2(2, true); else AD_ATTN2(2, false); }
       else { if (lk & 63) AD_ATTN2(1, true); else AD_ATTN2(1, false); }
 #undef AD_ATTN2
