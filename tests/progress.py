@@ -3,7 +3,10 @@ capture on, nothing it prints is seen until it ends, and a run that is silent fo
 watches it.  `progress` writes one line to the real stdout, capture or not; tests call it at the steps of their own
 work (weights drawn, oracle done, GPU done)."""
 
+import time
+
 _capture_manager = None
+_t0 = time.time()
 
 
 def set_capture_manager(manager):
@@ -16,4 +19,4 @@ def progress(msg):
         print(msg, flush=True)
         return
     with _capture_manager.global_and_fixture_disabled():
-        print(f"\n[progress] {msg}", end="", flush=True)
+        print(f"\n[progress +{time.time() - _t0:.0f}s] {msg}", end="", flush=True)
