@@ -180,7 +180,8 @@ def _temporal(cfg, u, wts, z):
     z: [frames, C, H, W] -> z + Out(MHA_over_frames(LN(z))); no positional term, no feed-forward."""
     n = u.name
     f, c, hh, ww = z.shape
-    t = z.reshape(f, c, hh * ww).transpose(2, 0, 1)            # [positions, frames, C]: batch = position
+    # [positions, frames, C]: batch = position (copied into that order: matmul on the strided view leaves the BLAS path)
+    t = np.ascontiguousarray(z.reshape(f, c, hh * ww).transpose(2, 0, 1))
     y = P.layer_norm(t, wts[f"{n}.temp.ln.g"], wts[f"{n}.temp.ln.b"], cfg.ln_eps)
     a = P.attention(P.linear(y, wts[f"{n}.temp.q.w"]), P.linear(y, wts[f"{n}.temp.k.w"]),
                     P.linear(y, wts[f"{n}.temp.v.w"]), cfg.temporal_heads)
