@@ -657,9 +657,13 @@ __global__ __launch_bounds__(128 * WM) void k_igemm_p3(IgemmParams p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
-  const int wave_m = wave >> 1, wave_n = wave & 1;
+  // wavefronts w and w + 4 share a SIMD: with wave_n = w / WM they hold different column halves whenever a SIMD has two,
+  // so when the tile's second half lies beyond N (N = 320: 2.5 tiles of 128) every SIMD keeps one working wavefront
+  const int wave_m = wave % WM, wave_n = wave / WM;
   const TileId tid3 = tile_of(p);
   const int m0 = tid3.m_tile * BM, n0 = tid3.n_tile * BN;
+  // all 64 columns of this wavefront are padding: it takes part in the tile loads and the barriers and skips the rest
+  const bool idle = n0 + wave_n * WTN >= p.N;
   const u32x4 rs0 = make_rsrc_words(p.src0, p.bytes0), rs1 = make_rsrc_words(p.src1, p.bytes1);
   const u32x4 rsw = make_rsrc_words(p.w, p.bytes_w);
 
@@ -761,8 +765,9 @@ __global__ __launch_bounds__(128 * WM) void k_igemm_p3(IgemmParams p) {
   };
   int stage = 0;
   // PHASE 2: a next tile follows and the tile after it is fetched; 1: a next tile follows; 0: last tile
-  auto k_tile = [&](auto phase) {
+  auto k_tile = [&](auto phase, auto idle_c) {
     constexpr int PHASE = decltype(phase)::value;
+    constexpr bool IDLE = decltype(idle_c)::value;
     int target = stage + NSTAGE - 1;
     if (target >= NSTAGE) target -= NSTAGE;
     int next = stage + 1;
@@ -782,11 +787,11 @@ __global__ __launch_bounds__(128 * WM) void k_igemm_p3(IgemmParams p) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const int g = i * TN + j;
-          Mma<T>::run(fr[ks & 1][i], fr[ks & 1][TM + j], acc[i][j]);
+          if constexpr (!IDLE) Mma<T>::run(fr[ks & 1][i], fr[ks & 1][TM + j], acc[i][j]);
           // fragment r of the next k-step follows MFMA group floor(r NG / (TM+TN)); load l follows slot floor(l 3NG / OPS)
 #pragma unroll
           for (int r = 0; r < TM + TN; ++r)
-            if (r * NG / (TM + TN) == g) {
+            if (!IDLE && r * NG / (TM + TN) == g) {
               if (ks < 3) read_frag(st, ks + 1, r);
               else if (PHASE >= 1) read_frag(sn, 4, r);
             }
@@ -805,12 +810,19 @@ __global__ __launch_bounds__(128 * WM) void k_igemm_p3(IgemmParams p) {
   // issue order so far: B(0), B(1), A(0), A(1): tile 0 is complete once only A(1) is outstanding
   if (nkt > 1) wait_vmcnt<AG>(); else wait_vmcnt<0>();
   __syncthreads();
+  int kt = 0;
+  if (idle) {
+    for (; kt + 2 < nkt; ++kt) k_tile(std::integral_constant<int, 2>{}, std::true_type{});
+    for (; kt + 1 < nkt; ++kt) k_tile(std::integral_constant<int, 1>{}, std::true_type{});
+    k_tile(std::integral_constant<int, 0>{}, std::true_type{});
+    __syncthreads();
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < TM + TN; ++r) read_frag(lds, 0, r);
-  int kt = 0;
-  for (; kt + 2 < nkt; ++kt) k_tile(std::integral_constant<int, 2>{});
-  for (; kt + 1 < nkt; ++kt) k_tile(std::integral_constant<int, 1>{});
-  k_tile(std::integral_constant<int, 0>{});
+  for (; kt + 2 < nkt; ++kt) k_tile(std::integral_constant<int, 2>{}, std::false_type{});
+  for (; kt + 1 < nkt; ++kt) k_tile(std::integral_constant<int, 1>{}, std::false_type{});
+  k_tile(std::integral_constant<int, 0>{}, std::false_type{});
   __syncthreads();     // every wavefront holds its last fragments: LDS can be reused by the epilogue
   igemm_epilogue<T, BM, WTM, WTN, TM, TN, MODE>(p, acc, m0, n0, wave_m, wave_n, l32, half, lds + wave * (WTM * kPitch), tid3.split);
 }
