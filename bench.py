@@ -49,9 +49,10 @@ def run_rounds(m, latent, text, streams, n):
 
 
 def study_saturation(ad, torch, d, r, dtype, wts, dev, cuts, K):
-    """One context (N streams, graph replay) against two independent contexts enqueued alternately on 2N streams.  The second
-    context's kernels are free to fill whatever the first leaves idle, at round boundaries in particular, so
-    (time of a pair of rounds) / 2 is a lower bound for the round time any cross-round overlap within one context can reach."""
+    """One context (N streams, graph replay, barrier rounds) against two independent contexts enqueued alternately on 2N streams.
+    The second context's kernels are free to fill whatever the first leaves idle, at round boundaries in particular.  It was
+    meant as a bound on what overlap across rounds can gain and gave 1.00-1.02x; the per-edge mode, measured directly, gains
+    2.7 % - two contexts also compete for caches and hardware queues, which hides what the filled gaps win."""
     import synthetic_inputs as SI
     N, w, S = r["N"], r["w"], r["S"]
     sampler = ad.AD_DDIM if r["sampler"] == "ddim" else ad.AD_EULER
@@ -104,6 +105,9 @@ def main():
     ap.add_argument("--tuned", type=int, default=1, help="1 (default, with --cuts flops): after the headline measurement also time the partition balanced by "
                     "measured unit times and refined by whole-round timings, and report it as tuned_partition")
     ap.add_argument("--repeats", type=int, default=10, help="the timed region of --steps rounds is repeated this many times; value is the median")
+    ap.add_argument("--edges", type=int, default=-1, help="per-edge mode for the timed region (no barrier between asynchronous rounds: events per producer / "
+                    "consumer edge, three copies of the stored tensors; same results bit for bit).  -1 (default): on where the library "
+                    "offers it (stride 1, --wrap 0), and the barrier rounds are timed beside it; 0: barrier rounds only; 1: per-edge only")
     ap.add_argument("--wrap", type=int, default=0, help="1: wrapped segmentation (first and last segment in one component; stride 1, FLOP-balanced cuts)")
     ap.add_argument("--tile", type=int, default=-1, help="GEMM kernel family override for measurements (ad_tune_conv_tile); -1 = automatic")
     ap.add_argument("--order", type=int, default=-1, help="GEMM workgroup order override for measurements (ad_tune_conv_order); -1 = automatic")
@@ -184,11 +188,12 @@ def main():
         T = w + max(W + K * R, min(K, 10) + 2) * S
         log(f"repeats reduced to {R} so that one schedule (T <= 1000) holds every timed round")
 
-    def timed_rounds(model, graphs, streams, k, reps):
+    def timed_rounds(model, graphs, streams, k, reps, edges=False):
         """w warm-up rounds of the method and W untimed rounds, then reps x (exactly k rounds bracketed by device synchronisation).
         Returns the list of seconds per repetition and the host enqueue time of the first one."""
         model.set_graph_mode(bool(graphs))
         model.reset(T, sampler=sampler, cfg_scale=r["cfg_scale"])
+        model.set_edge_mode(bool(edges))
         lat = noise.clone()
         ss = [torch.cuda.Stream(device=dev) for _ in range(streams)]
         torch.cuda.synchronize()
@@ -206,14 +211,26 @@ def main():
         return secs, host, lat, ss
 
     # ---- timed region: concurrent components -----------------------------------------------------
-    secs, t_host, lat, ss = timed_rounds(m, args.graphs, n_streams, K, R)
+    edges_ok = S == 1 and not args.wrap
+    if args.edges == 1 and not edges_ok:
+        sys.exit("--edges 1 needs stride 1 and --wrap 0")
+    use_edges = edges_ok and args.edges != 0
+    secs, t_host, lat, ss = timed_rounds(m, args.graphs, n_streams, K, R, edges=use_edges)
     sec = float(np.median(secs))
     steps_per_s = K * S / sec
     ms_per_step = sec / (K * S) * 1e3
     spread = dict(repeats=R, timed_seconds=round(float(sum(secs)), 3), ms_per_step_min=round(min(secs) / (K * S) * 1e3, 4),
                   ms_per_step_max=round(max(secs) / (K * S) * 1e3, 4))
-    log(f"concurrent ({n_streams} streams): {steps_per_s:.2f} steps/s, {ms_per_step:.3f} ms/step (median of {R} x {K} rounds, "
-        f"{spread['ms_per_step_min']:.3f} .. {spread['ms_per_step_max']:.3f})")
+    log(f"concurrent ({n_streams} streams{', per-edge mode' if use_edges else ''}): {steps_per_s:.2f} steps/s, {ms_per_step:.3f} ms/step "
+        f"(median of {R} x {K} rounds, {spread['ms_per_step_min']:.3f} .. {spread['ms_per_step_max']:.3f})")
+    barrier = None
+    if use_edges and args.edges == -1:
+        # the same rounds with a barrier around every round (the mode of every other configuration), for comparison
+        secs_b, host_b, _, _ = timed_rounds(m, args.graphs, n_streams, K, max(1, R // 2), edges=False)
+        sec_b = float(np.median(secs_b))
+        barrier = dict(steps_per_s=round(K * S / sec_b, 3), ms_per_step=round(sec_b / (K * S) * 1e3, 4), per_edge_over_barrier=round(sec_b / sec, 4),
+                       host_enqueue_ms_per_step=round(host_b / (K * S) * 1e3, 3))
+        log(f"barrier rounds: {barrier['steps_per_s']:.2f} steps/s ({barrier['per_edge_over_barrier']:.3f}x with per-edge mode)")
     # ---- the same rounds on one stream (sequential UNet with the same kernels): graph replay and direct launches ----
     K2 = min(K, 10)
     R2 = min(R, 5)
@@ -354,7 +371,7 @@ def main():
         m2 = ad.AsyncDiff(d, N, w, S, dtype, cuts=tcuts)
         m2.allocate(dev)
         m2.load_weights(wts)
-        secs_t, _, _, _ = timed_rounds(m2, args.graphs, n_streams, K, R)
+        secs_t, _, _, _ = timed_rounds(m2, args.graphs, n_streams, K, R, edges=use_edges)
         sec_t = float(np.median(secs_t))
         tuned = dict(component_first_units=[a for a, _ in m2.partition()], steps_per_s=round(K * S / sec_t, 3),
                      ms_per_step=round(sec_t / (K * S) * 1e3, 4), over_flops_partition=round(sec / sec_t, 4),
@@ -374,13 +391,14 @@ def main():
         "dtype": "bf16" if dtype == ad.AD_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: latent {d['latent_channels']}x{d['height']}x{d['width']}, batch {d['batch']} ({'frames' if frames else 'guidance'}), "
                                f"N={N} components on {n_streams} HIP streams, warm-up {w}, stride {S}, {r['sampler']}",
-                   "n_components": N, "stride": S, "streams": n_streams, "hip_graphs": bool(args.graphs), "partition": ("wrapped, " if args.wrap else "") + (("flops" if args.wrap else args.cuts) if args.cuts in ("auto", "flops") else "given"),
+                   "n_components": N, "stride": S, "streams": n_streams, "hip_graphs": bool(args.graphs), "per_edge_mode": bool(use_edges), "partition": ("wrapped, " if args.wrap else "") + (("flops" if args.wrap else args.cuts) if args.cuts in ("auto", "flops") else "given"),
                    "component_first_units": part_units, "flops_per_step": flops_step},
         "timing": spread,
         "component_evals_per_s": round(steps_per_s / S * n_par, 2),
         "sequential_steps_per_s": round(seq_steps_per_s, 3),
         "sequential_one_stream": {k: round(v, 3) for k, v in seq.items()},
         "concurrent_over_sequential": round(steps_per_s / seq_steps_per_s, 4),
+        "barrier_rounds": barrier,
         "tuned_partition": tuned,
         "host_enqueue_ms_per_step": round(t_host / (K * S) * 1e3, 3),
         "mfma_frac_whole_step": round(flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),

@@ -77,7 +77,7 @@ EXPORTS = [
     "ad_reset", "ad_get_timesteps", "ad_num_sched_rows", "ad_get_schedule", "ad_get_sampler_coeffs",
     "ad_component_forward", "ad_step", "ad_ddim_update", "ad_sampler_update_raw", "ad_get_slot_tensor", "ad_get_eps_buffer",
     "ad_conv_forward", "ad_conv_workspace_bytes", "ad_pack_conv_weight", "ad_groupnorm_scratch_bytes", "ad_groupnorm_forward", "ad_layernorm_forward",
-    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode", "ad_create_with_cuts", "ad_balance_cuts", "ad_tune_conv_order", "ad_create_wrapped", "ad_num_segments",
+    "ad_attention_forward", "ad_profile_enable", "ad_profile_clear", "ad_profile_count", "ad_profile_get", "ad_tune_conv_tile", "ad_precompute_text", "ad_set_graph_mode", "ad_set_edge_mode", "ad_create_with_cuts", "ad_balance_cuts", "ad_tune_conv_order", "ad_create_wrapped", "ad_num_segments",
     "ad_attention_frames_forward", "ad_groupnorm_forward_static", "ad_tune_attention",
 ]
 
@@ -131,6 +131,7 @@ def _load():
     L.ad_tune_attention.argtypes = [ci]
     L.ad_precompute_text.argtypes = [vp, vp, vp]
     L.ad_set_graph_mode.argtypes = [vp, ci]
+    L.ad_set_edge_mode.argtypes = [vp, ci]
     L.ad_profile_enable.argtypes = [vp, ci]
     L.ad_profile_clear.argtypes = [vp]
     L.ad_profile_count.argtypes = [vp]
@@ -292,6 +293,9 @@ class AsyncDiff:
 
     def set_graph_mode(self, on):
         check(lib.ad_set_graph_mode(self._h, int(on)))
+
+    def set_edge_mode(self, on):
+        check(lib.ad_set_edge_mode(self._h, int(on)))
 
     def precompute_text(self, text_emb, stream):
         check(lib.ad_precompute_text(self._h, _ptr(text_emb), C.c_void_p(stream.cuda_stream)))

@@ -401,11 +401,11 @@ static void plan_work(Ctx& c) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   // stored-state slots: every tensor that leaves its component (the noise prediction has its own buffers)
-  for (int s = 0; s < 2; ++s) c.slot_off[s].assign(nu, SIZE_MAX);
+  for (int s = 0; s < 3; ++s) c.slot_off[s].assign(nu, SIZE_MAX);
   for (const Component& cp : c.comps)
     for (int u : cp.out_units)
       if (u != nu - 1)
-        for (int s = 0; s < 2; ++s) c.slot_off[s][u] = take(tensor_bytes(c, u));
+        for (int s = 0; s < 3; ++s) c.slot_off[s][u] = take(tensor_bytes(c, u));
   c.eps_off.clear();
   for (int j = 0; j < c.stride; ++j) c.eps_off.push_back(take(tensor_bytes(c, nu - 1)));
   c.step_table_off = take((size_t)(kTrainSteps + 8) * sizeof(StepRec));

@@ -97,7 +97,8 @@ struct Ctx {
 
   // memory plan
   size_t weight_bytes = 0, work_bytes = 0;
-  std::vector<size_t> slot_off[2];     // per unit; SIZE_MAX when the unit's output never crosses components
+  std::vector<size_t> slot_off[3];     // per unit; SIZE_MAX when the unit's output never crosses components (the third
+                                       // copy is used by the per-edge mode only)
   std::vector<size_t> eps_off;         // per stride lane
   // cross-attention keys / values of the text embedding (constant over the steps): per unit, per layer
   std::vector<std::vector<size_t>> text_k_off, text_v_off;
@@ -136,6 +137,23 @@ struct Ctx {
     float cfg_scale = 0.f;
     std::vector<int> offsets;            // per row: component and (tau, latent, eps) step relative to the round's first step
   } round_graph[2];
+
+  // per-edge mode (ad_set_edge_mode): an asynchronous round is not bracketed by a barrier; every evaluation waits for the
+  // evaluations whose stored tensors it reads (previous round) and for the readers of the copy it overwrites (two rounds
+  // back; three copies of the stored tensors, copy = round mod 3).  Events by [component - 1][round mod 4], the sampler's by
+  // [round mod 4]; one device step counter per component (the components are in different rounds at the same time).
+  bool edge_mode = false;
+  std::vector<hipEvent_t> ev_done;
+  hipEvent_t ev_sampler[4] = {nullptr, nullptr, nullptr, nullptr};
+  struct CompGraph {
+    hipGraphExec_t exec = nullptr;
+    hipGraph_t graph = nullptr;
+    const void* latent = nullptr; const void* text = nullptr; const void* pooled = nullptr;
+    hipStream_t stream = nullptr;
+    float cfg_scale = 0.f;
+    int tau_off = 0, latent_off = 0, eps_off = 0;
+  };
+  std::vector<CompGraph> comp_graph;   // [(component - 1) * 3 + copy written]
 };
 
 // host logic

@@ -315,11 +315,21 @@ void ad_destroy(ad_ctx* ctx) {
   if (c->profiler) { prof_clear(prof_of(*c)); delete prof_of(*c); }
   for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
   if (c->ev_pack) (void)hipEventDestroy(c->ev_pack);
-  if (c->round_graph[0].exec || c->round_graph[1].exec) (void)hipDeviceSynchronize();
+  bool replayed = c->round_graph[0].exec || c->round_graph[1].exec;
+  for (auto& g : c->comp_graph) replayed = replayed || g.exec;
+  if (replayed) (void)hipDeviceSynchronize();
   for (auto& g : c->round_graph) {
     if (g.exec) (void)hipGraphExecDestroy(g.exec);
     if (g.graph) (void)hipGraphDestroy(g.graph);
   }
+  for (auto& g : c->comp_graph) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (g.graph) (void)hipGraphDestroy(g.graph);
+  }
+  for (hipEvent_t e : c->ev_done)
+    if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->ev_sampler)
+    if (e) (void)hipEventDestroy(e);
   delete c;
 }
 
@@ -459,7 +469,7 @@ ad_status ad_ddim_update(ad_ctx* ctx, void* x, const void* eps, int step_index, 
 ad_status ad_get_slot_tensor(const ad_ctx* ctx, int slot, int unit, void** ptr, size_t* bytes) {
   if (!ctx || !ptr) AD_FAIL(AD_ERR_INVALID, "null argument");
   const Ctx& c = *C(ctx);
-  if (slot < 0 || slot > 1 || unit < 0 || unit >= (int)c.units.size()) AD_FAIL(AD_ERR_INVALID, "slot/unit out of range");
+  if (slot < 0 || slot > 2 || unit < 0 || unit >= (int)c.units.size()) AD_FAIL(AD_ERR_INVALID, "slot/unit out of range");
   if (c.slot_off[slot][unit] == SIZE_MAX) AD_FAIL(AD_ERR_INVALID, "unit %d is not a stored component output", unit);
   if (!c.work_dev) AD_FAIL(AD_ERR_STATE, "no device memory bound");
   *ptr = c.work_dev + c.slot_off[slot][unit];
@@ -474,6 +484,110 @@ ad_status ad_get_eps_buffer(const ad_ctx* ctx, int j, void** ptr, size_t* bytes)
   if (!c.work_dev) AD_FAIL(AD_ERR_STATE, "no device memory bound");
   *ptr = c.work_dev + c.eps_off[j];
   if (bytes) *bytes = tensor_bytes(c, (int)c.units.size() - 1);
+  return AD_OK;
+}
+
+// Which copy of the stored tensors a schedule row reads and writes.  Barrier mode: the table's two slots.  Per-edge mode:
+// copy = round mod 3 for what a round writes, the round before for what an asynchronous round reads (a warm-up round
+// reads what it has just written).
+static inline int phys_write(const Ctx& c, const ad_sched_row& row) { return c.edge_mode ? row.round % 3 : row.write_slot; }
+static inline int phys_read(const Ctx& c, const ad_sched_row& row) {
+  if (!c.edge_mode) return row.read_slot;
+  return row.read_slot == row.write_slot ? row.round % 3 : (row.round + 2) % 3;
+}
+static inline hipEvent_t& ev_done_of(Ctx& c, int comp, int round) { return c.ev_done[(size_t)(comp - 1) * 4 + (round & 3)]; }
+
+// One asynchronous round without a barrier (per-edge mode; stride 1, sequential segmentation).  Component n runs on
+// streams[(n - 1) % ns].  Before it starts it waits for (a) the evaluations of the previous round whose stored tensors it
+// reads - for component 1 that is the sampler of the previous round, which also stands for the last component - and (b)
+// the evaluations of two rounds back that read the copy it is about to overwrite.  The sampler follows the last component on
+// its stream and waits for this round's component 1 (which has read the latent).  Nothing joins the streams: a component
+// whose producers are done starts its next round while slower components still work on this one.
+// graphs: replay one captured graph per (component, copy) instead of launching the kernels.
+static ad_status enqueue_round_edges(Ctx& c, size_t r0, size_t r1, void* latent, const void* text_emb, const void* pooled_emb,
+                                     const ad_stream* streams, int ns, bool graphs, std::vector<int>* steps_out) {
+  const int nu = (int)c.units.size();
+  const StepRec* table = (const StepRec*)(c.work_dev + c.step_table_off);
+  int* counters = (int*)(c.work_dev + c.step_counter_off);
+  const int base = c.steps_done;
+  const int g = c.rows[r0].round;
+  const size_t n = (size_t)(c.cfg.frames > 0 ? c.cfg.frames : 1) * c.cfg.latent_channels * c.cfg.height * c.cfg.width;
+  for (size_t r = r0; r < r1; ++r) {
+    const ad_sched_row& row = c.rows[r];
+    if (row.comp != (int)(r - r0) + 1) AD_FAIL(AD_ERR_STATE, "per-edge mode: a round lists its components in order");
+    const Component& cp = c.comps[row.comp - 1];
+    hipStream_t s = (hipStream_t)streams[(row.comp - 1) % ns];
+    if (cp.in_units.size() > 64 || cp.out_units.size() > 64) AD_FAIL(AD_ERR_INVALID, "too many component tensors");
+    // (a) producers of the previous round
+    bool waited[64] = {false};
+    for (int u : cp.in_units) {
+      if (u < 0) { AD_HIP(hipStreamWaitEvent(s, c.ev_sampler[(g + 3) & 3], 0)); continue; }
+      const int m = c.units[u].comp;
+      if (m != row.comp && !waited[m]) { waited[m] = true; AD_HIP(hipStreamWaitEvent(s, ev_done_of(c, m, g - 1), 0)); }
+    }
+    // (b) readers, two rounds back, of the copy written now
+    bool reader[64] = {false};
+    for (int m = 1; m <= c.N; ++m) {
+      if (m == row.comp) continue;
+      for (int u : c.comps[m - 1].in_units)
+        if (u >= 0 && c.units[u].comp == row.comp) reader[m] = true;
+    }
+    for (int m = 1; m <= c.N; ++m)
+      if (reader[m]) AD_HIP(hipStreamWaitEvent(s, ev_done_of(c, m, g - 2), 0));
+
+    const void* in[64];
+    void* out[64];
+    for (size_t i = 0; i < cp.in_units.size(); ++i)
+      in[i] = cp.in_units[i] < 0 ? latent : (const void*)(c.work_dev + c.slot_off[phys_read(c, row)][cp.in_units[i]]);
+    for (size_t i = 0; i < cp.out_units.size(); ++i) {
+      const int u = cp.out_units[i];
+      out[i] = u == nu - 1 ? c.work_dev + c.eps_off[0] : c.work_dev + c.slot_off[phys_write(c, row)][u];
+    }
+    int* counter = counters + row.comp;
+    const int tau_off = row.tau_step - base, latent_off = row.latent_step >= 0 ? row.latent_step - base : 0;
+    const int eps_off = row.eps_step >= 0 ? row.eps_step - base : INT32_MIN;
+    auto work = [&]() -> ad_status {
+      AD_TRY(run_component(c, row.comp, 0, in, c.taus[row.tau_step], 1.f, text_emb, pooled_emb, out, s, nullptr,
+                           StepRef{table, counter, tau_off}, StepRef{table, counter, latent_off}));
+      if (row.eps_step < 0) AD_TRY(launch_advance(counter, 1, s));
+      return AD_OK;
+    };
+    if (graphs) {
+      Ctx::CompGraph& cg = c.comp_graph[(size_t)(row.comp - 1) * 3 + phys_write(c, row)];
+      const bool same = cg.exec && cg.latent == latent && cg.text == text_emb && cg.pooled == pooled_emb && cg.stream == s &&
+                        cg.cfg_scale == c.cfg_scale && cg.tau_off == tau_off && cg.latent_off == latent_off && cg.eps_off == eps_off;
+      if (!same) {
+        if (cg.exec) AD_HIP(hipStreamSynchronize(s));    // a replay of the old graph may still be running
+        if (cg.exec) (void)hipGraphExecDestroy(cg.exec);
+        if (cg.graph) (void)hipGraphDestroy(cg.graph);
+        cg.exec = nullptr; cg.graph = nullptr;
+        AD_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed));
+        const ad_status st = work();
+        hipGraph_t graph = nullptr;
+        const hipError_t e = hipStreamEndCapture(s, &graph);
+        if (st != AD_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
+        if (e != hipSuccess) AD_FAIL(AD_ERR_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+        cg.graph = graph;
+        AD_HIP(hipGraphInstantiate(&cg.exec, cg.graph, nullptr, nullptr, 0));
+        cg.latent = latent; cg.text = text_emb; cg.pooled = pooled_emb; cg.stream = s; cg.cfg_scale = c.cfg_scale;
+        cg.tau_off = tau_off; cg.latent_off = latent_off; cg.eps_off = eps_off;
+      }
+      AD_HIP(hipGraphLaunch(cg.exec, s));
+    } else {
+      AD_TRY(work());
+    }
+    if (row.eps_step >= 0) {
+      // the sampler overwrites the latent: this round's component 1 has to be done with it
+      if (row.comp != 1) AD_HIP(hipStreamWaitEvent(s, ev_done_of(c, 1, g), 0));
+      AD_TRY(launch_sampler((float*)latent, (const float*)(c.work_dev + c.eps_off[0]), n, c.cfg.frames > 0 ? 1 : c.cfg.batch, 0.f, 0.f,
+                            StepRef{table, counter, eps_off}, c.cfg_scale, s));
+      AD_TRY(launch_advance(counter, 1, s));
+      AD_TRY(launch_advance(counters, 1, s));          // the counter of the barrier rounds moves along
+      AD_HIP(hipEventRecord(c.ev_sampler[g & 3], s));
+      if (steps_out) steps_out->push_back(row.eps_step);
+    }
+    AD_HIP(hipEventRecord(ev_done_of(c, row.comp, g), s));
+  }
   return AD_OK;
 }
 
@@ -516,7 +630,7 @@ static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const
     for (size_t i = 0; i < cp.in_units.size(); ++i) {
       if (cp.in_units[i] < 0) { in[i] = latent; continue; }
       const int u = cp.in_units[i];
-      const int slot = (row.fresh_from > 0 && c.units[u].comp == row.fresh_from) ? row.write_slot : row.read_slot;
+      const int slot = (row.fresh_from > 0 && c.units[u].comp == row.fresh_from) ? phys_write(c, row) : phys_read(c, row);
       in[i] = c.work_dev + c.slot_off[slot][u];
     }
     int lane = 0;
@@ -524,7 +638,7 @@ static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const
     for (size_t i = 0; i < cp.out_units.size(); ++i) {
       const int u = cp.out_units[i];
       if (u == nu - 1) out[i] = c.work_dev + c.eps_off[lane];
-      else if (row.write_slot >= 0) out[i] = c.work_dev + c.slot_off[row.write_slot][u];
+      else if (row.write_slot >= 0) out[i] = c.work_dev + c.slot_off[phys_write(c, row)][u];
       else AD_FAIL(AD_ERR_STATE, "schedule row drops a stored tensor");
     }
     const StepRef tau_ref{table, counter, row.tau_step - base};
@@ -553,6 +667,15 @@ static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const
     AD_HIP(hipStreamWaitEvent(s0, c.events[max_par + k], 0));
   }
   AD_TRY(launch_advance(counter, (int)eps_steps.size(), s0));
+  if (c.edge_mode) {
+    // a barrier round inside a per-edge run (warm-up): the per-component counters move along, and everything the next
+    // round may wait for counts as done here
+    for (int m = 1; m <= c.N; ++m) {
+      AD_TRY(launch_advance(counter + m, (int)eps_steps.size(), s0));
+      AD_HIP(hipEventRecord(ev_done_of(c, m, c.rows[r0].round), s0));
+    }
+    AD_HIP(hipEventRecord(c.ev_sampler[c.rows[r0].round & 3], s0));
+  }
   if (steps_out) *steps_out = eps_steps;
   return AD_OK;
 }
@@ -561,6 +684,24 @@ static void drop_graph(Ctx::RoundGraph& g) {
   if (g.exec) (void)hipGraphExecDestroy(g.exec);
   if (g.graph) (void)hipGraphDestroy(g.graph);
   g.exec = nullptr; g.graph = nullptr;
+}
+
+static void drop_comp_graphs(Ctx& c) {
+  for (auto& g : c.comp_graph) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (g.graph) (void)hipGraphDestroy(g.graph);
+    g.exec = nullptr; g.graph = nullptr;
+  }
+}
+
+ad_status ad_set_edge_mode(ad_ctx* ctx, int on) {
+  if (!ctx) AD_FAIL(AD_ERR_INVALID, "null argument");
+  Ctx& c = *C(ctx);
+  if (on && (c.stride != 1 || c.wrap)) AD_FAIL(AD_ERR_INVALID, "the per-edge mode needs stride 1 and the sequential segmentation");
+  if (on && c.N > 60) AD_FAIL(AD_ERR_INVALID, "the per-edge mode holds at most 60 components");
+  if (c.next_row != 0 && c.next_row < c.rows.size()) AD_FAIL(AD_ERR_STATE, "the mode cannot change in the middle of a run");
+  c.edge_mode = on != 0;
+  return AD_OK;
 }
 
 ad_status ad_set_graph_mode(ad_ctx* ctx, int on) {
@@ -593,6 +734,15 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
   }
   if (!c.ev_pack) AD_HIP(hipEventCreateWithFlags(&c.ev_pack, hipEventDisableTiming));
   hipStream_t s0 = (hipStream_t)streams[0];
+  if (c.edge_mode) {
+    // events of the per-edge rounds (the warm-up rounds of such a run record them too) and the per-component graphs
+    if ((int)c.ev_done.size() < 4 * c.N) c.ev_done.resize((size_t)4 * c.N, nullptr);
+    for (auto& ev : c.ev_done)
+      if (!ev) AD_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    for (auto& ev : c.ev_sampler)
+      if (!ev) AD_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    if (c.comp_graph.size() != (size_t)3 * c.N) { drop_comp_graphs(c); c.comp_graph.assign((size_t)3 * c.N, Ctx::CompGraph{}); }
+  }
 
   if (!c.step_table_ready) {
     // first round of a run: per-step scalars and the step counter go to the device (once, synchronously)
@@ -602,13 +752,15 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
       sampler_coeffs(c, i, &cx, &ce, &in_scale, &init_scale);
       tab[i] = StepRec{(float)c.taus[i], (float)in_scale, (float)cx, (float)ce};
     }
-    const int zero = c.steps_done;
+    int zero[64];                                       // the round counter and one counter per component
+    for (int& z : zero) z = c.steps_done;
     AD_HIP(hipDeviceSynchronize());
     AD_HIP(hipMemcpy(c.work_dev + c.step_table_off, tab.data(), tab.size() * sizeof(StepRec), hipMemcpyHostToDevice));
-    AD_HIP(hipMemcpy(c.work_dev + c.step_counter_off, &zero, sizeof(int), hipMemcpyHostToDevice));
+    AD_HIP(hipMemcpy(c.work_dev + c.step_counter_off, zero, sizeof(zero), hipMemcpyHostToDevice));
     AD_HIP(hipDeviceSynchronize());
     c.step_table_ready = true;
     for (auto& g : c.round_graph) drop_graph(g);      // the table belongs to the run; so do its graphs
+    drop_comp_graphs(c);
   }
   if (text_emb && c.text_cached != text_emb) {
     // first round of a run (or a new embedding): build the text key / value cache ahead of everything else
@@ -627,7 +779,10 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
   const bool profiling = prof && prof->on;
   std::vector<int> done;
   ad_status st = AD_OK;
-  if (c.use_graphs && full && !profiling) {
+  if (c.edge_mode && full && !profiling) {
+    st = enqueue_round_edges(c, r0, r1, latent, text_emb, pooled_emb, streams, ns, c.use_graphs, &done);
+    if (st != AD_OK) return st;
+  } else if (c.use_graphs && full && !profiling) {
     // an asynchronous full round depends on the step only through the device-side counter: capture it once
     // per slot parity (and per set of caller pointers), then replay
     Ctx::RoundGraph& g = c.round_graph[c.rows[r0].write_slot & 1];

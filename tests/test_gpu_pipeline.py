@@ -255,6 +255,70 @@ def test_graph_replay_equals_direct_launch_bitwise(name, dtype, N, w, S, T, samp
     case.m.set_graph_mode(False)
 
 
+@pytest.mark.parametrize("name,dtype,N,w,T,sampler,shift", [
+    ("tiny", B.AD_F32, 2, 1, 9, "ddim", False),
+    ("tiny", B.AD_F32, 3, 2, 12, "euler", True),
+    ("tiny", B.AD_F32, 4, 1, 14, "ddim", False),
+    ("tiny", B.AD_F32, 1, 0, 6, "ddim", True),
+    ("sd21_narrow", B.AD_BF16, 4, 1, 10, "ddim", False),
+    ("sd21_narrow", B.AD_BF16, 3, 2, 9, "ddim", True),
+])
+def test_edge_mode_equals_barrier_rounds_bitwise(name, dtype, N, w, T, sampler, shift):
+    """Per-edge mode (no barrier between asynchronous rounds, three copies of the stored tensors, events per
+    producer / consumer edge) gives the bits of the barrier rounds: round by round when the caller synchronises
+    between rounds, and at the end of a free-running trajectory in which components of different rounds overlap -
+    with direct launches and with one replayed graph per (component, copy), on as many streams as components, on two
+    and on one."""
+    case = Case(name, dtype, N, w, 1, T, sampler=sampler, cfg_scale=3.0, time_shift=shift, std=0.1 if name == "tiny" else 0.02)
+    smp = B.AD_DDIM if sampler == "ddim" else B.AD_EULER
+
+    def trajectory(edges, graphs, streams, sync_every_round):
+        case.m.set_edge_mode(edges)
+        case.m.set_graph_mode(graphs)
+        case.m.reset(T, sampler=smp, cfg_scale=3.0, time_shift=shift)
+        latent = case.init_latent()
+        ss = [torch.cuda.Stream(device=DEV) for _ in range(streams)]
+        torch.cuda.synchronize()
+        snaps = []
+        while case.m.step(latent, case.d_text, ss, pooled=case.d_pooled) is not None:
+            if sync_every_round:
+                torch.cuda.synchronize()
+                snaps.append(latent.cpu().numpy().copy())
+        torch.cuda.synchronize()
+        snaps.append(latent.cpu().numpy().copy())
+        return snaps
+
+    ref = trajectory(False, False, N, True)
+    assert np.isfinite(ref[-1]).all()
+    for graphs in (False, True):
+        stepwise = trajectory(True, graphs, N, True)
+        assert len(stepwise) == len(ref)
+        for r, (a, b) in enumerate(zip(ref, stepwise)):
+            assert np.array_equal(a, b), f"graphs {graphs}, round {r}"
+        for streams in sorted({N, 2, 1}):
+            for attempt in range(2):
+                free = trajectory(True, graphs, streams, False)
+                assert np.array_equal(free[-1], ref[-1]), f"graphs {graphs}, {streams} streams, free-running, run {attempt}"
+    case.m.set_edge_mode(False)
+    case.m.set_graph_mode(False)
+    # and back: the barrier rounds still give the same bits on the context that has run per-edge rounds
+    again = trajectory(False, True, N, False)
+    assert np.array_equal(again[-1], ref[-1])
+    case.m.set_graph_mode(False)
+
+
+def test_edge_mode_argument_checks():
+    d = CONFIGS["tiny"]
+    m = ad.AsyncDiff(d, 3, 1, 2, B.AD_F32)                 # stride 2
+    with pytest.raises(ad.AsyncDiffError):
+        m.set_edge_mode(True)
+    m.close()
+    m = ad.AsyncDiff(d, 3, 1, 1, B.AD_F32, wrap=True)      # wrapped segmentation
+    with pytest.raises(ad.AsyncDiffError):
+        m.set_edge_mode(True)
+    m.close()
+
+
 @pytest.mark.parametrize("cuts,graphs", [([1, 2], False), ([3, 9], True), ([2], True)])
 def test_caller_given_partition_matches_oracle(cuts, graphs):
     """A partition supplied by the caller (for instance one balanced by measured time) changes which tensors are
@@ -422,19 +486,24 @@ def test_full_size_bench_configuration_properties(full_size_weights):
     noise = dev_f32(SI.make_latent(d["latent_channels"], d["height"], d["width"]).astype(np.float32))
     d_text = dev(quantize(SI.make_text(d["batch"], d["ctx_len"], d["ctx_dim"]), B.AD_BF16), B.AD_BF16)
 
-    def trajectory(n, cuts, warm, streams, graphs, rounds=None):
-        progress(f"gpu: trajectory with {n} component(s) on {streams} stream(s), graphs {graphs}")
+    def trajectory(n, cuts, warm, streams, graphs, rounds=None, edges=False, free_running=False):
+        progress(f"gpu: trajectory with {n} component(s) on {streams} stream(s), graphs {graphs}, per-edge {edges}")
         m = ad.AsyncDiff(d, n, warm, 1, B.AD_BF16, cuts=cuts)
         m.allocate(DEV)
         m.load_weights(full_size_weights)
         m.set_graph_mode(graphs)
+        m.set_edge_mode(edges)
         m.reset(T, cfg_scale=7.5)
         latent = noise.clone()
         ss = [torch.cuda.Stream(device=DEV) for _ in range(streams)]
         torch.cuda.synchronize()
         snaps = []
         while (rounds is None or len(snaps) < rounds) and m.step(latent, d_text, ss) is not None:
-            torch.cuda.synchronize()
+            if not free_running:
+                torch.cuda.synchronize()
+                snaps.append(latent.cpu().numpy().copy())
+        torch.cuda.synchronize()
+        if free_running:
             snaps.append(latent.cpu().numpy().copy())
         m.close()
         return snaps
@@ -446,6 +515,14 @@ def test_full_size_bench_configuration_properties(full_size_weights):
     for r, (a, b) in enumerate(zip(direct, replay)):
         assert np.array_equal(a, b), f"round {r}"
     assert np.isfinite(replay[-1]).all()
+    # per-edge mode (what bench.py times by default): no barrier between rounds, same bits - round by round, and at the end
+    # of a run in which nothing synchronises and components of different rounds overlap
+    edge = trajectory(4, cuts, w, 4, True, edges=True)
+    assert len(edge) == T
+    for r, (a, b) in enumerate(zip(direct, edge)):
+        assert np.array_equal(a, b), f"per-edge round {r}"
+    free = trajectory(4, cuts, w, 4, True, edges=True, free_running=True)
+    assert np.array_equal(free[-1], direct[-1])
     single = trajectory(1, None, 0, 1, False, rounds=w)
     for r in range(w):
         assert np.array_equal(single[r], direct[r]), f"warm-up step {r}"
