@@ -160,7 +160,7 @@ def main():
             # the components share the GPU: neighbouring splits are timed as whole asynchronous rounds
             from paper_2406_06911_amd.tuning import refine_cuts
             t1 = time.time()
-            cuts, ms_round, tried = refine_cuts(d, N, w, S, dtype, wts, cuts, dev)
+            cuts, ms_round, tried = refine_cuts(d, N, w, S, dtype, wts, cuts, dev, edges=(S == 1 and not args.wrap and args.edges != 0))
             log(f"partition refined in {time.time() - t1:.1f}s over {len(tried)} splits: cuts {cuts}, {ms_round:.3f} ms per round")
             log("  splits tried: " + ", ".join(f"{list(k)}: {v:.3f}" for k, v in tried.items()))
     else:
@@ -366,7 +366,7 @@ def main():
         t1 = time.time()
         tcuts, unit_us = time_balanced_cuts(d, N, dtype, wts, dev)
         if args.refine:
-            tcuts, _, tried = refine_cuts(d, N, w, S, dtype, wts, tcuts, dev)
+            tcuts, _, tried = refine_cuts(d, N, w, S, dtype, wts, tcuts, dev, edges=use_edges)
         tune_s = time.time() - t1
         m2 = ad.AsyncDiff(d, N, w, S, dtype, cuts=tcuts)
         m2.allocate(dev)

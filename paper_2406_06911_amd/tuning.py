@@ -57,12 +57,14 @@ def time_balanced_cuts(cfg_dict, n_components, dtype, weights, device="cuda:0"):
     return balance_cuts(times, n_components), times
 
 
-def time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", rounds=12, settle=2):
-    """Milliseconds per asynchronous round (graph replay, one stream per concurrent evaluation) for a given split."""
+def time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", rounds=12, settle=2, edges=False):
+    """Milliseconds per asynchronous round (graph replay, one stream per concurrent evaluation) for a given split;
+    edges: in per-edge mode (no barrier between rounds; stride 1)."""
     m = AsyncDiff(cfg_dict, n_components, warmup, stride, dtype, cuts=cuts)
     m.allocate(device)
     m.load_weights(weights)
     m.set_graph_mode(True)
+    m.set_edge_mode(bool(edges))
     m.reset(warmup + (settle + rounds + 2) * stride)
     tdt = torch.bfloat16 if dtype == AD_BF16 else torch.float32
     frames = cfg_dict.get("frames", 0)
@@ -87,7 +89,7 @@ def time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, de
     return ms
 
 
-def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", max_evals=40, gain=0.0005):
+def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", max_evals=40, gain=0.0005, edges=False):
     """Steepest descent around `cuts`: every split with one cut moved by one or two units is timed, the best one is
     taken while the measured round time drops by more than `gain` (relative) and fewer than `max_evals` splits
     have been timed.  Returns (cuts, ms per round, {cuts tuple: ms})."""
@@ -99,7 +101,7 @@ def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, de
     def measure(c):
         key = tuple(c)
         if key not in seen:
-            seen[key] = time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, list(c), device)
+            seen[key] = time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, list(c), device, edges=edges)
         return seen[key]
 
     best = list(cuts)
