@@ -24,12 +24,11 @@ PEAK_HBM_GBS = 8000.0
 # `rocprofv3 --pmc` runs of this file (FETCH_SIZE, WRITE_SIZE; KiB per dispatch scaled by the factors 2.00 and 1.00 that the
 # same counters show for the 2^26-element sampler launch).  Commands and tables: profiles/bench_sd21_768_all_kernels.md.
 MEASURED_TRAFFIC = {"sd21_768": {
-    "igemm_bf16_128x128_p3": 91963135, "igemm_bf16_128x128_dma": 56108535, "igemm_bf16_256x128_p3": 75786808,
-    "igemm_bf16_64x64_p3": 25692599, "igemm_bf16_128x128_p3_splitk": 52864068,
-    "igemm_bf16_256x128_p3_splitk": 119037697, "splitk_reduce": 18418274, "attn_mfma2_bf16": 33214464,
-    "attn_mfma_bf16": 14639820,
-    "gn_apply": 17512630, "gn_partial": 7287290, "layernorm": 13111232, "igemm_bf16_64x64_splitk": 51743432,
-    "linear_rows": 5601074, "gn_small": 3033907}}
+    "igemm_bf16_128x128_p3": 91935451, "igemm_bf16_128x128_dma": 56090270, "igemm_bf16_256x128_p3": 75437418,
+    "igemm_bf16_64x64_p3": 25701165, "igemm_bf16_128x128_p3_splitk": 52878129,
+    "igemm_bf16_256x128_p3_splitk": 118992536, "splitk_reduce": 18418391, "attn_mfma2_bf16": 33263038,
+    "attn_mfma_bf16": 14635399, "gn_apply": 17514426, "gn_partial": 7291156, "layernorm": 13106944,
+    "igemm_bf16_64x64_splitk": 51769835, "linear_rows": 5541171, "gn_small": 3033703}}
 
 
 TRAFFIC_SOURCE = "not measured in this run: FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this file, profiles/bench_sd21_768_all_kernels.md"
