@@ -607,6 +607,14 @@ static ad_status enqueue_round(Ctx& c, size_t r0, size_t r1, void* latent, const
   int* counter = (int*)(c.work_dev + c.step_counter_off);
   const int base = c.steps_done;             // the device counter holds this value when the round runs
 
+  if (c.edge_mode) {
+    // a barrier round inside a per-edge run (warm-up, a profiled round): the rounds before it were not joined, so
+    // streams[0] first gets behind everything they may still be doing
+    const int g = c.rows[r0].round;
+    for (int m = 1; m <= c.N; ++m)
+      for (int back = 1; back <= 2; ++back) AD_HIP(hipStreamWaitEvent(s0, ev_done_of(c, m, g - back), 0));
+    AD_HIP(hipStreamWaitEvent(s0, c.ev_sampler[(g + 3) & 3], 0));
+  }
   // open the round: the other streams start behind everything streams[0] has been given so far
   AD_HIP(hipEventRecord(c.events[0], s0));
   for (int k = 1; k < ns; ++k) AD_HIP(hipStreamWaitEvent((hipStream_t)streams[k], c.events[0], 0));

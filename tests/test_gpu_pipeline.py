@@ -272,7 +272,7 @@ def test_edge_mode_equals_barrier_rounds_bitwise(name, dtype, N, w, T, sampler, 
     case = Case(name, dtype, N, w, 1, T, sampler=sampler, cfg_scale=3.0, time_shift=shift, std=0.1 if name == "tiny" else 0.02)
     smp = B.AD_DDIM if sampler == "ddim" else B.AD_EULER
 
-    def trajectory(edges, graphs, streams, sync_every_round):
+    def trajectory(edges, graphs, streams, sync_every_round, profiled_round=-1):
         case.m.set_edge_mode(edges)
         case.m.set_graph_mode(graphs)
         case.m.reset(T, sampler=smp, cfg_scale=3.0, time_shift=shift)
@@ -280,7 +280,13 @@ def test_edge_mode_equals_barrier_rounds_bitwise(name, dtype, N, w, T, sampler, 
         ss = [torch.cuda.Stream(device=DEV) for _ in range(streams)]
         torch.cuda.synchronize()
         snaps = []
-        while case.m.step(latent, case.d_text, ss, pooled=case.d_pooled) is not None:
+        rounds = 0
+        while True:
+            # a round with per-launch timing on is enqueued as a barrier round in the middle of the per-edge rounds
+            case.m.profile(rounds == profiled_round)
+            if case.m.step(latent, case.d_text, ss, pooled=case.d_pooled) is None:
+                break
+            rounds += 1
             if sync_every_round:
                 torch.cuda.synchronize()
                 snaps.append(latent.cpu().numpy().copy())
@@ -297,7 +303,7 @@ def test_edge_mode_equals_barrier_rounds_bitwise(name, dtype, N, w, T, sampler, 
             assert np.array_equal(a, b), f"graphs {graphs}, round {r}"
         for streams in sorted({N, 2, 1}):
             for attempt in range(2):
-                free = trajectory(True, graphs, streams, False)
+                free = trajectory(True, graphs, streams, False, profiled_round=w + 2 if attempt else -1)
                 assert np.array_equal(free[-1], ref[-1]), f"graphs {graphs}, {streams} streams, free-running, run {attempt}"
     case.m.set_edge_mode(False)
     case.m.set_graph_mode(False)
