@@ -230,15 +230,17 @@ ad_status ad_set_graph_mode(ad_ctx* ctx, int on);
 
 /* Per-edge mode (off by default; Section 3.2, Eq. 7: a component needs nothing but the outputs its predecessors produced
  * in the previous step): full asynchronous rounds are enqueued without the barrier that otherwise opens and closes a
- * round.  Component n runs on streams[(n - 1) % n_streams]; before it starts it waits (events) for the evaluations of
+ * round.  Evaluation e of a round runs on streams[e % n_streams]; before it starts it waits (events) for the evaluations of
  * the previous round whose stored outputs it reads - component 1 for the previous round's sampler - and for the
  * evaluations of two rounds back that read the copy of its outputs it overwrites: the stored tensors are kept in three
  * copies (copy = round mod 3) instead of two.  A component whose producers are done therefore starts its next round while
  * slower components still work on the current one.  Results are bit-identical to the barrier rounds.  With graph mode on,
  * one graph per (component, copy) is replayed.  Differences for the caller: streams[0] is NOT joined with the other
  * streams when ad_step returns - synchronise every stream (or the device) before reading the latent - and
- * ad_get_slot_tensor's slot is the copy 0..2.  Needs stride 1 and the sequential segmentation (AD_ERR_INVALID otherwise);
- * cannot be switched in the middle of a run (AD_ERR_STATE).  Warm-up rounds are enqueued as before. */
+ * ad_get_slot_tensor's slot is the copy 0..2.  With stride S the S evaluations of the last component run on the streams
+ * after those of the components, the sampler behind all of them.  Needs the sequential segmentation (AD_ERR_INVALID with
+ * the wrapped one); cannot be switched in the middle of a run (AD_ERR_STATE).  Warm-up rounds and a trailing partial round
+ * are enqueued as before, behind everything the rounds before them left running. */
 ad_status ad_set_edge_mode(ad_ctx* ctx, int on);
 
 /* Sampler update of step `step_index` (Section 3.1, Eq. 3, read as deterministic DDIM; or Euler),

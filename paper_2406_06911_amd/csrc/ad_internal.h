@@ -153,7 +153,7 @@ struct Ctx {
     float cfg_scale = 0.f;
     int tau_off = 0, latent_off = 0, eps_off = 0;
   };
-  std::vector<CompGraph> comp_graph;   // [(component - 1) * 3 + copy written]
+  std::vector<CompGraph> comp_graph;   // [evaluation of the round * 3 + copy written]
 };
 
 // host logic

@@ -497,26 +497,32 @@ static inline int phys_read(const Ctx& c, const ad_sched_row& row) {
 }
 static inline hipEvent_t& ev_done_of(Ctx& c, int comp, int round) { return c.ev_done[(size_t)(comp - 1) * 4 + (round & 3)]; }
 
-// One asynchronous round without a barrier (per-edge mode; stride 1, sequential segmentation).  Component n runs on
-// streams[(n - 1) % ns].  Before it starts it waits for (a) the evaluations of the previous round whose stored tensors it
-// reads - for component 1 that is the sampler of the previous round, which also stands for the last component - and (b)
-// the evaluations of two rounds back that read the copy it is about to overwrite.  The sampler follows the last component on
-// its stream and waits for this round's component 1 (which has read the latent).  Nothing joins the streams: a component
-// whose producers are done starts its next round while slower components still work on this one.
-// graphs: replay one captured graph per (component, copy) instead of launching the kernels.
+// One asynchronous round without a barrier (per-edge mode; sequential segmentation).  Component n runs on
+// streams[(n - 1) % ns], the S evaluations of the last component (stride S) on the streams after it.  Before an
+// evaluation starts it waits for (a) the evaluations of the previous round whose stored tensors it reads - for component 1
+// that is the sampler of the previous round, which also stands for the last component - and (b) the evaluations of two
+// rounds back that read the copy it is about to overwrite.  The sampler follows the last evaluation of the last component
+// on its stream, behind the other ones of that component and behind this round's component 1 (which has read the latent).
+// Nothing joins the streams: a component whose producers are done starts its next round while slower components still work
+// on this one.  graphs: replay one captured graph per (evaluation, copy) instead of launching the kernels.
 static ad_status enqueue_round_edges(Ctx& c, size_t r0, size_t r1, void* latent, const void* text_emb, const void* pooled_emb,
                                      const ad_stream* streams, int ns, bool graphs, std::vector<int>* steps_out) {
   const int nu = (int)c.units.size();
+  const int S = c.stride;
   const StepRec* table = (const StepRec*)(c.work_dev + c.step_table_off);
   int* counters = (int*)(c.work_dev + c.step_counter_off);
   const int base = c.steps_done;
   const int g = c.rows[r0].round;
   const size_t n = (size_t)(c.cfg.frames > 0 ? c.cfg.frames : 1) * c.cfg.latent_channels * c.cfg.height * c.cfg.width;
+  std::vector<hipStream_t> lane_stream;
+  std::vector<int> lane_eps_off, lane_step;
   for (size_t r = r0; r < r1; ++r) {
     const ad_sched_row& row = c.rows[r];
-    if (row.comp != (int)(r - r0) + 1) AD_FAIL(AD_ERR_STATE, "per-edge mode: a round lists its components in order");
+    const int e = (int)(r - r0);                       // evaluation index within the round
+    const int lane = e < c.N - 1 ? 0 : e - (c.N - 1);
+    if (row.comp != (e < c.N - 1 ? e + 1 : c.N)) AD_FAIL(AD_ERR_STATE, "per-edge mode: a round lists its components in order");
     const Component& cp = c.comps[row.comp - 1];
-    hipStream_t s = (hipStream_t)streams[(row.comp - 1) % ns];
+    hipStream_t s = (hipStream_t)streams[e % ns];
     if (cp.in_units.size() > 64 || cp.out_units.size() > 64) AD_FAIL(AD_ERR_INVALID, "too many component tensors");
     // (a) producers of the previous round
     bool waited[64] = {false};
@@ -525,6 +531,8 @@ static ad_status enqueue_round_edges(Ctx& c, size_t r0, size_t r1, void* latent,
       const int m = c.units[u].comp;
       if (m != row.comp && !waited[m]) { waited[m] = true; AD_HIP(hipStreamWaitEvent(s, ev_done_of(c, m, g - 1), 0)); }
     }
+    // the noise-prediction buffer of this lane was read by the previous round's sampler, possibly on another stream
+    if (row.comp == c.N && c.N > 1) AD_HIP(hipStreamWaitEvent(s, c.ev_sampler[(g + 3) & 3], 0));
     // (b) readers, two rounds back, of the copy written now
     bool reader[64] = {false};
     for (int m = 1; m <= c.N; ++m) {
@@ -541,19 +549,21 @@ static ad_status enqueue_round_edges(Ctx& c, size_t r0, size_t r1, void* latent,
       in[i] = cp.in_units[i] < 0 ? latent : (const void*)(c.work_dev + c.slot_off[phys_read(c, row)][cp.in_units[i]]);
     for (size_t i = 0; i < cp.out_units.size(); ++i) {
       const int u = cp.out_units[i];
-      out[i] = u == nu - 1 ? c.work_dev + c.eps_off[0] : c.work_dev + c.slot_off[phys_write(c, row)][u];
+      if (u == nu - 1) out[i] = c.work_dev + c.eps_off[lane];
+      else if (row.write_slot >= 0) out[i] = c.work_dev + c.slot_off[phys_write(c, row)][u];
+      else AD_FAIL(AD_ERR_STATE, "schedule row drops a stored tensor");
     }
     int* counter = counters + row.comp;
     const int tau_off = row.tau_step - base, latent_off = row.latent_step >= 0 ? row.latent_step - base : 0;
     const int eps_off = row.eps_step >= 0 ? row.eps_step - base : INT32_MIN;
     auto work = [&]() -> ad_status {
-      AD_TRY(run_component(c, row.comp, 0, in, c.taus[row.tau_step], 1.f, text_emb, pooled_emb, out, s, nullptr,
+      AD_TRY(run_component(c, row.comp, lane, in, c.taus[row.tau_step], 1.f, text_emb, pooled_emb, out, s, nullptr,
                            StepRef{table, counter, tau_off}, StepRef{table, counter, latent_off}));
-      if (row.eps_step < 0) AD_TRY(launch_advance(counter, 1, s));
+      if (row.eps_step < 0) AD_TRY(launch_advance(counter, S, s));      // a full round is S steps for every component
       return AD_OK;
     };
     if (graphs) {
-      Ctx::CompGraph& cg = c.comp_graph[(size_t)(row.comp - 1) * 3 + phys_write(c, row)];
+      Ctx::CompGraph& cg = c.comp_graph[(size_t)e * 3 + g % 3];
       const bool same = cg.exec && cg.latent == latent && cg.text == text_emb && cg.pooled == pooled_emb && cg.stream == s &&
                         cg.cfg_scale == c.cfg_scale && cg.tau_off == tau_off && cg.latent_off == latent_off && cg.eps_off == eps_off;
       if (!same) {
@@ -564,9 +574,9 @@ static ad_status enqueue_round_edges(Ctx& c, size_t r0, size_t r1, void* latent,
         AD_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed));
         const ad_status st = work();
         hipGraph_t graph = nullptr;
-        const hipError_t e = hipStreamEndCapture(s, &graph);
+        const hipError_t err = hipStreamEndCapture(s, &graph);
         if (st != AD_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
-        if (e != hipSuccess) AD_FAIL(AD_ERR_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+        if (err != hipSuccess) AD_FAIL(AD_ERR_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(err));
         cg.graph = graph;
         AD_HIP(hipGraphInstantiate(&cg.exec, cg.graph, nullptr, nullptr, 0));
         cg.latent = latent; cg.text = text_emb; cg.pooled = pooled_emb; cg.stream = s; cg.cfg_scale = c.cfg_scale;
@@ -577,17 +587,31 @@ static ad_status enqueue_round_edges(Ctx& c, size_t r0, size_t r1, void* latent,
       AD_TRY(work());
     }
     if (row.eps_step >= 0) {
-      // the sampler overwrites the latent: this round's component 1 has to be done with it
-      if (row.comp != 1) AD_HIP(hipStreamWaitEvent(s, ev_done_of(c, 1, g), 0));
-      AD_TRY(launch_sampler((float*)latent, (const float*)(c.work_dev + c.eps_off[0]), n, c.cfg.frames > 0 ? 1 : c.cfg.batch, 0.f, 0.f,
-                            StepRef{table, counter, eps_off}, c.cfg_scale, s));
-      AD_TRY(launch_advance(counter, 1, s));
-      AD_TRY(launch_advance(counters, 1, s));          // the counter of the barrier rounds moves along
-      AD_HIP(hipEventRecord(c.ev_sampler[g & 3], s));
-      if (steps_out) steps_out->push_back(row.eps_step);
+      lane_stream.push_back(s); lane_eps_off.push_back(eps_off); lane_step.push_back(row.eps_step);
+    } else {
+      AD_HIP(hipEventRecord(ev_done_of(c, row.comp, g), s));
     }
-    AD_HIP(hipEventRecord(ev_done_of(c, row.comp, g), s));
   }
+  if (lane_stream.empty()) AD_FAIL(AD_ERR_STATE, "per-edge mode: a full round ends with the last component");
+  // sampler updates in step order on the stream of the last evaluation, behind the other evaluations of the last component
+  hipStream_t ss = lane_stream.back();
+  for (size_t j = 0; j + 1 < lane_stream.size(); ++j)
+    if (lane_stream[j] != ss) {
+      AD_HIP(hipEventRecord(c.events[1 + j], lane_stream[j]));
+      AD_HIP(hipStreamWaitEvent(ss, c.events[1 + j], 0));
+    }
+  // the sampler overwrites the latent: this round's component 1 has to be done with it
+  if (c.N > 1) AD_HIP(hipStreamWaitEvent(ss, ev_done_of(c, 1, g), 0));
+  int* counter = counters + c.N;
+  for (size_t j = 0; j < lane_stream.size(); ++j) {
+    AD_TRY(launch_sampler((float*)latent, (const float*)(c.work_dev + c.eps_off[j]), n, c.cfg.frames > 0 ? 1 : c.cfg.batch, 0.f, 0.f,
+                          StepRef{table, counter, lane_eps_off[j]}, c.cfg_scale, ss));
+    if (steps_out) steps_out->push_back(lane_step[j]);
+  }
+  AD_TRY(launch_advance(counter, (int)lane_stream.size(), ss));
+  AD_TRY(launch_advance(counters, (int)lane_stream.size(), ss));          // the counter of the barrier rounds moves along
+  AD_HIP(hipEventRecord(c.ev_sampler[g & 3], ss));
+  AD_HIP(hipEventRecord(ev_done_of(c, c.N, g), ss));
   return AD_OK;
 }
 
@@ -705,7 +729,7 @@ static void drop_comp_graphs(Ctx& c) {
 ad_status ad_set_edge_mode(ad_ctx* ctx, int on) {
   if (!ctx) AD_FAIL(AD_ERR_INVALID, "null argument");
   Ctx& c = *C(ctx);
-  if (on && (c.stride != 1 || c.wrap)) AD_FAIL(AD_ERR_INVALID, "the per-edge mode needs stride 1 and the sequential segmentation");
+  if (on && c.wrap) AD_FAIL(AD_ERR_INVALID, "the per-edge mode needs the sequential segmentation");
   if (on && c.N > 60) AD_FAIL(AD_ERR_INVALID, "the per-edge mode holds at most 60 components");
   if (c.next_row != 0 && c.next_row < c.rows.size()) AD_FAIL(AD_ERR_STATE, "the mode cannot change in the middle of a run");
   c.edge_mode = on != 0;
@@ -749,7 +773,8 @@ ad_status ad_step(ad_ctx* ctx, void* latent, const void* text_emb, const void* p
       if (!ev) AD_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
     for (auto& ev : c.ev_sampler)
       if (!ev) AD_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
-    if (c.comp_graph.size() != (size_t)3 * c.N) { drop_comp_graphs(c); c.comp_graph.assign((size_t)3 * c.N, Ctx::CompGraph{}); }
+    const size_t n_graphs = (size_t)3 * (c.N + c.stride - 1);
+    if (c.comp_graph.size() != n_graphs) { drop_comp_graphs(c); c.comp_graph.assign(n_graphs, Ctx::CompGraph{}); }
   }
 
   if (!c.step_table_ready) {
