@@ -105,8 +105,7 @@ def main():
                     "measured unit times and refined by whole-round timings, and report it as tuned_partition")
     ap.add_argument("--repeats", type=int, default=10, help="the timed region of --steps rounds is repeated this many times; value is the median")
     ap.add_argument("--edges", type=int, default=-1, help="per-edge mode for the timed region (no barrier between asynchronous rounds: events per producer / "
-                    "consumer edge, three copies of the stored tensors; same results bit for bit).  -1 (default): on where the library "
-                    "offers it (--wrap 0), and the barrier rounds are timed beside it; 0: barrier rounds only; 1: per-edge only")
+                    "consumer edge, three copies of the stored tensors; same results bit for bit).  -1 (default): on except with --wrap 1, and the barrier rounds are timed beside it; 0: barrier rounds only; 1: per-edge only")
     ap.add_argument("--wrap", type=int, default=0, help="1: wrapped segmentation (first and last segment in one component; stride 1, FLOP-balanced cuts)")
     ap.add_argument("--tile", type=int, default=-1, help="GEMM kernel family override for measurements (ad_tune_conv_tile); -1 = automatic")
     ap.add_argument("--order", type=int, default=-1, help="GEMM workgroup order override for measurements (ad_tune_conv_order); -1 = automatic")
@@ -159,7 +158,7 @@ def main():
             # the components share the GPU: neighbouring splits are timed as whole asynchronous rounds
             from paper_2406_06911_amd.tuning import refine_cuts
             t1 = time.time()
-            cuts, ms_round, tried = refine_cuts(d, N, w, S, dtype, wts, cuts, dev, edges=(not args.wrap and args.edges != 0))
+            cuts, ms_round, tried = refine_cuts(d, N, w, S, dtype, wts, cuts, dev, edges=(args.edges == 1 or (args.edges == -1 and not args.wrap)))
             log(f"partition refined in {time.time() - t1:.1f}s over {len(tried)} splits: cuts {cuts}, {ms_round:.3f} ms per round")
             log("  splits tried: " + ", ".join(f"{list(k)}: {v:.3f}" for k, v in tried.items()))
     else:
@@ -210,10 +209,7 @@ def main():
         return secs, host, lat, ss
 
     # ---- timed region: concurrent components -----------------------------------------------------
-    edges_ok = not args.wrap
-    if args.edges == 1 and not edges_ok:
-        sys.exit("--edges 1 needs --wrap 0")
-    use_edges = edges_ok and args.edges != 0
+    use_edges = args.edges == 1 or (args.edges == -1 and not args.wrap)     # wrapped segmentation: measured 1 % slower per-edge
     secs, t_host, lat, ss = timed_rounds(m, args.graphs, n_streams, K, R, edges=use_edges)
     sec = float(np.median(secs))
     steps_per_s = K * S / sec

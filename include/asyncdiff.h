@@ -238,8 +238,8 @@ ad_status ad_set_graph_mode(ad_ctx* ctx, int on);
  * one graph per (component, copy) is replayed.  Differences for the caller: streams[0] is NOT joined with the other
  * streams when ad_step returns - synchronise every stream (or the device) before reading the latent - and
  * ad_get_slot_tensor's slot is the copy 0..2.  With stride S the S evaluations of the last component run on the streams
- * after those of the components, the sampler behind all of them.  Needs the sequential segmentation (AD_ERR_INVALID with
- * the wrapped one); cannot be switched in the middle of a run (AD_ERR_STATE).  Warm-up rounds and a trailing partial round
+ * after those of the components, the sampler behind all of them; with the wrapped segmentation the tail waits for the head
+ * of its own round.  Cannot be switched in the middle of a run (AD_ERR_STATE).  Warm-up rounds and a trailing partial round
  * are enqueued as before, behind everything the rounds before them left running. */
 ad_status ad_set_edge_mode(ad_ctx* ctx, int on);
 

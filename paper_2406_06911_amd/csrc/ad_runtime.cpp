@@ -497,7 +497,7 @@ static inline int phys_read(const Ctx& c, const ad_sched_row& row) {
 }
 static inline hipEvent_t& ev_done_of(Ctx& c, int comp, int round) { return c.ev_done[(size_t)(comp - 1) * 4 + (round & 3)]; }
 
-// One asynchronous round without a barrier (per-edge mode; sequential segmentation).  Component n runs on
+// One asynchronous round without a barrier (per-edge mode).  Component n runs on
 // streams[(n - 1) % ns], the S evaluations of the last component (stride S) on the streams after it.  Before an
 // evaluation starts it waits for (a) the evaluations of the previous round whose stored tensors it reads - for component 1
 // that is the sampler of the previous round, which also stands for the last component - and (b) the evaluations of two
@@ -524,12 +524,14 @@ static ad_status enqueue_round_edges(Ctx& c, size_t r0, size_t r1, void* latent,
     const Component& cp = c.comps[row.comp - 1];
     hipStream_t s = (hipStream_t)streams[e % ns];
     if (cp.in_units.size() > 64 || cp.out_units.size() > 64) AD_FAIL(AD_ERR_INVALID, "too many component tensors");
-    // (a) producers of the previous round
+    // (a) producers of the previous round; the tail of the wrapped segmentation reads the head of its own round
     bool waited[64] = {false};
     for (int u : cp.in_units) {
       if (u < 0) { AD_HIP(hipStreamWaitEvent(s, c.ev_sampler[(g + 3) & 3], 0)); continue; }
       const int m = c.units[u].comp;
-      if (m != row.comp && !waited[m]) { waited[m] = true; AD_HIP(hipStreamWaitEvent(s, ev_done_of(c, m, g - 1), 0)); }
+      if (m == row.comp || waited[m]) continue;
+      waited[m] = true;
+      AD_HIP(hipStreamWaitEvent(s, ev_done_of(c, m, m == row.fresh_from ? g : g - 1), 0));
     }
     // the noise-prediction buffer of this lane was read by the previous round's sampler, possibly on another stream
     if (row.comp == c.N && c.N > 1) AD_HIP(hipStreamWaitEvent(s, c.ev_sampler[(g + 3) & 3], 0));
@@ -545,8 +547,12 @@ static ad_status enqueue_round_edges(Ctx& c, size_t r0, size_t r1, void* latent,
 
     const void* in[64];
     void* out[64];
-    for (size_t i = 0; i < cp.in_units.size(); ++i)
-      in[i] = cp.in_units[i] < 0 ? latent : (const void*)(c.work_dev + c.slot_off[phys_read(c, row)][cp.in_units[i]]);
+    for (size_t i = 0; i < cp.in_units.size(); ++i) {
+      const int u = cp.in_units[i];
+      if (u < 0) { in[i] = latent; continue; }
+      const bool fresh = row.fresh_from > 0 && c.units[u].comp == row.fresh_from;
+      in[i] = c.work_dev + c.slot_off[fresh ? phys_write(c, row) : phys_read(c, row)][u];
+    }
     for (size_t i = 0; i < cp.out_units.size(); ++i) {
       const int u = cp.out_units[i];
       if (u == nu - 1) out[i] = c.work_dev + c.eps_off[lane];
@@ -729,7 +735,6 @@ static void drop_comp_graphs(Ctx& c) {
 ad_status ad_set_edge_mode(ad_ctx* ctx, int on) {
   if (!ctx) AD_FAIL(AD_ERR_INVALID, "null argument");
   Ctx& c = *C(ctx);
-  if (on && c.wrap) AD_FAIL(AD_ERR_INVALID, "the per-edge mode needs the sequential segmentation");
   if (on && c.N > 60) AD_FAIL(AD_ERR_INVALID, "the per-edge mode holds at most 60 components");
   if (c.next_row != 0 && c.next_row < c.rows.size()) AD_FAIL(AD_ERR_STATE, "the mode cannot change in the middle of a run");
   c.edge_mode = on != 0;

@@ -255,11 +255,15 @@ def test_graph_replay_equals_direct_launch_bitwise(name, dtype, N, w, S, T, samp
     case.m.set_graph_mode(False)
 
 
-@pytest.mark.parametrize("name,dtype,N,w,S,T,sampler,shift", [
+@pytest.mark.parametrize("name,dtype,N,w,S,T,sampler,shift,wrap", [(*p, False) if len(p) == 8 else p for p in [
     ("tiny", B.AD_F32, 2, 1, 1, 9, "ddim", False),
     ("tiny", B.AD_F32, 3, 2, 1, 12, "euler", True),
     ("tiny", B.AD_F32, 4, 1, 1, 14, "ddim", False),
     ("tiny", B.AD_F32, 1, 0, 1, 6, "ddim", True),
+    # wrapped segmentation: the tail follows the head of its own round and reads it from the copy being written
+    ("tiny", B.AD_F32, 2, 1, 1, 9, "ddim", False, True),
+    ("tiny", B.AD_F32, 3, 2, 1, 11, "euler", True, True),
+    ("sdxl_narrow", B.AD_BF16, 4, 1, 1, 9, "euler", False, True),
     # stride denoising: the last component is evaluated S times per round on streams of its own; T - w not a multiple
     # of S ends with a partial round, which is a barrier round
     ("tiny", B.AD_F32, 3, 1, 2, 14, "ddim", False),
@@ -268,14 +272,14 @@ def test_graph_replay_equals_direct_launch_bitwise(name, dtype, N, w, S, T, samp
     ("sd21_narrow", B.AD_BF16, 4, 1, 1, 10, "ddim", False),
     ("sd21_narrow", B.AD_BF16, 3, 2, 1, 9, "ddim", True),
     ("sdxl_narrow", B.AD_BF16, 4, 1, 2, 10, "euler", False),
-])
-def test_edge_mode_equals_barrier_rounds_bitwise(name, dtype, N, w, S, T, sampler, shift):
+]])
+def test_edge_mode_equals_barrier_rounds_bitwise(name, dtype, N, w, S, T, sampler, shift, wrap):
     """Per-edge mode (no barrier between asynchronous rounds, three copies of the stored tensors, events per
     producer / consumer edge) gives the bits of the barrier rounds: round by round when the caller synchronises
     between rounds, and at the end of a free-running trajectory in which components of different rounds overlap -
     with direct launches and with one replayed graph per (component, copy), on as many streams as components, on two
     and on one."""
-    case = Case(name, dtype, N, w, S, T, sampler=sampler, cfg_scale=3.0, time_shift=shift, std=0.1 if name == "tiny" else 0.02)
+    case = Case(name, dtype, N, w, S, T, sampler=sampler, cfg_scale=3.0, time_shift=shift, std=0.1 if name == "tiny" else 0.02, wrap=wrap)
     smp = B.AD_DDIM if sampler == "ddim" else B.AD_EULER
     P = N + S - 1                                          # evaluations that run side by side
 
@@ -320,12 +324,17 @@ def test_edge_mode_equals_barrier_rounds_bitwise(name, dtype, N, w, S, T, sample
     case.m.set_graph_mode(False)
 
 
-def test_edge_mode_argument_checks():
-    d = CONFIGS["tiny"]
-    m = ad.AsyncDiff(d, 3, 1, 1, B.AD_F32, wrap=True)      # wrapped segmentation
+def test_edge_mode_cannot_change_in_the_middle_of_a_run():
+    case = Case("tiny", B.AD_F32, 2, 1, 1, 6, std=0.1)
+    latent = case.init_latent()
+    ss = [torch.cuda.Stream(device=DEV) for _ in range(2)]
+    case.m.step(latent, case.d_text, ss)
     with pytest.raises(ad.AsyncDiffError):
-        m.set_edge_mode(True)
-    m.close()
+        case.m.set_edge_mode(True)
+    torch.cuda.synchronize()
+    case.m.reset(6)
+    case.m.set_edge_mode(True)          # at the start of a run it may
+    case.m.set_edge_mode(False)
 
 
 @pytest.mark.parametrize("cuts,graphs", [([1, 2], False), ([3, 9], True), ([2], True)])
