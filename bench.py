@@ -361,7 +361,7 @@ def main():
         t1 = time.time()
         tcuts, unit_us = time_balanced_cuts(d, N, dtype, wts, dev)
         if args.refine:
-            tcuts, _, tried = refine_cuts(d, N, w, S, dtype, wts, tcuts, dev, edges=use_edges)
+            tcuts, _, tried = refine_cuts(d, N, w, S, dtype, wts, tcuts, dev, edges=use_edges, other_starts=[headline_cuts[1:]])
         tune_s = time.time() - t1
         m2 = ad.AsyncDiff(d, N, w, S, dtype, cuts=tcuts)
         m2.allocate(dev)

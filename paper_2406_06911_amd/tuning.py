@@ -89,10 +89,12 @@ def time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, de
     return ms
 
 
-def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", max_evals=40, gain=0.0005, edges=False):
+def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, device="cuda:0", max_evals=40, gain=0.0005, edges=False,
+                other_starts=()):
     """Steepest descent around `cuts`: every split with one cut moved by one or two units is timed, the best one is
     taken while the measured round time drops by more than `gain` (relative) and fewer than `max_evals` splits
-    have been timed.  Returns (cuts, ms per round, {cuts tuple: ms})."""
+    have been timed.  other_starts: further splits (the FLOP-balanced one, say) that are timed first; the descent starts
+    from the best of them and `cuts`.  Returns (cuts, ms per round, {cuts tuple: ms})."""
     probe = AsyncDiff(cfg_dict, 1, 0, 1, dtype)
     nu = len(probe.units())
     probe.close()
@@ -101,11 +103,16 @@ def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, de
     def measure(c):
         key = tuple(c)
         if key not in seen:
-            seen[key] = time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, list(c), device, edges=edges)
+            # without a barrier the rounds overlap: more of them, and a longer run-in, for a steady figure
+            seen[key] = time_rounds(cfg_dict, n_components, warmup, stride, dtype, weights, list(c), device, edges=edges,
+                                    rounds=24 if edges else 12, settle=6 if edges else 2)
         return seen[key]
 
     best = list(cuts)
     best_ms = measure(best)
+    for other in other_starts:
+        if measure(list(other)) < best_ms:
+            best, best_ms = list(other), measure(list(other))
     while len(seen) < max_evals:
         # steepest descent: time every neighbour of the current split (one cut moved by one or two units)
         cand_best, cand_ms = None, best_ms
@@ -113,8 +120,8 @@ def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, de
             for step in (-1, 1, -2, 2):
                 cand = list(best)
                 cand[k] += step
-                edges = [0] + cand + [nu]
-                if any(a >= b for a, b in zip(edges, edges[1:])) or (tuple(cand) not in seen and len(seen) >= max_evals):
+                bounds = [0] + cand + [nu]
+                if any(a >= b for a, b in zip(bounds, bounds[1:])) or (tuple(cand) not in seen and len(seen) >= max_evals):
                     continue
                 ms = measure(cand)
                 if ms < cand_ms:
