@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--repeats", type=int, default=10, help="the timed region of --steps rounds is repeated this many times; value is the median")
     ap.add_argument("--edges", type=int, default=-1, help="per-edge mode for the timed region (no barrier between asynchronous rounds: events per producer / "
                     "consumer edge, three copies of the stored tensors; same results bit for bit).  -1 (default): on except with --wrap 1, and the barrier rounds are timed beside it; 0: barrier rounds only; 1: per-edge only")
+    ap.add_argument("--place", type=int, default=1, help="1 (default): before a timed region with one stream per concurrent evaluation, time every assignment "
+                    "of the evaluations to the streams over a few rounds and use the fastest (the hardware queues behind the streams are "
+                    "not equivalent); 0: evaluation e on stream e")
     ap.add_argument("--wrap", type=int, default=0, help="1: wrapped segmentation (first and last segment in one component; stride 1, FLOP-balanced cuts)")
     ap.add_argument("--tile", type=int, default=-1, help="GEMM kernel family override for measurements (ad_tune_conv_tile); -1 = automatic")
     ap.add_argument("--order", type=int, default=-1, help="GEMM workgroup order override for measurements (ad_tune_conv_order); -1 = automatic")
@@ -186,14 +189,31 @@ def main():
         T = w + max(W + K * R, min(K, 10) + 2) * S
         log(f"repeats reduced to {R} so that one schedule (T <= 1000) holds every timed round")
 
-    def timed_rounds(model, graphs, streams, k, reps, edges=False):
+    placement_log = {}
+
+    def timed_rounds(model, graphs, streams, k, reps, edges=False, place=False, tag=""):
         """w warm-up rounds of the method and W untimed rounds, then reps x (exactly k rounds bracketed by device synchronisation).
+        place: first choose which stream each evaluation of a round uses by timing every assignment over a few rounds.
         Returns the list of seconds per repetition and the host enqueue time of the first one."""
         model.set_graph_mode(bool(graphs))
+        ss = [torch.cuda.Stream(device=dev) for _ in range(streams)]
+        if place and streams == n_par:
+            from paper_2406_06911_amd.tuning import pick_stream_placement
+
+            def reset_for(nrounds):
+                model.reset(w + nrounds * S, sampler=sampler, cfg_scale=r["cfg_scale"])
+                model.set_edge_mode(bool(edges))
+            t1 = time.time()
+            ss, tried = pick_stream_placement(model, reset_for, noise.clone, text, POOLED, ss, n_par)
+            if tried:
+                best = min(tried, key=tried.get)
+                placement_log[tag] = dict(assignment=list(best), ms_per_round=round(tried[best], 3), natural_order_ms=round(tried[tuple(range(n_par))], 3),
+                                          worst_ms=round(max(tried.values()), 3), assignments_timed=len(tried), seconds=round(time.time() - t1, 1))
+                log(f"stream placement ({tag}): evaluation -> stream {list(best)}, {tried[best]:.3f} ms per round (natural order "
+                    f"{tried[tuple(range(n_par))]:.3f}, worst {max(tried.values()):.3f}; {len(tried)} assignments in {time.time() - t1:.1f}s)")
         model.reset(T, sampler=sampler, cfg_scale=r["cfg_scale"])
         model.set_edge_mode(bool(edges))
         lat = noise.clone()
-        ss = [torch.cuda.Stream(device=dev) for _ in range(streams)]
         torch.cuda.synchronize()
         run_rounds(model, lat, text, ss, w + W)
         secs, host = [], None
@@ -210,7 +230,7 @@ def main():
 
     # ---- timed region: concurrent components -----------------------------------------------------
     use_edges = args.edges == 1 or (args.edges == -1 and not args.wrap)     # wrapped segmentation: measured 1 % slower per-edge
-    secs, t_host, lat, ss = timed_rounds(m, args.graphs, n_streams, K, R, edges=use_edges)
+    secs, t_host, lat, ss = timed_rounds(m, args.graphs, n_streams, K, R, edges=use_edges, place=bool(args.place), tag="headline")
     sec = float(np.median(secs))
     steps_per_s = K * S / sec
     ms_per_step = sec / (K * S) * 1e3
@@ -366,7 +386,7 @@ def main():
         m2 = ad.AsyncDiff(d, N, w, S, dtype, cuts=tcuts)
         m2.allocate(dev)
         m2.load_weights(wts)
-        secs_t, _, _, _ = timed_rounds(m2, args.graphs, n_streams, K, R, edges=use_edges)
+        secs_t, _, _, _ = timed_rounds(m2, args.graphs, n_streams, K, R, edges=use_edges, place=bool(args.place), tag="tuned_partition")
         sec_t = float(np.median(secs_t))
         tuned = dict(component_first_units=[a for a, _ in m2.partition()], steps_per_s=round(K * S / sec_t, 3),
                      ms_per_step=round(sec_t / (K * S) * 1e3, 4), over_flops_partition=round(sec / sec_t, 4),
@@ -394,6 +414,7 @@ def main():
         "sequential_one_stream": {k: round(v, 3) for k, v in seq.items()},
         "concurrent_over_sequential": round(steps_per_s / seq_steps_per_s, 4),
         "barrier_rounds": barrier,
+        "stream_placement": placement_log or None,
         "tuned_partition": tuned,
         "host_enqueue_ms_per_step": round(t_host / (K * S) * 1e3, 3),
         "mfma_frac_whole_step": round(flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),

@@ -130,3 +130,32 @@ def refine_cuts(cfg_dict, n_components, warmup, stride, dtype, weights, cuts, de
             break
         best, best_ms = cand_best, cand_ms
     return best, best_ms, seen
+
+
+def pick_stream_placement(model, reset_fn, latent_fn, text, pooled, pool, n_eval, rounds=12, settle=5, max_eval=4):
+    """Which stream of `pool` each of the n_eval evaluations of a round should use (evaluation e of a round runs on
+    streams[e % len(streams)]).  The hardware queues behind the streams of a process are not equivalent: on the system this
+    was written on, two of the four execute like one queue, and the round is up to 15 % slower when the wrong two
+    components meet on them (and a few percent faster when the right two do, the last two of the FLOP partition).  Every
+    assignment of the evaluations to distinct streams of the pool is timed over a few rounds; returns the fastest as a
+    list of streams, and {assignment tuple: ms per round}.  More than max_eval evaluations: the pool in its own order."""
+    import itertools
+    if n_eval > max_eval or len(pool) < n_eval or n_eval < 2:
+        return list(pool[:max(1, n_eval)]), {}
+    tried = {}
+    for perm in itertools.permutations(range(len(pool)), n_eval):
+        streams = [pool[i] for i in perm]
+        reset_fn(settle + rounds + 2)
+        latent = latent_fn()
+        torch.cuda.synchronize()
+        for _ in range(model.warmup + settle):
+            model.step(latent, text, streams, pooled=pooled)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(rounds):
+            model.step(latent, text, streams, pooled=pooled)
+        torch.cuda.synchronize()
+        tried[perm] = (time.perf_counter() - t0) / rounds * 1e3
+    best = min(tried, key=tried.get)
+    return [pool[i] for i in best], tried
+
